@@ -1,0 +1,151 @@
+"""Pins for the oracle's variance-optimal level search (Sec. 3)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+
+
+def total_variance(points, endpoints):
+    """sum_x (b - x)(x - a) for x in [a, b], straight from the definition of err(x, I)."""
+    e = np.asarray(endpoints, np.float64)
+    tot = 0.0
+    for x in points:
+        k = np.searchsorted(e, x, side="right") - 1
+        k = min(max(k, 0), len(e) - 2)
+        tot += (e[k + 1] - x) * (x - e[k])
+    return tot
+
+
+def brute_force(points, cand, s):
+    """Best total variance over every choice of s-1 interior endpoints among cand[1:-1]."""
+    best, arg = np.inf, None
+    M = len(cand) - 1
+    for interior in itertools.combinations(range(1, M), s - 1):
+        idx = (0,) + interior + (M,)
+        v = total_variance(points, [cand[i] for i in idx])
+        if v < best - 1e-15:
+            best, arg = v, idx
+    return best, arg
+
+
+def test_interval_cost_from_moments_equals_definition():
+    rng = np.random.default_rng(0)
+    t = np.sort(rng.uniform(0, 1, 300))
+    M = 10
+    cand = np.arange(M + 1) / M
+    mom = oracle.bin_moments(t, cand)
+    assert mom[:, 0].sum() == 300
+    # one interval [0,1]: T(1, M)
+    tot, idx = oracle.dp_levels(mom, cand, 1)
+    assert list(idx) == [0, M]
+    assert np.isclose(tot, total_variance(t, [0.0, 1.0]), rtol=1e-12)
+
+
+@pytest.mark.parametrize("M,s,seed", [(8, 2, 0), (12, 3, 1), (16, 4, 2), (16, 5, 3), (10, 7, 4)])
+def test_dp_equals_brute_force_on_candidate_grid(M, s, seed):
+    rng = np.random.default_rng(seed)
+    # skewed data, so the optimum is far from uniform
+    t = np.clip(rng.beta(0.6, 3.0, size=200), 0, 1)
+    cand = np.arange(M + 1) / M
+    mom = oracle.bin_moments(t, cand)
+    tot, idx = oracle.dp_levels(mom, cand, s)
+    bf, arg = brute_force(t, cand, s)
+    assert np.isclose(tot, bf, rtol=1e-10, atol=1e-12)
+    assert idx[0] == 0 and idx[-1] == M and np.all(np.diff(idx) > 0)
+    assert np.isclose(total_variance(t, cand[idx]), tot, rtol=1e-10, atol=1e-12)
+
+
+def test_exact_dp_with_data_points_as_candidates():
+    """Lemma 3: an optimal partition has its endpoints at data points (or 0, 1).  The DP on
+    candidates = data points must therefore be as good as a fine brute force over an
+    independent dense grid of endpoints."""
+    rng = np.random.default_rng(5)
+    t = np.sort(np.round(rng.beta(2, 5, size=10), 3))
+    t = np.unique(t)
+    cand = np.concatenate([[0.0], t[(t > 0) & (t < 1)], [1.0]])
+    mom = oracle.bin_moments(t, cand)
+    s = 3
+    tot, idx = oracle.dp_levels(mom, cand, s)
+    bf, _ = brute_force(t, cand, s)
+    assert np.isclose(tot, bf, rtol=1e-10, atol=1e-13)
+    fine = np.arange(0, 1001) / 1000.0           # contains every data point (3 decimals)
+    best = np.inf
+    for a, b in itertools.combinations(range(1, 1000, 7), 2):
+        best = min(best, total_variance(t, [0.0, fine[a], fine[b], 1.0]))
+    assert tot <= best + 1e-12
+
+
+def test_monotone_in_levels_and_refinement_and_beats_uniform():
+    rng = np.random.default_rng(6)
+    t = np.clip(rng.lognormal(-2.0, 1.0, size=2000), 0, 1)
+    M = 63                                       # divisible by 2^b - 1 for b = 1, 2, 3
+    cand = np.arange(M + 1) / M
+    mom = oracle.bin_moments(t, cand)
+    prev = np.inf
+    for bits in (1, 2, 3):
+        s = (1 << bits) - 1
+        tot, idx = oracle.dp_levels(mom, cand, s)
+        assert tot <= prev + 1e-12
+        prev = tot
+        uniform = np.arange(s + 1) / s           # a subset of the candidates
+        assert tot <= total_variance(t, uniform) + 1e-10
+    # the skew makes the gain large (Sec. 5.2: optimal levels save bits)
+    assert prev < 0.7 * total_variance(t, np.arange(8) / 7)
+    # refining the candidate grid cannot hurt
+    cand2 = np.arange(2 * M + 1) / (2 * M)
+    tot2, _ = oracle.dp_levels(oracle.bin_moments(t, cand2), cand2, 7)
+    assert tot2 <= prev + 1e-12
+
+
+def test_discretisation_error_shrinks_with_M():
+    """Theorem 2: the gap to the optimum decays like 1/(M k); here against the exact DP."""
+    rng = np.random.default_rng(7)
+    t = np.sort(rng.uniform(0, 1, 120))
+    cand_exact = np.concatenate([[0.0], t, [1.0]])
+    s = 3
+    opt, _ = oracle.dp_levels(oracle.bin_moments(t, cand_exact), cand_exact, s)
+    gaps = []
+    for M in (8, 32, 128):
+        cand = np.arange(M + 1) / M
+        tot, _ = oracle.dp_levels(oracle.bin_moments(t, cand), cand, s)
+        assert tot >= opt - 1e-12
+        gaps.append((tot - opt) / len(t))
+        # a = 1 (equal small intervals); b, c from the data
+        bmax = oracle.bin_moments(t, cand)[:, 0].max() * M / len(t)
+        c = 1.0 * s          # a large interval crosses at most M = c M / k small ones
+        assert gaps[-1] <= bmax * s / (4 * M ** 3) + bmax * c ** 2 / (M * s) + 1e-12
+    assert gaps[2] < gaps[0]
+
+
+def test_hist_moments_and_levels_optimal_end_to_end():
+    rng = np.random.default_rng(8)
+    n, d, M, bits = 3000, 3, 64, 2
+    A = np.exp(rng.standard_normal((n, d))).astype(np.float32)
+    A[:, 2] = 0.25                               # a flat column
+    lo, hi = oracle.col_range(A)
+    hist = oracle.hist_moments(A, lo, hi, M)
+    assert np.all(hist[:, :, 0].sum(axis=1) == n)
+    t0 = (A[:, 0].astype(np.float64) - lo[0]) / (float(hi[0]) - float(lo[0]))
+    ref = oracle.bin_moments(t0, np.arange(M + 1) / M)
+    assert np.allclose(hist[0], ref, rtol=1e-12, atol=1e-12)
+    L, G, mv = oracle.levels_optimal(hist, lo, hi, bits)
+    assert np.array_equal(L[:, 0], lo) and np.array_equal(L[:, -1], hi)
+    assert np.all(G[:, 0] == 0) and np.all(G[:, -1] == M)
+    assert np.all(np.diff(G[:2].astype(int), axis=1) > 0)
+    assert np.all(L[2] == 0.25)
+    for j in range(2):
+        expect = lo[j].astype(np.float64) + (float(hi[j]) - float(lo[j])) * G[j] / M
+        assert np.allclose(L[j], expect, rtol=1e-7)
+    # reported objective is the mean over features of total/N in normalised units
+    per = []
+    for j in range(3):
+        tot, _ = oracle.dp_levels(hist[j], np.arange(M + 1) / M, 3)
+        per.append(tot / n)
+    assert np.isclose(mv, np.mean(per), rtol=1e-12)
+    # optimal levels give a lower quantisation variance than uniform levels on this data
+    tj = t0
+    var_opt = total_variance(tj, G[0] / M)
+    var_uni = total_variance(tj, np.arange(4) / 3)
+    assert var_opt < 0.6 * var_uni
