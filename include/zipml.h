@@ -1,0 +1,157 @@
+/*
+ * libzipml -- double-sampled low-precision minibatch SGD for least squares on AMD MI355X (gfx950).
+ *
+ * The method is that of "ZipML: Training Models with End-to-End Low Precision"
+ * (arXiv 1611.05402): every sample row is stochastically quantised twice, independently, to
+ * b-bit per-feature levels (Sec. 2.1, Supp. A.3), and each minibatch step uses the unbiased
+ * double-sampled gradient  g = mean_i Q1(a_i) (Q2(a_i)^T x - b_i)  (Sec. 2.2, eq. (5)), optionally
+ * with the model and the gradient stochastically quantised as well (Supp. C-E).
+ *
+ * General conventions
+ *   - Plain C ABI.  Pointers named *_dev are DEVICE pointers owned by the caller; the library never
+ *     allocates or frees device memory and keeps no pointer after a call returns.  Pointers named
+ *     *_host are host pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work is
+ *     enqueued on it.  Calls that return a host value (zipml_loss, zipml_sgd_status, the OPTIMAL
+ *     mode of zipml_levels) synchronise that stream; every other call is asynchronous.
+ *   - Every call returns ZIPML_OK (0) or a negative error code; nothing aborts or throws across the
+ *     boundary.  Argument errors are detected before any work is enqueued.
+ *   - A is row-major fp32 with leading dimension lda >= d.  Level tables are [d][2^bits] fp32,
+ *     non-decreasing along the second axis.  All device pointers must be 16-byte aligned.
+ *   - The packed layout of the quantised copies is private to the library (copy 1 is stored
+ *     feature-major for the gradient pass, copy 2 sample-major for the dot-product pass, both in
+ *     blocks of 32 features); zipml_unpack_codes is its only definition.
+ *   - Random numbers: Philox4x32-10, key = seed, counter = (row, feature / 4, epoch * 256 + stream),
+ *     output word feature % 4, the top 24 bits as a uniform in [0,1).  Streams 1, 2 are the two
+ *     sample quantisations (row = sample index), 3 and 4 the model and gradient quantisations
+ *     (row = step index within the epoch).  epoch must be < 2^24.
+ */
+#ifndef ZIPML_H
+#define ZIPML_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------------------------- */
+#define ZIPML_OK            0
+#define ZIPML_EINVAL       -1   /* bad argument value (sizes, bits, batch, NULL pointer)          */
+#define ZIPML_EALIGN       -2   /* a device pointer is not 16-byte aligned                        */
+#define ZIPML_ERANGE       -3   /* integer dot product could overflow int32 for these sizes       */
+#define ZIPML_EWORKSPACE   -4   /* workspace missing or smaller than zipml_workspace_bytes()      */
+#define ZIPML_ELAUNCH      -5   /* the HIP runtime refused a launch or copy                       */
+#define ZIPML_EUNSUPPORTED -6   /* valid request that this build does not implement               */
+#define ZIPML_ETIMEOUT     -7   /* a grid-wide wait inside the epoch kernel gave up               */
+
+/* ---- modes and flags ---------------------------------------------------------------------- */
+#define ZIPML_UNIFORM 0          /* 2^bits evenly spaced levels on [lo_j, hi_j]    (Sec. 2.1)     */
+#define ZIPML_OPTIMAL 1          /* variance-optimal levels by dynamic programming (Sec. 3)       */
+
+#define ZIPML_RANGE_GIVEN 1      /* zipml_levels: lo_dev / hi_dev are inputs                      */
+#define ZIPML_SYMMETRIC   2      /* zipml_levels: range [-M_j, M_j], M_j = max(|min|, |max|)
+                                    (Supp. A.3 "Column Scaling")                                  */
+
+#define ZIPML_SGD_STEPWISE 1     /* zipml_sgd_epoch: two launches per step instead of one
+                                    persistent launch per epoch (same arithmetic)                 */
+#define ZIPML_SGD_AVERAGED 2     /* zipml_sgd_epoch: the averaged estimator
+                                    1/2 [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)]  (Supp. B.2, footnote) */
+
+const char *zipml_strerror(int code);
+
+/* Bytes of ONE packed copy of an n x d matrix at `bits` bits per value, padding included
+ * (n and d are rounded up to multiples of 32).  0 if the arguments are invalid. */
+size_t zipml_packed_bytes(int64_t n, int64_t d, int bits);
+
+/* Bytes of device workspace that zipml_levels, zipml_sgd_epoch, zipml_debug_step and zipml_loss
+ * need for a problem of this shape (one buffer serves all of them, one call at a time).
+ * n_candidates may be 0 if ZIPML_OPTIMAL is never used. */
+size_t zipml_workspace_bytes(int64_t n, int64_t d, int bits, int64_t batch, int n_candidates);
+
+/* Per-feature quantisation levels.
+ *   Sec. 2.1 (levels partition the scaled range), Supp. A.3 "Column Scaling" (one range per
+ *   feature from the column min/max), Sec. 3.1-3.2 (variance-optimal levels: one scan of the data
+ *   into n_candidates equal bins per feature, then the dynamic program T(k,m) on the bin edges).
+ * Unless ZIPML_RANGE_GIVEN, lo_dev[d] / hi_dev[d] are written with the column ranges.
+ * levels_dev[d][2^bits] is written.  grid_idx_dev[d][2^bits] (optional, may be NULL) receives the
+ * integer grid position of every level: c for UNIFORM, the chosen bin edge for OPTIMAL, so that
+ * level = lo_j + (hi_j - lo_j) * grid_idx / grid_max with grid_max = 2^bits - 1 or n_candidates.
+ * mean_variance_host (optional, OPTIMAL only) receives the objective of eq. (6) averaged over
+ * features.  UNIFORM is asynchronous; OPTIMAL copies the bin moments to the host, runs the dynamic
+ * program on the host cores and copies the levels back, so it synchronises the stream.
+ * bits in 1..8; OPTIMAL needs 2^bits - 1 <= n_candidates <= 4096. */
+int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t d, int64_t lda, int bits,
+                 int mode, int flags, int n_candidates, float *lo_dev, float *hi_dev,
+                 float *levels_dev, uint16_t *grid_idx_dev, double *mean_variance_host,
+                 void *workspace_dev, size_t workspace_bytes);
+
+/* Two independent stochastic quantisations of rows [row0, row0 + n_rows) of an n_total x d matrix
+ * (Sec. 2.1: value v between neighbouring levels l <= v <= u goes to u with probability
+ * (v - l)/(u - l), evaluated in fp32; Sec. 2.2: two independent copies).  A_dev points at the
+ * first of the n_rows rows.  Values outside the level range are clamped to it.  packed1_dev and
+ * packed2_dev each hold zipml_packed_bytes(n_total, d, bits) bytes; calls for disjoint row ranges
+ * fill disjoint parts, so a large matrix can be quantised chunk by chunk.  row0 must be a multiple
+ * of 32, and so must n_rows unless the chunk ends at n_total. */
+int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, int64_t d, int64_t lda,
+                   int64_t row0, int64_t n_total, const float *levels_dev, int bits, uint64_t seed,
+                   uint32_t epoch, void *packed1_dev, void *packed2_dev);
+
+/* One epoch of double-sampled minibatch SGD on F(x) = 1/(2n) sum_i (a_i^T x - b_i)^2
+ * (Sec. 2 and eq. (5); the minibatch gradient is the mean over `batch` consecutive samples; the
+ * n / batch steps run in storage order).  x_dev[d] is the fp32 master model, updated in place:
+ * x <- x - lr * g every step (Supp. E: the update is in full precision).
+ *   model_bits = grad_bits = 0: full-precision model and gradient (fp32 arithmetic).
+ *   model_bits in 2..8: the model is stochastically quantised each step with row scaling
+ *     (Supp. A.3 eq. (quant2), Supp. C), s = 2^(model_bits-1) - 1 magnitude intervals, and the dot
+ *     product becomes an exact integer sum of grid_idx * model code; this needs grid_idx_dev and a
+ *     level grid shared by all features: level value = grid_lo + grid_step * grid_idx.
+ *   grad_bits in 2..8 (needs model_bits > 0): the mean gradient is quantised the same way before
+ *     the update (Supp. D, E).
+ * grid_max is the largest grid index (2^bits - 1 for UNIFORM levels, n_candidates for OPTIMAL);
+ * ZIPML_ERANGE if grid_max * s * d could exceed int32.
+ * batch must divide n and be 4, 8, 16 or a multiple of 32.
+ * The call is asynchronous; a failed grid-wide wait is reported by zipml_sgd_status. */
+int zipml_sgd_epoch(void *stream, const void *packed1_dev, const void *packed2_dev,
+                    const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
+                    float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d,
+                    int bits, float *x_dev, int64_t batch, float lr, int grad_bits, int model_bits,
+                    uint64_t seed, uint32_t epoch, int flags, void *workspace_dev,
+                    size_t workspace_bytes);
+
+/* Waits for the stream and returns the status word the last zipml_sgd_epoch / zipml_debug_step
+ * left in this workspace: ZIPML_OK or ZIPML_ETIMEOUT. */
+int zipml_sgd_status(void *stream, const void *workspace_dev, size_t workspace_bytes);
+
+/* Loss F(x) = 1/(2n) sum_i (a_i^T x - b_i)^2 (Sec. 1 eq. (1) with the square loss).  With A_dev
+ * the exact fp32 rows are used; with A_dev == NULL the rows are decoded from one packed copy
+ * (`copy` = 1 or 2) and levels_dev.  Dot products in fp32, squares and their sum in fp64.
+ * Synchronises the stream and writes *loss_host. */
+int zipml_loss(void *stream, const float *A_dev, int64_t lda, const void *packed_dev, int copy,
+               const float *levels_dev, int bits, const float *b_dev, const float *x_dev,
+               int64_t n, int64_t d, double *loss_host, void *workspace_dev,
+               size_t workspace_bytes);
+
+/* ---- parity / debug exports (not on the timed path) --------------------------------------- */
+
+/* Canonical codes of one packed copy (`copy` = 1 or 2): codes_dev[n][d], row-major uint8. */
+int zipml_unpack_codes(void *stream, const void *packed_dev, int copy, int64_t n, int64_t d,
+                       int bits, uint8_t *codes_dev);
+
+/* Runs the single step `step` of the epoch from the model in x_dev (updated in place) and exposes
+ * its intermediates; any output pointer may be NULL.  model_codes_dev[d] and grad_codes_dev[d] are
+ * the signed integer codes of Q3 / Q4, acc_dev[batch] the int32 dot products (integer mode only),
+ * r_dev[batch] the residuals Q2(a_i)^T x - b_i, g_dev[d] the mean gradient before Q4. */
+int zipml_debug_step(void *stream, const void *packed1_dev, const void *packed2_dev,
+                     const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
+                     float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d,
+                     int bits, float *x_dev, int64_t batch, float lr, int grad_bits,
+                     int model_bits, uint64_t seed, uint32_t epoch, int64_t step, int flags,
+                     int32_t *model_codes_dev, int32_t *acc_dev, float *r_dev, float *g_dev,
+                     int32_t *grad_codes_dev, void *workspace_dev, size_t workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZIPML_H */

@@ -1,0 +1,62 @@
+"""Builds libzipml.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OUT = os.path.join(HERE, "libzipml.so")
+SOURCES = ["zipml_quantize.hip", "zipml_sgd.hip", "zipml_loss.hip", "zipml_levels.hip"]
+HEADERS = ["zipml_device.h", "zipml_host.h"]
+
+# -ffp-contract=off: fp32/fp64 decision sequences must stay single IEEE operations (fused
+#   multiply-adds are written explicitly where they are wanted).
+# -munsafe-fp-atomics: hardware float/double atomic adds instead of compare-and-swap loops.
+# -packed-fp32-ops off: packed fp32 instructions are not to be generated on the test machines.
+FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off",
+         "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-function"]
+
+
+def _stale(target: str, deps) -> bool:
+    if not os.path.exists(target):
+        return True
+    t = os.path.getmtime(target)
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def build(force: bool = False, verbose: bool = False) -> str:
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    hdrs = [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(HERE, "..", "include", "zipml.h")]
+    jobs = []
+    for src in SOURCES:
+        s = os.path.join(CSRC, src)
+        o = os.path.join(objdir, src.replace(".hip", ".o"))
+        if force or _stale(o, [s] + hdrs):
+            jobs.append(["hipcc", *FLAGS, "-c", s, "-o", o])
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            sys.stderr.write(r.stdout + r.stderr)
+            raise RuntimeError("hipcc failed: " + " ".join(cmd))
+        if verbose and r.stderr.strip():
+            lines = [l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l]
+            sys.stderr.write("\n".join(lines) + "\n")
+
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        list(ex.map(run, jobs))
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    if force or jobs or _stale(OUT, objs):
+        run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT, "-lpthread"])
+    return OUT
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv, verbose=True))

@@ -1,0 +1,118 @@
+// Device-side building blocks shared by the libzipml kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace zipml {
+
+constexpr int kWave = 64;
+constexpr int kGroup = 32;   // features (copy 2) or samples (copy 1) per packed unit
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  Key = seed; counter = (row lo, row hi, col/4,
+// epoch*256 + stream).  Word col%4 of the block is the draw of that column.
+// ---------------------------------------------------------------------------------------------
+struct Philox4 {
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Philox4{{c0, c1, c2, c3}};
+}
+
+__device__ __forceinline__ Philox4 philox_block(uint64_t seed, uint32_t epoch, uint64_t row,
+                                                uint32_t col4, uint32_t stream)
+{
+    return philox4x32_10((uint32_t)row, (uint32_t)(row >> 32), col4, (epoch << 8) | stream,
+                         (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+// Top 24 bits as a uniform in [0, 1); exact in fp32.
+__device__ __forceinline__ float u24(uint32_t word)
+{
+    return (float)(word >> 8) * (1.0f / 16777216.0f);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Packed units: 32 codes of BITS bits each, little-endian bit string in BITS dwords.
+// ---------------------------------------------------------------------------------------------
+template <int BITS>
+__device__ __forceinline__ uint32_t unit_code(const uint32_t (&w)[BITS], int k)
+{
+    const int bit = k * BITS, wi = bit >> 5, sh = bit & 31;
+    uint32_t v = w[wi] >> sh;
+    if (sh + BITS > 32) v |= w[wi + 1] << (32 - sh);   // the branch folds: k is a constant after unrolling
+    return v & ((1u << BITS) - 1u);
+}
+
+template <int BITS>
+__device__ __forceinline__ void unit_set(uint32_t (&w)[BITS], int k, uint32_t code)
+{
+    const int bit = k * BITS, wi = bit >> 5, sh = bit & 31;
+    w[wi] |= code << sh;
+    if (sh + BITS > 32) w[wi + 1] |= code >> (32 - sh);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Device-scope (all XCDs) access to data that other workgroups write during the same kernel.
+// Each XCD has its own L2, so such data must go through device-coherent accesses.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ T load_dev(const T *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void store_dev(T *p, T v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void add_dev(T *p, T v)
+{
+    (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void release_dev()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+}
+
+// ---------------------------------------------------------------------------------------------
+// Wave and block reductions.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v)
+{
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Sum over the block; every thread gets the result.  scratch: >= blockDim/64 + 1 elements of T.
+template <typename T>
+__device__ __forceinline__ T block_sum(T v, T *scratch)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int nw = (blockDim.x + kWave - 1) >> 6;
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    T tot = 0;
+    for (int w = 0; w < nw; ++w) tot += scratch[w];
+    return tot;
+}
+
+}  // namespace zipml

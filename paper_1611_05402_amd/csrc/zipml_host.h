@@ -1,0 +1,47 @@
+// Host-side helpers shared by the libzipml entry points.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/zipml.h"
+
+namespace zipml {
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool valid_bits(int bits) { return bits >= 1 && bits <= 8; }
+
+// Packed layout (private).  n and d are padded to multiples of 32.
+//   copy 2 (dot pass):      [feature group g][sample i][bits dwords]          32 features per unit
+//   copy 1 (gradient pass): [feature group g][sample group][feature in g][bits dwords]
+//                                                                            32 samples per unit
+struct Layout {
+    int64_t n, d, n_pad, d_pad;
+    int64_t d32;    // feature groups
+    int64_t n32;    // sample groups
+    int bits;
+    size_t bytes() const { return (size_t)n_pad * (size_t)d_pad * (size_t)bits / 8; }
+};
+inline Layout make_layout(int64_t n, int64_t d, int bits)
+{
+    Layout L;
+    L.n = n; L.d = d; L.bits = bits;
+    L.n_pad = round_up(n, 32); L.d_pad = round_up(d, 32);
+    L.d32 = L.d_pad / 32; L.n32 = L.n_pad / 32;
+    return L;
+}
+
+// Workspace carving (all offsets 256-byte aligned).
+struct Workspace {
+    static constexpr size_t kStatus = 0;          // int32 status word + counters   (4 KiB)
+    static constexpr size_t kSync = 4096;         // grid barrier counters          (4 KiB)
+    static constexpr size_t kNorm = 8192;         // norm exchange: 2 x 3 x 512 doubles (24 KiB)
+    static constexpr size_t kAcc = 8192 + 24576;  // 3 reduction buffers of batch_pad + 64 words
+    static size_t acc_words(int64_t batch) { return (size_t)round_up(batch + 64, 64); }
+    static size_t sgd_bytes(int64_t batch) { return kAcc + 3 * acc_words(batch) * 4; }
+};
+
+inline int hip_check(hipError_t e) { return e == hipSuccess ? ZIPML_OK : ZIPML_ELAUNCH; }
+
+}  // namespace zipml

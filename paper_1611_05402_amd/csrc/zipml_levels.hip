@@ -1,0 +1,306 @@
+// zipml_levels: per-feature ranges and quantisation levels.
+//
+// Supp. A.3 "Column Scaling": one range per feature from the column minimum and maximum.
+// Sec. 2.1: uniform levels.  Sec. 3.1-3.2: variance-optimal levels -- one scan of the data into
+// M equal bins per feature (count, sum, sum of squares of the normalised values), then the dynamic
+// program T(k,m) = min_j T(k-1,j) + V(j,m) over the bin edges, run on the host cores.
+#include "zipml_device.h"
+#include "zipml_host.h"
+
+#include <algorithm>
+#include <atomic>
+#include <limits>
+#include <thread>
+#include <vector>
+
+namespace zipml {
+
+// Order-preserving map float -> uint32 so that min/max can use integer atomics.
+__device__ __forceinline__ uint32_t f2key(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key2f(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+__global__ void k_range_init(uint32_t *kmin, uint32_t *kmax, int64_t d)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < d) { kmin[j] = 0xFFFFFFFFu; kmax[j] = 0u; }
+}
+
+// One thread per feature (consecutive lanes read consecutive floats of a row), a slab of rows per
+// blockIdx.y.
+__global__ __launch_bounds__(256) void k_range_scan(const float *__restrict__ A, int64_t n,
+                                                    int64_t d, int64_t lda, int64_t rows_per_slab,
+                                                    uint32_t *kmin, uint32_t *kmax)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d) return;
+    const int64_t i0 = (int64_t)blockIdx.y * rows_per_slab;
+    const int64_t i1 = i0 + rows_per_slab < n ? i0 + rows_per_slab : n;
+    if (i0 >= i1) return;
+    float mn = A[i0 * lda + j], mx = mn;
+    for (int64_t i = i0 + 1; i < i1; ++i) {
+        const float v = A[i * lda + j];
+        mn = v < mn ? v : mn;
+        mx = v > mx ? v : mx;
+    }
+    atomicMin(kmin + j, f2key(mn));
+    atomicMax(kmax + j, f2key(mx));
+}
+
+__global__ void k_range_final(const uint32_t *kmin, const uint32_t *kmax, int64_t d, int symmetric,
+                              float *lo, float *hi)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d) return;
+    float mn = key2f(kmin[j]), mx = key2f(kmax[j]);
+    if (symmetric) {
+        const float m = fabsf(mn) > fabsf(mx) ? fabsf(mn) : fabsf(mx);
+        mn = -m;
+        mx = m;
+    }
+    lo[j] = mn;
+    hi[j] = mx;
+}
+
+// L[j][c] = fp32( lo + c (hi - lo) / (K - 1) ), evaluated in fp64; grid index = c.
+__global__ void k_levels_uniform(const float *__restrict__ lo, const float *__restrict__ hi,
+                                 int64_t d, int K, float *__restrict__ levels,
+                                 uint16_t *__restrict__ grid)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= d * K) return;
+    const int64_t j = e / K;
+    const int c = (int)(e % K);
+    const double l = (double)lo[j], w = (double)hi[j] - (double)lo[j];
+    levels[e] = (float)(l + ((double)c * w) / (double)(K - 1));
+    if (grid) grid[e] = (uint16_t)c;
+}
+
+__global__ void k_zero_f64(double *p, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.0;
+}
+
+// Per-bin moments of the normalised values; hist is [d][M][3] fp64 (count, sum t, sum t^2).
+__global__ __launch_bounds__(256) void k_hist(const float *__restrict__ A, int64_t n, int64_t d,
+                                              int64_t lda, int64_t rows_per_slab,
+                                              const float *__restrict__ lo,
+                                              const float *__restrict__ hi, int M,
+                                              double *__restrict__ hist)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d) return;
+    const int64_t i0 = (int64_t)blockIdx.y * rows_per_slab;
+    const int64_t i1 = i0 + rows_per_slab < n ? i0 + rows_per_slab : n;
+    const double l = (double)lo[j], w = (double)hi[j] - (double)lo[j];
+    double *h = hist + (size_t)j * M * 3;
+    for (int64_t i = i0; i < i1; ++i) {
+        double t = 0.0;
+        if (w > 0.0) {
+            t = ((double)A[i * lda + j] - l) / w;
+            t = t < 0.0 ? 0.0 : t;
+            t = t > 1.0 ? 1.0 : t;
+        }
+        int m = (int)(t * (double)M);
+        if (m > M - 1) m = M - 1;
+        unsafeAtomicAdd(h + m * 3 + 0, 1.0);
+        unsafeAtomicAdd(h + m * 3 + 1, t);
+        unsafeAtomicAdd(h + m * 3 + 2, t * t);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host dynamic program for one feature: s intervals over the M+1 bin edges m/M.
+// Returns the total variance; idx[0..s] are the chosen edges.  Ties: smallest j.
+// ---------------------------------------------------------------------------------------------
+static double dp_one_feature(const double *mom, int M, int s, std::vector<double> &C,
+                             std::vector<double> &S1, std::vector<double> &S2,
+                             std::vector<double> &prev, std::vector<double> &cur,
+                             std::vector<uint16_t> &arg, int *idx)
+{
+    const size_t W = (size_t)M + 1;
+    C[0] = S1[0] = S2[0] = 0.0;
+    for (int m = 0; m < M; ++m) {
+        C[m + 1] = C[m] + mom[m * 3 + 0];
+        S1[m + 1] = S1[m] + mom[m * 3 + 1];
+        S2[m + 1] = S2[m] + mom[m * 3 + 2];
+    }
+    auto edge = [&](int m) { return (double)m / (double)M; };   // M need not be a power of two
+    auto V = [&](int j, int m) {
+        const double dj = edge(j), dm = edge(m);
+        return -(S2[m] - S2[j]) + (dj + dm) * (S1[m] - S1[j]) - dj * dm * (C[m] - C[j]);
+    };
+    const double INF = std::numeric_limits<double>::infinity();
+    std::fill(prev.begin(), prev.end(), INF);
+    for (int m = 1; m <= M; ++m) { prev[m] = V(0, m); arg[1 * W + m] = 0; }
+    for (int k = 2; k <= s; ++k) {
+        std::fill(cur.begin(), cur.end(), INF);
+        for (int m = k; m <= M; ++m) {
+            double best = INF;
+            int bj = k - 1;
+            for (int j = k - 1; j <= m - 1; ++j) {
+                const double v = prev[j] + V(j, m);
+                if (v < best) { best = v; bj = j; }
+            }
+            cur[m] = best;
+            arg[(size_t)k * W + m] = (uint16_t)bj;
+        }
+        std::swap(prev, cur);
+    }
+    const double total = prev[M];
+    int m = M;
+    for (int k = s; k >= 1; --k) { idx[k] = m; m = arg[(size_t)k * W + m]; }
+    idx[0] = 0;
+    return total;
+}
+
+static size_t levels_workspace_bytes(int64_t d, int n_candidates)
+{
+    size_t keys = (size_t)round_up(d * 8, 256);
+    size_t hist = (size_t)d * (size_t)n_candidates * 3 * sizeof(double);
+    return keys + hist;
+}
+
+}  // namespace zipml
+
+using namespace zipml;
+
+extern "C" size_t zipml_workspace_bytes(int64_t n, int64_t d, int bits, int64_t batch,
+                                        int n_candidates)
+{
+    if (n <= 0 || d <= 0 || !valid_bits(bits) || batch <= 0 || n_candidates < 0) return 0;
+    size_t sgd = Workspace::sgd_bytes(batch) + (size_t)round_up(d, 32) * 4;
+    size_t lev = levels_workspace_bytes(d, n_candidates);
+    size_t loss = (2048 + 1) * sizeof(double);
+    size_t need = std::max(sgd, std::max(lev, loss));
+    return (size_t)round_up((int64_t)need, 256);
+}
+
+extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t d, int64_t lda,
+                            int bits, int mode, int flags, int n_candidates, float *lo_dev,
+                            float *hi_dev, float *levels_dev, uint16_t *grid_idx_dev,
+                            double *mean_variance_host, void *workspace_dev,
+                            size_t workspace_bytes)
+{
+    if (!lo_dev || !hi_dev || !levels_dev || d <= 0 || !valid_bits(bits)) return ZIPML_EINVAL;
+    if (mode != ZIPML_UNIFORM && mode != ZIPML_OPTIMAL) return ZIPML_EINVAL;
+    if (flags & ~(ZIPML_RANGE_GIVEN | ZIPML_SYMMETRIC)) return ZIPML_EINVAL;
+    const bool need_data = !(flags & ZIPML_RANGE_GIVEN) || mode == ZIPML_OPTIMAL;
+    if (need_data && (!A_dev || n <= 0 || lda < d)) return ZIPML_EINVAL;
+    const int K = 1 << bits;
+    if (mode == ZIPML_OPTIMAL && (n_candidates < K - 1 || n_candidates > 4096)) return ZIPML_EINVAL;
+    if (!aligned16(lo_dev) || !aligned16(hi_dev) || !aligned16(levels_dev) ||
+        (grid_idx_dev && !aligned16(grid_idx_dev)) || (A_dev && (reinterpret_cast<uintptr_t>(A_dev) & 3u)))
+        return ZIPML_EALIGN;
+    const size_t need = levels_workspace_bytes(d, mode == ZIPML_OPTIMAL ? n_candidates : 0);
+    if (need_data && (!workspace_dev || workspace_bytes < need || !aligned16(workspace_dev)))
+        return ZIPML_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const unsigned cb = (unsigned)((d + 255) / 256);
+    // rows are split into slabs so that the scan fills the device
+    int64_t slabs = std::max<int64_t>(1, std::min<int64_t>(n / 64 + 1, 4096 / cb + 1));
+    const int64_t rows_per_slab = n > 0 ? (n + slabs - 1) / slabs : 1;
+    slabs = n > 0 ? (n + rows_per_slab - 1) / rows_per_slab : 1;
+
+    if (!(flags & ZIPML_RANGE_GIVEN)) {
+        uint32_t *kmin = (uint32_t *)workspace_dev, *kmax = kmin + d;
+        hipLaunchKernelGGL(k_range_init, dim3(cb), dim3(256), 0, s, kmin, kmax, d);
+        hipLaunchKernelGGL(k_range_scan, dim3(cb, (unsigned)slabs), dim3(256), 0, s, A_dev, n, d, lda,
+                           rows_per_slab, kmin, kmax);
+        hipLaunchKernelGGL(k_range_final, dim3(cb), dim3(256), 0, s, kmin, kmax, d,
+                           (flags & ZIPML_SYMMETRIC) ? 1 : 0, lo_dev, hi_dev);
+        if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+    }
+    if (mode == ZIPML_UNIFORM) {
+        const int64_t total = d * K;
+        hipLaunchKernelGGL(k_levels_uniform, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           lo_dev, hi_dev, d, K, levels_dev, grid_idx_dev);
+        return hip_check(hipGetLastError());
+    }
+
+    // ---- OPTIMAL: bin moments on the device, dynamic program on the host
+    const int M = n_candidates, sI = K - 1;
+    double *hist_dev = (double *)((unsigned char *)workspace_dev + round_up(d * 8, 256));
+    const int64_t hcount = d * (int64_t)M * 3;
+    hipLaunchKernelGGL(k_zero_f64, dim3((unsigned)((hcount + 255) / 256)), dim3(256), 0, s, hist_dev,
+                       hcount);
+    hipLaunchKernelGGL(k_hist, dim3(cb, (unsigned)slabs), dim3(256), 0, s, A_dev, n, d, lda,
+                       rows_per_slab, lo_dev, hi_dev, M, hist_dev);
+    if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+    std::vector<double> hist((size_t)hcount);
+    std::vector<float> lo((size_t)d), hi((size_t)d);
+    if (hipMemcpyAsync(hist.data(), hist_dev, sizeof(double) * (size_t)hcount, hipMemcpyDeviceToHost,
+                       s) != hipSuccess ||
+        hipMemcpyAsync(lo.data(), lo_dev, sizeof(float) * (size_t)d, hipMemcpyDeviceToHost, s) !=
+            hipSuccess ||
+        hipMemcpyAsync(hi.data(), hi_dev, sizeof(float) * (size_t)d, hipMemcpyDeviceToHost, s) !=
+            hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return ZIPML_ELAUNCH;
+
+    std::vector<float> levels((size_t)d * K);
+    std::vector<uint16_t> grid((size_t)d * K);
+    std::vector<double> per_feature((size_t)d, 0.0);
+    unsigned nthreads = std::max(1u, std::min(std::thread::hardware_concurrency(), 16u));
+    if ((int64_t)nthreads > d) nthreads = (unsigned)d;
+    std::atomic<int64_t> next{0};
+    auto worker = [&]() {
+        const size_t W = (size_t)M + 1;
+        std::vector<double> C(W), S1(W), S2(W), prev(W), cur(W);
+        std::vector<uint16_t> arg(W * ((size_t)sI + 1));
+        std::vector<int> idx((size_t)sI + 1);
+        for (;;) {
+            const int64_t j = next.fetch_add(1);
+            if (j >= d) break;
+            const double *mom = hist.data() + (size_t)j * M * 3;
+            const double total = dp_one_feature(mom, M, sI, C, S1, S2, prev, cur, arg, idx.data());
+            double cnt = 0.0;
+            for (int m = 0; m < M; ++m) cnt += mom[m * 3];
+            per_feature[(size_t)j] = cnt > 0.0 ? total / cnt : 0.0;
+            const double l = (double)lo[(size_t)j], w = (double)hi[(size_t)j] - l;
+            for (int c = 0; c < K; ++c) {
+                grid[(size_t)j * K + c] = (uint16_t)idx[c];
+                levels[(size_t)j * K + c] = (float)(l + (w * (double)idx[c]) / (double)M);
+            }
+        }
+    };
+    std::vector<std::thread> pool;
+    for (unsigned t = 1; t < nthreads; ++t) pool.emplace_back(worker);
+    worker();
+    for (auto &t : pool) t.join();
+    if (mean_variance_host) {
+        double mv = 0.0;
+        for (int64_t j = 0; j < d; ++j) mv += per_feature[(size_t)j];
+        *mean_variance_host = mv / (double)d;
+    }
+    if (hipMemcpyAsync(levels_dev, levels.data(), sizeof(float) * levels.size(),
+                       hipMemcpyHostToDevice, s) != hipSuccess)
+        return ZIPML_ELAUNCH;
+    if (grid_idx_dev && hipMemcpyAsync(grid_idx_dev, grid.data(), sizeof(uint16_t) * grid.size(),
+                                       hipMemcpyHostToDevice, s) != hipSuccess)
+        return ZIPML_ELAUNCH;
+    if (hipStreamSynchronize(s) != hipSuccess) return ZIPML_ELAUNCH;
+    return ZIPML_OK;
+}
+
+extern "C" const char *zipml_strerror(int code)
+{
+    switch (code) {
+        case ZIPML_OK: return "ok";
+        case ZIPML_EINVAL: return "invalid argument";
+        case ZIPML_EALIGN: return "device pointer not 16-byte aligned";
+        case ZIPML_ERANGE: return "integer dot product could overflow int32";
+        case ZIPML_EWORKSPACE: return "workspace missing or too small";
+        case ZIPML_ELAUNCH: return "HIP launch or copy failed";
+        case ZIPML_EUNSUPPORTED: return "not supported by this build";
+        case ZIPML_ETIMEOUT: return "grid-wide wait timed out";
+        default: return "unknown error";
+    }
+}

@@ -1,0 +1,228 @@
+// zipml_quantize / zipml_unpack_codes: fp32 rows -> two independent packed b-bit copies.
+//
+// Stochastic quantisation of Sec. 2.1 with per-feature levels (Supp. A.3 "Column Scaling") and the
+// two independent copies of Sec. 2.2.  One workgroup handles a tile of 32 samples x 128 features:
+// it reads the fp32 tile with coalesced 512-byte row segments, takes the rounding decision for both
+// copies (one Philox block per copy covers 4 neighbouring features), transposes the codes through
+// LDS and writes sample-major units for copy 2 and feature-major units for copy 1.
+#include "zipml_device.h"
+#include "zipml_host.h"
+
+namespace zipml {
+
+// Largest l <= K-2 with L[l] <= v (v already clamped to the level range) and the probability of
+// rounding up to L[l+1]: three correctly rounded fp32 operations.
+__device__ __forceinline__ int bracket(const float *__restrict__ L, int K, float v, float &frac)
+{
+    const float L0 = L[0], Lk = L[K - 1];
+    if (v < L0) v = L0;
+    if (v > Lk) v = Lk;
+    int l = 0;
+    for (int s = K >> 1; s >= 1; s >>= 1) {
+        const int c = l + s;
+        if (c <= K - 2 && L[c] <= v) l = c;
+    }
+    const float base = L[l];
+    const float w = L[l + 1] - base;
+    const float num = v - base;
+    frac = (w > 0.0f) ? __fdiv_rn(num, w) : 0.0f;
+    return l;
+}
+
+constexpr int kTileCols = 128;   // 4 feature groups
+constexpr int kLdsRow = 33;      // dwords per LDS row of 128 code bytes (+1: conflict-free columns)
+
+template <int BITS>
+__global__ __launch_bounds__(256) void k_quantize_pack(
+    const float *__restrict__ A, int64_t n_rows, int64_t d, int64_t lda, int64_t row0,
+    int64_t n_pad, int64_t n32, int64_t d32, const float *__restrict__ levels, uint64_t seed,
+    uint32_t epoch, uint32_t *__restrict__ p1, uint32_t *__restrict__ p2, int vec_ok)
+{
+    __shared__ uint32_t c1w[32 * kLdsRow];
+    __shared__ uint32_t c2w[32 * kLdsRow];
+    constexpr int K = 1 << BITS;
+    const int tid = threadIdx.x;
+    const int64_t rg_local = blockIdx.x;              // sample group inside this chunk
+    const int64_t col0 = (int64_t)blockIdx.y * kTileCols;
+
+    // ---- phase 1: decide both codes of every element of the tile
+    const int cq = tid & 31;
+    const int64_t col = col0 + 4 * cq;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int r = pass * 8 + (tid >> 5);
+        const int64_t i = rg_local * 32 + r;
+        uint32_t w1 = 0, w2 = 0;
+        if (i < n_rows && col < d) {
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            const float *src = A + i * lda + col;
+            if (vec_ok && col + 3 < d) {
+                const float4 q = *reinterpret_cast<const float4 *>(src);
+                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < d) v[e] = src[e];
+            }
+            const uint64_t row = (uint64_t)(row0 + i);
+            const Philox4 r1 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 1u);
+            const Philox4 r2 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 2u);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (col + e < d) {
+                    float frac;
+                    const int l = bracket(levels + (col + e) * K, K, v[e], frac);
+                    const uint32_t a = (uint32_t)l + (u24(r1.w[e]) < frac ? 1u : 0u);
+                    const uint32_t b = (uint32_t)l + (u24(r2.w[e]) < frac ? 1u : 0u);
+                    w1 |= a << (8 * e);
+                    w2 |= b << (8 * e);
+                }
+            }
+        }
+        c1w[r * kLdsRow + cq] = w1;
+        c2w[r * kLdsRow + cq] = w2;
+    }
+    __syncthreads();
+
+    // ---- phase 2: pack 32 codes per unit and store
+    const int64_t rg = row0 / 32 + rg_local;          // sample group in the whole matrix
+    if (tid < 128) {
+        // copy 2: one unit = sample r, feature group gq
+        const int r = tid & 31, gq = tid >> 5;
+        const int64_t g = col0 / 32 + gq;
+        if (g < d32) {
+            uint32_t unit[BITS];
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) unit[q] = 0;
+#pragma unroll
+            for (int k = 0; k < 32; ++k) {
+                const uint32_t w = c2w[r * kLdsRow + gq * 8 + (k >> 2)];
+                unit_set<BITS>(unit, k, (w >> (8 * (k & 3))) & 0xFFu);
+            }
+            uint32_t *dst = p2 + (g * n_pad + rg * 32 + r) * BITS;
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
+        }
+    } else {
+        // copy 1: one unit = feature c, the 32 samples of this group
+        const int c = tid - 128, gq = c >> 5, cin = c & 31;
+        const int64_t g = col0 / 32 + gq;
+        if (g < d32) {
+            uint32_t unit[BITS];
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) unit[q] = 0;
+#pragma unroll
+            for (int k = 0; k < 32; ++k) {
+                const uint32_t w = c1w[k * kLdsRow + (c >> 2)];
+                unit_set<BITS>(unit, k, (w >> (8 * (c & 3))) & 0xFFu);
+            }
+            uint32_t *dst = p1 + ((g * n32 + rg) * 32 + cin) * BITS;
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
+        }
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ packed, int copy,
+                                                int64_t n, int64_t d, int64_t n_pad, int64_t n32,
+                                                int64_t d32, uint8_t *__restrict__ codes)
+{
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // unit index
+    if (u >= d32 * n_pad) return;
+    uint32_t unit[BITS];
+#pragma unroll
+    for (int q = 0; q < BITS; ++q) unit[q] = packed[u * BITS + q];
+    if (copy == 2) {
+        const int64_t g = u / n_pad, i = u % n_pad;
+        if (i >= n) return;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int64_t j = g * 32 + k;
+            if (j < d) codes[i * d + j] = (uint8_t)unit_code<BITS>(unit, k);
+        }
+    } else {
+        const int64_t g = u / n_pad, rem = u % n_pad, rg = rem / 32, cin = rem % 32;
+        const int64_t j = g * 32 + cin;
+        if (j >= d) return;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int64_t i = rg * 32 + k;
+            if (i < n) codes[i * d + j] = (uint8_t)unit_code<BITS>(unit, k);
+        }
+    }
+}
+
+template <int BITS>
+static int launch_quantize(hipStream_t s, const float *A, int64_t n_rows, int64_t d, int64_t lda,
+                           int64_t row0, const Layout &lay, const float *levels, uint64_t seed,
+                           uint32_t epoch, uint32_t *p1, uint32_t *p2)
+{
+    const int vec_ok = (lda % 4 == 0) && aligned16(A);
+    dim3 grid((unsigned)((n_rows + 31) / 32), (unsigned)((lay.d32 + 3) / 4));
+    hipLaunchKernelGGL(k_quantize_pack<BITS>, grid, dim3(256), 0, s, A, n_rows, d, lda, row0,
+                       lay.n_pad, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok);
+    return hip_check(hipGetLastError());
+}
+
+template <int BITS>
+static int launch_unpack(hipStream_t s, const uint32_t *packed, int copy, const Layout &lay,
+                         uint8_t *codes)
+{
+    const int64_t units = lay.d32 * lay.n_pad;
+    hipLaunchKernelGGL(k_unpack<BITS>, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
+                       packed, copy, lay.n, lay.d, lay.n_pad, lay.n32, lay.d32, codes);
+    return hip_check(hipGetLastError());
+}
+
+}  // namespace zipml
+
+using namespace zipml;
+
+#define ZIPML_DISPATCH_BITS(bits, CALL)                                           \
+    switch (bits) {                                                               \
+        case 1: return CALL(1); case 2: return CALL(2); case 3: return CALL(3);   \
+        case 4: return CALL(4); case 5: return CALL(5); case 6: return CALL(6);   \
+        case 7: return CALL(7); case 8: return CALL(8);                           \
+        default: return ZIPML_EINVAL;                                             \
+    }
+
+extern "C" size_t zipml_packed_bytes(int64_t n, int64_t d, int bits)
+{
+    if (n <= 0 || d <= 0 || !valid_bits(bits)) return 0;
+    return make_layout(n, d, bits).bytes();
+}
+
+extern "C" int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, int64_t d,
+                              int64_t lda, int64_t row0, int64_t n_total,
+                              const float *levels_dev, int bits, uint64_t seed, uint32_t epoch,
+                              void *packed1_dev, void *packed2_dev)
+{
+    if (!A_dev || !levels_dev || !packed1_dev || !packed2_dev) return ZIPML_EINVAL;
+    if (n_rows <= 0 || d <= 0 || lda < d || n_total <= 0 || !valid_bits(bits)) return ZIPML_EINVAL;
+    if (row0 < 0 || row0 % 32 != 0 || row0 + n_rows > n_total) return ZIPML_EINVAL;
+    if (n_rows % 32 != 0 && row0 + n_rows != n_total) return ZIPML_EINVAL;
+    if (epoch >= (1u << 24)) return ZIPML_EINVAL;
+    if (!aligned16(levels_dev) || !aligned16(packed1_dev) || !aligned16(packed2_dev) ||
+        (reinterpret_cast<uintptr_t>(A_dev) & 3u))
+        return ZIPML_EALIGN;
+    const Layout lay = make_layout(n_total, d, bits);
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t *p1 = (uint32_t *)packed1_dev, *p2 = (uint32_t *)packed2_dev;
+#define CALL(B) launch_quantize<B>(s, A_dev, n_rows, d, lda, row0, lay, levels_dev, seed, epoch, p1, p2)
+    ZIPML_DISPATCH_BITS(bits, CALL)
+#undef CALL
+}
+
+extern "C" int zipml_unpack_codes(void *stream, const void *packed_dev, int copy, int64_t n,
+                                  int64_t d, int bits, uint8_t *codes_dev)
+{
+    if (!packed_dev || !codes_dev || n <= 0 || d <= 0 || !valid_bits(bits)) return ZIPML_EINVAL;
+    if (copy != 1 && copy != 2) return ZIPML_EINVAL;
+    if (!aligned16(packed_dev)) return ZIPML_EALIGN;
+    const Layout lay = make_layout(n, d, bits);
+    hipStream_t s = (hipStream_t)stream;
+#define CALL(B) launch_unpack<B>(s, (const uint32_t *)packed_dev, copy, lay, codes_dev)
+    ZIPML_DISPATCH_BITS(bits, CALL)
+#undef CALL
+}

@@ -1,0 +1,93 @@
+"""The C-ABI library loads, exports every symbol its header declares, and rejects bad
+arguments with error codes before touching the GPU (runs without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1611_05402_amd import zipml
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(zipml.LIB_PATH):
+        from paper_1611_05402_amd import build
+        build.build()
+    return zipml.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "zipml.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(zipml_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_exports_match_header(lib):
+    names = declared_functions()
+    assert len(names) >= 10
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in include/zipml.h but not exported"
+    assert sorted(zipml.EXPORTS) == names
+
+
+def test_strerror_and_sizes(lib):
+    assert zipml.strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert zipml.strerror(code) not in ("ok", "unknown error")
+    assert zipml.strerror(-99) == "unknown error"
+    # n, d padded to multiples of 32; bits/8 bytes per value
+    assert zipml.packed_bytes(4096, 64, 4) == 4096 * 64 // 2
+    assert zipml.packed_bytes(65536, 2048, 8) == 128 << 20
+    assert zipml.packed_bytes(1000, 70, 3) == 1024 * 96 * 3 // 8
+    assert zipml.packed_bytes(0, 64, 4) == 0 and zipml.packed_bytes(10, 64, 9) == 0
+    assert zipml.workspace_bytes(4096, 64, 4, 16) >= 4096
+    assert zipml.workspace_bytes(4096, 64, 4, 16, 1024) >= 64 * 1024 * 24
+    assert zipml.workspace_bytes(4096, 64, 0, 16) == 0
+
+
+def test_argument_errors_are_codes_not_crashes(lib):
+    null = None
+    fake = C.c_void_p(0x1000)          # aligned, never dereferenced: validation fails first
+    odd = C.c_void_p(0x1004)
+    # quantize
+    assert lib.zipml_quantize(null, null, 32, 8, 8, 0, 32, fake, 4, 0, 0, fake, fake) == zipml.EINVAL
+    assert lib.zipml_quantize(null, fake, 32, 8, 4, 0, 32, fake, 4, 0, 0, fake, fake) == zipml.EINVAL   # lda < d
+    assert lib.zipml_quantize(null, fake, 32, 8, 8, 0, 32, fake, 9, 0, 0, fake, fake) == zipml.EINVAL   # bits
+    assert lib.zipml_quantize(null, fake, 32, 8, 8, 16, 64, fake, 4, 0, 0, fake, fake) == zipml.EINVAL  # row0 % 32
+    assert lib.zipml_quantize(null, fake, 20, 8, 8, 0, 64, fake, 4, 0, 0, fake, fake) == zipml.EINVAL   # ragged middle chunk
+    assert lib.zipml_quantize(null, fake, 32, 8, 8, 0, 32, fake, 4, 0, 1 << 24, fake, fake) == zipml.EINVAL
+    assert lib.zipml_quantize(null, fake, 32, 8, 8, 0, 32, fake, 4, 0, 0, odd, fake) == zipml.EALIGN
+    # unpack
+    assert lib.zipml_unpack_codes(null, fake, 3, 32, 8, 4, fake) == zipml.EINVAL
+    assert lib.zipml_unpack_codes(null, odd, 1, 32, 8, 4, fake) == zipml.EALIGN
+    # sgd
+    def sgd(n=64, d=8, bits=4, batch=16, gb=0, mb=0, grid=null, gmax=0, flags=0, ws=fake, wsb=1 << 20,
+            x=fake, epoch=0):
+        return lib.zipml_sgd_epoch(null, fake, fake, fake, grid, 0.0, 0.0, gmax, fake, n, d, bits, x,
+                                   batch, 0.1, gb, mb, 0, epoch, flags, ws, wsb)
+    assert sgd(batch=24) == zipml.EINVAL            # not 4/8/16 or a multiple of 32
+    assert sgd(n=100, batch=32) == zipml.EINVAL     # batch does not divide n
+    assert sgd(bits=0) == zipml.EINVAL
+    assert sgd(mb=1) == zipml.EINVAL and sgd(mb=9) == zipml.EINVAL
+    assert sgd(mb=8) == zipml.EINVAL                # integer mode needs grid indices
+    assert sgd(gb=8) == zipml.EUNSUPPORTED          # gradient quantisation needs model quantisation
+    assert sgd(flags=zipml.SGD_AVERAGED) == zipml.EUNSUPPORTED
+    assert sgd(flags=64) == zipml.EINVAL
+    assert sgd(x=odd) == zipml.EALIGN
+    assert sgd(ws=null) in (zipml.EWORKSPACE, zipml.EALIGN)
+    assert sgd(wsb=16) == zipml.EWORKSPACE
+    assert sgd(n=1 << 20, d=1 << 20, bits=8, batch=32, mb=8, grid=fake, gmax=255) == zipml.ERANGE
+    assert sgd(epoch=1 << 24) == zipml.EINVAL
+    # levels
+    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, 2, 0, 0, fake, fake, fake, null, None, fake, 1 << 20) == zipml.EINVAL
+    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, zipml.OPTIMAL, 0, 8, fake, fake, fake, null, None, fake, 1 << 20) == zipml.EINVAL  # M < 2^bits - 1
+    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, zipml.UNIFORM, 0, 0, fake, fake, fake, null, None, fake, 8) == zipml.EWORKSPACE
+    # loss
+    out = C.c_double(0)
+    assert lib.zipml_loss(null, fake, 8, null, 2, null, 0, fake, fake, 0, 8, C.byref(out), fake, 1 << 20) == zipml.EINVAL
+    assert lib.zipml_loss(null, null, 0, null, 2, null, 0, fake, fake, 64, 8, C.byref(out), fake, 1 << 20) == zipml.EINVAL
+    assert lib.zipml_loss(null, fake, 8, null, 2, null, 0, fake, fake, 64, 8, C.byref(out), fake, 8) == zipml.EWORKSPACE
+    assert lib.zipml_sgd_status(null, null, 0) == zipml.EWORKSPACE

@@ -1,0 +1,346 @@
+"""GPU parity: every step of the hot path, through the C ABI, against the CPU oracle.
+
+Integer results (quantised codes, model/gradient codes, int32 dot products) must be
+bit-exact; the fp32 model and the loss must agree within a relative L2 of 1e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_harness import DEV, GpuProblem, dev, rel_l2
+from paper_1611_05402_amd import synth, zipml
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5   # relative L2 on model and loss (fp32 arithmetic)
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def uniform_levels_np(d, bits, lo, hi):
+    return oracle.levels_uniform(np.full(d, lo, np.float32), np.full(d, hi, np.float32), bits)
+
+
+# ------------------------------------------------------------------ levels
+@pytest.mark.parametrize("flags", [0, zipml.SYMMETRIC])
+def test_uniform_levels_and_ranges(flags):
+    say("levels uniform flags", flags)
+    rng = np.random.default_rng(0)
+    A = (rng.standard_normal((3000, 70)) * rng.uniform(0.1, 3, 70)).astype(np.float32)
+    p = GpuProblem(A, np.zeros(3000, np.float32), 5, 32)
+    p.make_levels(zipml.UNIFORM, flags)
+    lo, hi = oracle.col_range(A, symmetric=bool(flags & zipml.SYMMETRIC))
+    assert np.array_equal(p.lo.cpu().numpy(), lo) and np.array_equal(p.hi.cpu().numpy(), hi)
+    assert np.array_equal(p.levels.cpu().numpy(), oracle.levels_uniform(lo, hi, 5))
+    assert np.array_equal(p.grid.cpu().numpy(), np.tile(np.arange(32, dtype=np.int16), (70, 1)))
+    # a given range is used as is
+    p.make_levels(zipml.UNIFORM, 0, lo=np.full(70, -4.0), hi=np.full(70, 4.0))
+    assert np.array_equal(p.levels.cpu().numpy(), uniform_levels_np(70, 5, -4.0, 4.0))
+
+
+def test_optimal_levels_match_oracle_dp():
+    say("levels optimal")
+    w = synth.e2e(n=6000, d=40, n_candidates=256)
+    A, b = w.full()
+    p = GpuProblem(A, b, 3, 32, n_candidates=256)
+    mv = p.make_levels(zipml.OPTIMAL, 0, n_candidates=256, want_mv=True)
+    lo, hi = oracle.col_range(A)
+    hist = oracle.hist_moments(A, lo, hi, 256)
+    L, G, mv_ref = oracle.levels_optimal(hist, lo, hi, 3)
+    assert np.isclose(mv, mv_ref, rtol=1e-9)
+    Gg = p.grid.cpu().numpy().view(np.uint16)
+    Lg = p.levels.cpu().numpy()
+    cand = np.arange(257) / 256
+    for j in range(40):
+        if not np.array_equal(Gg[j], G[j]):
+            # several optima: the GPU's choice must be as good as the oracle's
+            t = (A[:, j].astype(np.float64) - lo[j]) / (float(hi[j]) - float(lo[j]))
+            mom = oracle.bin_moments(t, cand)
+            C = np.concatenate([[0], np.cumsum(mom[:, 0])])
+            S1 = np.concatenate([[0], np.cumsum(mom[:, 1])])
+            S2 = np.concatenate([[0], np.cumsum(mom[:, 2])])
+
+            def cost(idx):
+                tot = 0.0
+                for a_, b_ in zip(idx[:-1], idx[1:]):
+                    tot += (-(S2[b_] - S2[a_]) + (cand[a_] + cand[b_]) * (S1[b_] - S1[a_])
+                            - cand[a_] * cand[b_] * (C[b_] - C[a_]))
+                return tot
+            assert np.isclose(cost(Gg[j]), cost(G[j]), rtol=1e-9, atol=1e-12)
+        expect = (lo[j].astype(np.float64) + (float(hi[j]) - float(lo[j])) * Gg[j] / 256)
+        assert np.array_equal(Lg[j], expect.astype(np.float32))
+    assert np.mean([np.array_equal(Gg[j], G[j]) for j in range(40)]) > 0.9
+
+
+# ------------------------------------------------------------------ quantise
+QCASES = [
+    # name, n, d, bits, level spec
+    ("tiny", 4096, 64, 4, "fixed"),
+    ("ragged1", 1000, 70, 1, "fixed"),
+    ("ragged3", 1000, 70, 3, "minmax"),
+    ("b5", 512, 33, 5, "symmetric"),
+    ("b6", 480, 160, 6, "fixed"),
+    ("b7", 96, 224, 7, "fixed"),
+    ("dense8", 2048, 288, 8, "fixed"),
+    ("lowbit", 4096, 96, 2, "symmetric"),
+]
+
+
+@pytest.mark.parametrize("name,n,d,bits,spec", QCASES)
+def test_quantized_codes_bit_exact(name, n, d, bits, spec):
+    say("quantize", name, n, d, bits, spec)
+    w = synth.lowbit(n=n, d=d) if spec == "symmetric" else synth.tiny(n=n, d=d)
+    A, b = w.full()
+    if name == "ragged3":
+        A = (A * 1.7 + 0.3).astype(np.float32)
+    p = GpuProblem(A, b, bits, 32)
+    if spec == "fixed":
+        A[::7, ::5] = 1.5          # values outside the level range are clamped
+        A[1::7, ::3] = -1.0        # and values exactly on a level stay there
+        p = GpuProblem(A, b, bits, 32)
+        L = uniform_levels_np(d, bits, -1.0, 1.0)
+        p.set_levels(L)
+    else:
+        lo, hi = oracle.col_range(A, symmetric=(spec == "symmetric"))
+        L = oracle.levels_uniform(lo, hi, bits)
+        p.make_levels(zipml.UNIFORM, zipml.SYMMETRIC if spec == "symmetric" else 0)
+        assert np.array_equal(p.levels.cpu().numpy(), L)
+    seed, epoch = 0x1234567887654321, 5
+    p.quantize(seed, epoch)
+    c1, c2 = oracle.quantize(A, L, bits, seed, epoch)
+    assert np.array_equal(p.codes(1), c1)
+    assert np.array_equal(p.codes(2), c2)
+    # chunk-wise quantisation fills the same buffers
+    q = GpuProblem(A, b, bits, 32)
+    q.set_levels(L)
+    q.quantize(seed, epoch, chunks=3)
+    assert torch.equal(q.p1, p.p1) and torch.equal(q.p2, p.p2)
+
+
+def test_quantize_optimal_levels_and_epoch_key():
+    say("quantize optimal levels")
+    w = synth.e2e(n=2048, d=64, n_candidates=128)
+    A, b = w.full()
+    lo, hi = oracle.col_range(A)
+    L, G, _ = oracle.levels_optimal(oracle.hist_moments(A, lo, hi, 128), lo, hi, 3)
+    p = GpuProblem(A, b, 3, 32)
+    p.set_levels(L, G)
+    for epoch in (0, 1):
+        p.quantize(9, epoch)
+        c1, c2 = oracle.quantize(A, L, 3, 9, epoch)
+        assert np.array_equal(p.codes(1), c1) and np.array_equal(p.codes(2), c2)
+
+
+# ------------------------------------------------------------------ loss
+def test_loss_fp32_and_packed():
+    say("loss")
+    for (n, d, bits) in [(4096, 64, 4), (1000, 70, 3), (2048, 288, 8), (333, 5, 2)]:
+        w = synth.tiny(n=n, d=d)
+        A, b = w.full()
+        L = uniform_levels_np(d, bits, -1.0, 1.0)
+        p = GpuProblem(A, b, bits, 32)
+        p.set_levels(L)
+        p.quantize(3, 0)
+        rng = np.random.default_rng(n)
+        for x in (np.zeros(d, np.float32), w.x_star, rng.standard_normal(d).astype(np.float32)):
+            xd = dev(x)
+            ref = oracle.loss(A, b, x)
+            assert abs(p.loss(xd) - ref) <= TOL * ref + 1e-12
+            c1, c2 = oracle.quantize(A, L, bits, 3, 0)
+            for copy, c in ((1, c1), (2, c2)):
+                ref = oracle.loss_codes(c, L, bits, b, x)
+                assert abs(p.loss(xd, packed_copy=copy) - ref) <= TOL * ref + 1e-12
+
+
+# ------------------------------------------------------------------ SGD, fp32 model
+SGD_CASES = [
+    # name, workload factory, kwargs, epochs, lr
+    ("tiny", synth.tiny, dict(), 5, 0.01),
+    ("tiny_b4", synth.tiny, dict(n=512, d=64, batch=4), 2, 0.01),
+    ("tiny_b8_ragged_d", synth.tiny, dict(n=512, d=70, batch=8, bits=3), 2, 0.01),
+    ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256), 3, 1e-3),
+    ("lowbit_small", synth.lowbit, dict(n=8192, d=96, batch=1024), 2, 0.05),
+    ("b1", synth.tiny, dict(n=1024, d=96, batch=32, bits=1), 2, 0.01),
+    ("b5", synth.tiny, dict(n=1024, d=160, batch=64, bits=5), 2, 0.01),
+    ("b6", synth.tiny, dict(n=1024, d=32, batch=128, bits=6), 2, 0.01),
+    ("b7", synth.tiny, dict(n=1024, d=64, batch=32, bits=7), 2, 0.01),
+    ("tomo_small", synth.tomo, dict(n=2048, d=1024, batch=512), 2, 0.5),
+]
+
+
+def _levels_for(w, A):
+    if w.range_mode == "symmetric":
+        lo, hi = oracle.col_range(A, symmetric=True)
+    else:
+        lo, hi = np.full(w.d, w.lo, np.float32), np.full(w.d, w.hi, np.float32)
+    return oracle.levels_uniform(lo, hi, w.bits)
+
+
+@pytest.mark.parametrize("flags", [0, zipml.SGD_STEPWISE], ids=["persistent", "stepwise"])
+@pytest.mark.parametrize("name,factory,kw,epochs,lr", SGD_CASES, ids=[c[0] for c in SGD_CASES])
+def test_sgd_epochs_match_oracle(name, factory, kw, epochs, lr, flags):
+    say("sgd", name, "flags", flags)
+    w = factory(**kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L)
+    p.quantize(7, 0)
+    c1, c2 = oracle.quantize(A, L, w.bits, 7, 0)
+    assert np.array_equal(p.codes(1), c1) and np.array_equal(p.codes(2), c2)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(epochs):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, lr)
+        p.epoch(x, lr, flags=flags)
+        xg = x.cpu().numpy()
+        err = rel_l2(xg, x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}")
+        assert err <= TOL
+        l_ref = oracle.loss(A, b, x_ref)
+        assert abs(p.loss(x) - l_ref) <= TOL * l_ref + 1e-12
+    assert np.linalg.norm(x_ref) > 0
+
+
+def test_sgd_fp32_with_non_uniform_levels():
+    say("sgd fp32, optimal levels (table look-up path)")
+    w = synth.e2e(n=2048, d=96, batch=64, n_candidates=128)
+    A, b = w.full()
+    lo, hi = oracle.col_range(A)
+    L, G, _ = oracle.levels_optimal(oracle.hist_moments(A, lo, hi, 128), lo, hi, 3)
+    p = GpuProblem(A, b, 3, 64)
+    p.set_levels(L, G)
+    p.quantize(1, 0)
+    c1, c2 = oracle.quantize(A, L, 3, 1, 0)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(2):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, 3, x_ref, 64, 0.2)
+        p.epoch(x, 0.2)
+        assert rel_l2(x.cpu().numpy(), x_ref) <= TOL
+
+
+# ------------------------------------------------------------------ end-to-end low precision
+def _grid_uniform(bits, lo, hi):
+    K = 1 << bits
+    return np.float32(lo), np.float32((np.float64(hi) - np.float64(lo)) / (K - 1)), K - 1
+
+
+E2E_CASES = [
+    ("tiny_u4", dict(n=1024, d=64, batch=16, bits=4), 8, 8),
+    ("tiny_u8_b256", dict(n=2048, d=288, batch=256, bits=8), 8, 8),
+    ("tiny_u2_ragged", dict(n=512, d=70, batch=32, bits=2), 4, 6),
+    ("model_only", dict(n=1024, d=96, batch=64, bits=4), 0, 8),
+]
+
+
+@pytest.mark.parametrize("flags", [0, zipml.SGD_STEPWISE], ids=["persistent", "stepwise"])
+@pytest.mark.parametrize("name,kw,gb,mb", E2E_CASES, ids=[c[0] for c in E2E_CASES])
+def test_end_to_end_uniform_grid_bit_exact(name, kw, gb, mb, flags):
+    say("e2e", name, "flags", flags)
+    w = synth.tiny(**kw)
+    A, b = w.full()
+    L = uniform_levels_np(w.d, w.bits, -1.0, 1.0)
+    G = np.tile(np.arange(1 << w.bits, dtype=np.uint16), (w.d, 1))
+    glo, gstep, gmax = _grid_uniform(w.bits, -1.0, 1.0)
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L, G)
+    p.quantize(11, 2)
+    c1, c2 = oracle.quantize(A, L, w.bits, 11, 2)
+    rng = np.random.default_rng(5)
+    x0 = (rng.standard_normal(w.d) * 0.3).astype(np.float32)
+    # one step from a given model: every intermediate
+    step = 3
+    x_ref, dbg = oracle.sgd_epoch_e2e(c1, c2, L, G, glo, gstep, b, w.bits, x0, w.batch, 0.05, gb, mb,
+                                      11, 2, first_step=step, num_steps=1, debug=True)
+    xd = dev(x0)
+    mo = torch.zeros(w.d, dtype=torch.int32, device=DEV)
+    ac = torch.zeros(w.batch, dtype=torch.int32, device=DEV)
+    rr = torch.zeros(w.batch, dtype=torch.float32, device=DEV)
+    gg = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    gq = torch.zeros(w.d, dtype=torch.int32, device=DEV)
+    zipml.debug_step(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, xd, w.batch, 0.05, step, p.ws,
+                     grid_idx=p.grid, grid_lo=glo, grid_step=gstep, grid_max=gmax, grad_bits=gb,
+                     model_bits=mb, seed=11, epoch=2, flags=flags, model_codes=mo, acc=ac, r=rr, g=gg,
+                     grad_codes=gq)
+    assert zipml.sgd_status(p.ws) == 0
+    assert np.array_equal(mo.cpu().numpy(), dbg["m"])
+    assert np.array_equal(ac.cpu().numpy(), dbg["acc"])
+    assert np.array_equal(rr.cpu().numpy().view(np.uint32), dbg["r"].view(np.uint32))
+    assert np.array_equal(gg.cpu().numpy().view(np.uint32), dbg["g"].view(np.uint32))
+    if gb:
+        assert np.array_equal(gq.cpu().numpy(), dbg["gq"])
+    assert np.array_equal(xd.cpu().numpy().view(np.uint32), x_ref.view(np.uint32))
+    # whole epochs stay bit-identical
+    x_ref = x0.copy()
+    xd = dev(x0)
+    for ep in range(2):
+        x_ref = oracle.sgd_epoch_e2e(c1, c2, L, G, glo, gstep, b, w.bits, x_ref, w.batch, 0.05, gb,
+                                     mb, 11, ep)
+        p.epoch(xd, 0.05, seed=11, epoch=ep, flags=flags, grad_bits=gb, model_bits=mb, grid_lo=glo,
+                grid_step=gstep, grid_max=gmax)
+        assert np.array_equal(xd.cpu().numpy().view(np.uint32), x_ref.view(np.uint32))
+    # and the run is reproducible
+    xd2 = dev(x0)
+    for ep in range(2):
+        p.epoch(xd2, 0.05, seed=11, epoch=ep, flags=flags, grad_bits=gb, model_bits=mb, grid_lo=glo,
+                grid_step=gstep, grid_max=gmax)
+    assert torch.equal(xd, xd2)
+
+
+def test_end_to_end_optimal_levels_bit_exact():
+    say("e2e optimal 3-bit levels, 8-bit model and gradient")
+    M = 256
+    w = synth.e2e(n=2048, d=160, batch=64, n_candidates=M)
+    A, b = w.full()
+    lo, hi = np.zeros(w.d, np.float32), np.ones(w.d, np.float32)
+    L, G, _ = oracle.levels_optimal(oracle.hist_moments(A, lo, hi, M), lo, hi, 3)
+    glo, gstep, gmax = np.float32(0.0), np.float32(1.0 / M), M
+    p = GpuProblem(A, b, 3, 64)
+    p.set_levels(L, G)
+    p.quantize(4, 0)
+    c1, c2 = oracle.quantize(A, L, 3, 4, 0)
+    assert np.array_equal(p.codes(1), c1) and np.array_equal(p.codes(2), c2)
+    x_ref = np.zeros(w.d, np.float32)
+    xd = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(2):
+        x_ref = oracle.sgd_epoch_e2e(c1, c2, L, G, glo, gstep, b, 3, x_ref, 64, 0.3, 8, 8, 4, ep)
+        p.epoch(xd, 0.3, seed=4, epoch=ep, grad_bits=8, model_bits=8, grid_lo=glo, grid_step=gstep,
+                grid_max=gmax)
+        assert np.array_equal(xd.cpu().numpy().view(np.uint32), x_ref.view(np.uint32))
+    assert np.linalg.norm(x_ref) > 0
+
+
+# ------------------------------------------------------------------ edge cases
+def test_degenerate_inputs():
+    say("edge cases")
+    # a single step per epoch, one feature group, flat column, zero model in integer mode
+    w = synth.tiny(n=32, d=5, batch=32, bits=2)
+    A, b = w.full()
+    A[:, 2] = 0.5
+    lo, hi = oracle.col_range(A)
+    L = oracle.levels_uniform(lo, hi, 2)
+    p = GpuProblem(A, b, 2, 32)
+    p.make_levels(zipml.UNIFORM, 0)
+    assert np.array_equal(p.levels.cpu().numpy(), L)
+    p.quantize(1, 0)
+    c1, c2 = oracle.quantize(A, L, 2, 1, 0)
+    assert np.array_equal(p.codes(1), c1) and np.array_equal(p.codes(2), c2)
+    x = torch.zeros(5, dtype=torch.float32, device=DEV)
+    p.epoch(x, 0.1)
+    assert rel_l2(x.cpu().numpy(), oracle.sgd_epoch(c1, c2, L, b, 2, np.zeros(5), 32, 0.1)) <= TOL
+    # zero-length work and rejected shapes return codes
+    with pytest.raises(zipml.ZipmlError) as e:
+        zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, 32, 5, 2, x, 24, 0.1, p.ws)
+    assert e.value.code == zipml.EINVAL
+    # a batch too large for the persistent kernel is refused, not mis-executed
+    big = synth.tiny(n=1 << 15, d=32, batch=1 << 15, bits=8)
+    Ab, bb = big.full()
+    pb = GpuProblem(Ab, bb, 8, 1 << 15)
+    xb = torch.zeros(32, dtype=torch.float32, device=DEV)
+    with pytest.raises(zipml.ZipmlError) as e:
+        zipml.sgd_epoch(pb.p1, pb.p2, pb.levels, pb.b, 1 << 15, 32, 8, xb, 1 << 15, 0.1, pb.ws)
+    assert e.value.code == zipml.EUNSUPPORTED
