@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
+#include <stdio.h>
 #include <stdint.h>
 
 #include "../../include/zipml.h"
@@ -42,6 +43,24 @@ struct Workspace {
     static size_t sgd_bytes(int64_t batch) { return kAcc + 3 * acc_words(batch) * 4; }
 };
 
-inline int hip_check(hipError_t e) { return e == hipSuccess ? ZIPML_OK : ZIPML_ELAUNCH; }
+// Called on entry of every API function: hipGetLastError() is sticky per host thread, so an
+// error left behind by an earlier, unrelated runtime call of the caller (e.g. a pointer query on
+// host memory) must not be mistaken for a failed launch of ours.
+inline hipStream_t entry_stream(void *stream)
+{
+    (void)hipGetLastError();
+    return (hipStream_t)stream;
+}
+
+// Maps a HIP status to a library status; the HIP error text goes to stderr so that ZIPML_ELAUNCH
+// can be diagnosed.
+inline int hip_check_at(hipError_t e, const char *file, int line)
+{
+    if (e == hipSuccess) return ZIPML_OK;
+    fprintf(stderr, "libzipml: HIP error '%s' at %s:%d\n", hipGetErrorString(e), file, line);
+    return ZIPML_ELAUNCH;
+}
+#define hip_check(e) hip_check_at((e), __FILE__, __LINE__)
+#define HIP_FAILED(e) (hip_check_at((e), __FILE__, __LINE__) != ZIPML_OK)
 
 }  // namespace zipml

@@ -202,7 +202,7 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
     const size_t need = levels_workspace_bytes(d, mode == ZIPML_OPTIMAL ? n_candidates : 0);
     if (need_data && (!workspace_dev || workspace_bytes < need || !aligned16(workspace_dev)))
         return ZIPML_EWORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
+    hipStream_t s = entry_stream(stream);
     const unsigned cb = (unsigned)((d + 255) / 256);
     // rows are split into slabs so that the scan fills the device
     int64_t slabs = std::max<int64_t>(1, std::min<int64_t>(n / 64 + 1, 4096 / cb + 1));
@@ -216,7 +216,7 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
                            rows_per_slab, kmin, kmax);
         hipLaunchKernelGGL(k_range_final, dim3(cb), dim3(256), 0, s, kmin, kmax, d,
                            (flags & ZIPML_SYMMETRIC) ? 1 : 0, lo_dev, hi_dev);
-        if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+        if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     }
     if (mode == ZIPML_UNIFORM) {
         const int64_t total = d * K;
@@ -233,7 +233,7 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
                        hcount);
     hipLaunchKernelGGL(k_hist, dim3(cb, (unsigned)slabs), dim3(256), 0, s, A_dev, n, d, lda,
                        rows_per_slab, lo_dev, hi_dev, M, hist_dev);
-    if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     std::vector<double> hist((size_t)hcount);
     std::vector<float> lo((size_t)d), hi((size_t)d);
     if (hipMemcpyAsync(hist.data(), hist_dev, sizeof(double) * (size_t)hcount, hipMemcpyDeviceToHost,

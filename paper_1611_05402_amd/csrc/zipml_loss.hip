@@ -158,7 +158,7 @@ extern "C" int zipml_loss(void *stream, const float *A_dev, int64_t lda, const v
     if (!workspace_dev || workspace_bytes < (size_t)(kLossMaxBlocks + 1) * sizeof(double))
         return ZIPML_EWORKSPACE;
     if (!aligned16(workspace_dev) || !aligned16(x_dev)) return ZIPML_EALIGN;
-    hipStream_t s = (hipStream_t)stream;
+    hipStream_t s = entry_stream(stream);
     double *partial = (double *)workspace_dev;
     double *out = partial + kLossMaxBlocks;
     int blocks = 0;
@@ -196,10 +196,10 @@ extern "C" int zipml_loss(void *stream, const float *A_dev, int64_t lda, const v
             case 8: launch_loss_packed<8>(s, p, copy, lay, levels_dev, b_dev, x_dev, blocks, partial); break;
         }
     }
-    if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(kLossThreads), 0, s, partial, blocks,
                        1.0 / (2.0 * (double)n), out);
-    if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (hipMemcpyAsync(loss_host, out, sizeof(double), hipMemcpyDeviceToHost, s) != hipSuccess)
         return ZIPML_ELAUNCH;
     if (hipStreamSynchronize(s) != hipSuccess) return ZIPML_ELAUNCH;

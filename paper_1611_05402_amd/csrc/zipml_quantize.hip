@@ -207,7 +207,7 @@ extern "C" int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, 
         (reinterpret_cast<uintptr_t>(A_dev) & 3u))
         return ZIPML_EALIGN;
     const Layout lay = make_layout(n_total, d, bits);
-    hipStream_t s = (hipStream_t)stream;
+    hipStream_t s = entry_stream(stream);
     uint32_t *p1 = (uint32_t *)packed1_dev, *p2 = (uint32_t *)packed2_dev;
 #define CALL(B) launch_quantize<B>(s, A_dev, n_rows, d, lda, row0, lay, levels_dev, seed, epoch, p1, p2)
     ZIPML_DISPATCH_BITS(bits, CALL)
@@ -221,7 +221,7 @@ extern "C" int zipml_unpack_codes(void *stream, const void *packed_dev, int copy
     if (copy != 1 && copy != 2) return ZIPML_EINVAL;
     if (!aligned16(packed_dev)) return ZIPML_EALIGN;
     const Layout lay = make_layout(n, d, bits);
-    hipStream_t s = (hipStream_t)stream;
+    hipStream_t s = entry_stream(stream);
 #define CALL(B) launch_unpack<B>(s, (const uint32_t *)packed_dev, copy, lay, codes_dev)
     ZIPML_DISPATCH_BITS(bits, CALL)
 #undef CALL

@@ -510,20 +510,20 @@ template <int BITS>
 static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
 {
     auto kern = k_sgd<BITS>;
-    if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)p.shmem) != hipSuccess)
+    if (HIP_FAILED(hipFuncSetAttribute((const void *)kern,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.shmem)))
         return ZIPML_ELAUNCH;
     const int words = 3 * a.acc_words;
     hipLaunchKernelGGL(k_sgd_reset, dim3((words + 255) / 256), dim3(256), 0, s, a.status, a.sync,
                        a.acc, words, 1);
-    if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (!stepwise) {
         a.persistent = 1;
         a.seg_first = 0;
         a.seg_last = 3;
         void *params[] = {&a};
-        if (hipLaunchCooperativeKernel((const void *)kern, dim3(a.W), dim3(kThreads), params,
-                                       (unsigned)p.shmem, s) != hipSuccess)
+        if (HIP_FAILED(hipLaunchCooperativeKernel((const void *)kern, dim3(a.W), dim3(kThreads),
+                                                  params, (unsigned)p.shmem, s)))
             return ZIPML_ELAUNCH;
         return ZIPML_OK;
     }
@@ -544,7 +544,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
             a.seg_last = seg;
             if (seg == 2 && a.grad_bits == 0) a.seg_last = 3;
             hipLaunchKernelGGL(kern, dim3(a.W), dim3(kThreads), p.shmem, s, a);
-            if (hipGetLastError() != hipSuccess) return ZIPML_ELAUNCH;
+            if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
         }
     }
     return ZIPML_OK;
@@ -621,7 +621,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.acc_words = (int)Workspace::acc_words(batch);
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
-    hipStream_t s = (hipStream_t)stream;
+    hipStream_t s = entry_stream(stream);
     const bool stepwise = (flags & ZIPML_SGD_STEPWISE) != 0;
     switch (bits) {
         case 1: return launch_sgd<1>(s, a, p, stepwise);
@@ -675,7 +675,7 @@ extern "C" int zipml_sgd_status(void *stream, const void *workspace_dev, size_t 
 {
     if (!workspace_dev || workspace_bytes < 4096) return ZIPML_EWORKSPACE;
     int st = 0;
-    hipStream_t s = (hipStream_t)stream;
+    hipStream_t s = entry_stream(stream);
     if (hipMemcpyAsync(&st, (const unsigned char *)workspace_dev + Workspace::kStatus, sizeof(int),
                        hipMemcpyDeviceToHost, s) != hipSuccess)
         return ZIPML_ELAUNCH;

@@ -40,6 +40,10 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1611_05402_amd.build` "
                                "(or __graft_entry__.build()) first")
+        # PyTorch ships its own HIP runtime; it has to be the one already loaded when libzipml.so
+        # resolves libamdhip64, otherwise the process ends up with two runtimes and the tensors'
+        # device pointers belong to the other one.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.zipml_strerror.restype = C.c_char_p
         L.zipml_strerror.argtypes = [C.c_int]
