@@ -20,7 +20,7 @@
  *     non-decreasing along the second axis.  All device pointers must be 16-byte aligned.
  *   - The packed layout of the quantised copies is private to the library (copy 1 is stored
  *     feature-major for the gradient pass, copy 2 sample-major for the dot-product pass, both in
- *     blocks of 32 features); zipml_unpack_codes is its only definition.
+ *     units of 32 codes); zipml_unpack_codes is its only definition.
  *   - Random numbers: Philox4x32-10, key = seed, counter = (row, feature / 4, epoch * 256 + stream),
  *     output word feature % 4, the top 24 bits as a uniform in [0,1).  Streams 1, 2 are the two
  *     sample quantisations (row = sample index), 3 and 4 the model and gradient quantisations
@@ -62,7 +62,7 @@ extern "C" {
 const char *zipml_strerror(int code);
 
 /* Bytes of ONE packed copy of an n x d matrix at `bits` bits per value, padding included
- * (n and d are rounded up to multiples of 32).  0 if the arguments are invalid. */
+ * (n is rounded up to a multiple of 64, d to a multiple of 32).  0 if the arguments are invalid. */
 size_t zipml_packed_bytes(int64_t n, int64_t d, int bits);
 
 /* Bytes of device workspace that zipml_levels, zipml_sgd_epoch, zipml_debug_step and zipml_loss

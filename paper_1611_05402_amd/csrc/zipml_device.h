@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace zipml {
 
 constexpr int kWave = 64;
@@ -98,6 +100,30 @@ __device__ __forceinline__ T wave_sum(T v)
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
     return v;
+}
+
+// fp32 / int32 sum over the 64 lanes with DPP row operations (no LDS traffic); every lane gets the
+// result.  Steps: xor 1, xor 2 inside each quad, mirror inside each half row, mirror inside each
+// row of 16, then the four row sums are combined through scalar registers.
+template <typename T>
+__device__ __forceinline__ T wave_sum_dpp(T v)
+{
+    static_assert(sizeof(T) == 4, "32-bit types only");
+    auto dpp = [](T x, auto ctrl) {
+        int xi = __builtin_bit_cast(int, x);
+        xi = __builtin_amdgcn_update_dpp(0, xi, decltype(ctrl)::value, 0xF, 0xF, true);
+        return __builtin_bit_cast(T, xi);
+    };
+    v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+    v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+    v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+    v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
+    const int vi = __builtin_bit_cast(int, v);
+    const T r0 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 0));
+    const T r1 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 16));
+    const T r2 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 32));
+    const T r3 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 48));
+    return (r0 + r1) + (r2 + r3);
 }
 
 // Sum over the block; every thread gets the result.  scratch: >= blockDim/64 + 1 elements of T.

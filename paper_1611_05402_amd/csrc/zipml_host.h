@@ -13,14 +13,18 @@ inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_bits(int bits) { return bits >= 1 && bits <= 8; }
 
-// Packed layout (private).  n and d are padded to multiples of 32.
-//   copy 2 (dot pass):      [feature group g][sample i][bits dwords]          32 features per unit
-//   copy 1 (gradient pass): [feature group g][sample group][feature in g][bits dwords]
-//                                                                            32 samples per unit
+// Packed layout (private).  A unit is 32 codes of `bits` bits: a little-endian bit string of
+// `bits` dwords.  n is padded to a multiple of 64, d to a multiple of 32.  Units are stored
+// dword-planar, so that the lanes of a wave read consecutive dwords (global memory and LDS alike):
+//   copy 2 (dot pass):      unit = one sample x 32 features
+//                           [feature group g][block of 64 samples][dword q][sample in block]
+//   copy 1 (gradient pass): unit = one feature x 32 samples
+//                           [feature group g][group of 32 samples][dword q][feature in group]
 struct Layout {
     int64_t n, d, n_pad, d_pad;
     int64_t d32;    // feature groups
-    int64_t n32;    // sample groups
+    int64_t n32;    // sample groups of 32 (copy 1)
+    int64_t nb64;   // sample blocks of 64 (copy 2)
     int bits;
     size_t bytes() const { return (size_t)n_pad * (size_t)d_pad * (size_t)bits / 8; }
 };
@@ -28,8 +32,8 @@ inline Layout make_layout(int64_t n, int64_t d, int bits)
 {
     Layout L;
     L.n = n; L.d = d; L.bits = bits;
-    L.n_pad = round_up(n, 32); L.d_pad = round_up(d, 32);
-    L.d32 = L.d_pad / 32; L.n32 = L.n_pad / 32;
+    L.n_pad = round_up(n, 64); L.d_pad = round_up(d, 32);
+    L.d32 = L.d_pad / 32; L.n32 = L.n_pad / 32; L.nb64 = L.n_pad / 64;
     return L;
 }
 

@@ -35,7 +35,7 @@ constexpr int kLdsRow = 33;      // dwords per LDS row of 128 code bytes (+1: co
 template <int BITS>
 __global__ __launch_bounds__(256) void k_quantize_pack(
     const float *__restrict__ A, int64_t n_rows, int64_t d, int64_t lda, int64_t row0,
-    int64_t n_pad, int64_t n32, int64_t d32, const float *__restrict__ levels, uint64_t seed,
+    int64_t nb64, int64_t n32, int64_t d32, const float *__restrict__ levels, uint64_t seed,
     uint32_t epoch, uint32_t *__restrict__ p1, uint32_t *__restrict__ p2, int vec_ok)
 {
     __shared__ uint32_t c1w[32 * kLdsRow];
@@ -99,9 +99,10 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
                 const uint32_t w = c2w[r * kLdsRow + gq * 8 + (k >> 2)];
                 unit_set<BITS>(unit, k, (w >> (8 * (k & 3))) & 0xFFu);
             }
-            uint32_t *dst = p2 + (g * n_pad + rg * 32 + r) * BITS;
+            const int64_t i = rg * 32 + r;
+            uint32_t *dst = p2 + ((g * nb64 + i / 64) * BITS) * 64 + (i % 64);
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
+            for (int q = 0; q < BITS; ++q) dst[q * 64] = unit[q];
         }
     } else {
         // copy 1: one unit = feature c, the 32 samples of this group
@@ -116,9 +117,9 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
                 const uint32_t w = c1w[k * kLdsRow + (c >> 2)];
                 unit_set<BITS>(unit, k, (w >> (8 * (c & 3))) & 0xFFu);
             }
-            uint32_t *dst = p1 + ((g * n32 + rg) * 32 + cin) * BITS;
+            uint32_t *dst = p1 + ((g * n32 + rg) * BITS) * 32 + cin;
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
+            for (int q = 0; q < BITS; ++q) dst[q * 32] = unit[q];
         }
     }
 }
@@ -131,11 +132,12 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // unit index
     if (u >= d32 * n_pad) return;
     uint32_t unit[BITS];
-#pragma unroll
-    for (int q = 0; q < BITS; ++q) unit[q] = packed[u * BITS + q];
     if (copy == 2) {
         const int64_t g = u / n_pad, i = u % n_pad;
         if (i >= n) return;
+        const uint32_t *src = packed + ((g * (n_pad / 64) + i / 64) * BITS) * 64 + (i % 64);
+#pragma unroll
+        for (int q = 0; q < BITS; ++q) unit[q] = src[q * 64];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             const int64_t j = g * 32 + k;
@@ -145,6 +147,9 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
         const int64_t g = u / n_pad, rem = u % n_pad, rg = rem / 32, cin = rem % 32;
         const int64_t j = g * 32 + cin;
         if (j >= d) return;
+        const uint32_t *src = packed + ((g * n32 + rg) * BITS) * 32 + cin;
+#pragma unroll
+        for (int q = 0; q < BITS; ++q) unit[q] = src[q * 32];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             const int64_t i = rg * 32 + k;
@@ -161,7 +166,7 @@ static int launch_quantize(hipStream_t s, const float *A, int64_t n_rows, int64_
     const int vec_ok = (lda % 4 == 0) && aligned16(A);
     dim3 grid((unsigned)((n_rows + 31) / 32), (unsigned)((lay.d32 + 3) / 4));
     hipLaunchKernelGGL(k_quantize_pack<BITS>, grid, dim3(256), 0, s, A, n_rows, d, lda, row0,
-                       lay.n_pad, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok);
+                       lay.nb64, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok);
     return hip_check(hipGetLastError());
 }
 

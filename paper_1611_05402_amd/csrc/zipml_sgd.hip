@@ -4,23 +4,34 @@
 //
 // Decomposition (feature-owner): workgroup w owns a block of 32*GQ features for the whole epoch and
 // keeps its slice of the model in LDS.  Per step it
-//   1. streams its slice of copy 2 (sample-major units) and adds the partial dot products of the
-//      `batch` samples into a device-wide accumulator,
+//   1. reads its slice of copy 2 (sample-major units) and adds the partial dot products of the
+//      `batch` samples into a device-wide accumulator (device-scope atomics),
 //   2. meets the other workgroups at ONE grid-wide barrier,
-//   3. reads the `batch` residuals, streams its slice of copy 1 (feature-major units), forms its
-//      slice of the mean gradient and updates its slice of the model -- all locally.
-// The packed data does not depend on the model, so the slice for step t+1 is fetched straight into
-// LDS (global_load_lds) while step t waits at the barrier.
+//   3. reads the `batch` sums, forms the residuals, reads its slice of copy 1 (feature-major
+//      units), forms its slice of the mean gradient and updates its slice of the model, locally.
+// A step is bound by the latency of that one device-wide exchange, not by bandwidth, so the kernel
+// is organised around it:
+//   - the packed data does not depend on the model: the slice for step t+1 is fetched straight
+//     into LDS (global_load_lds) while step t waits at the barrier;
+//   - loads of one wave return in order, so a wave with a prefetch in flight cannot do a
+//     latency-critical load: wave 0 never prefetches, it polls the barrier and reads the sums;
+//   - exchanged data moves only through device-scope atomics / loads, so the barrier needs no
+//     cache write-back, only "my atomics have been performed" (s_waitcnt vmcnt(0)).
 // End-to-end mode adds two small exchanges per step (the l2 norms of model and gradient).
 #include "zipml_device.h"
 #include "zipml_host.h"
 
 #include <math.h>
+#include <stdlib.h>
 
 namespace zipml {
 
 constexpr int kThreads = 256;
-constexpr uint32_t kSpinLimit = 1u << 22;   // bounded wait: a lost workgroup ends in ZIPML_ETIMEOUT
+constexpr int kWaves = kThreads / kWave;
+constexpr int kFetchThreads = kThreads - kWave;   // waves 1.. issue the prefetch
+constexpr uint32_t kSpinLimit = 1u << 24;         // bounded wait: a lost workgroup ends in ZIPML_ETIMEOUT
+
+enum Mode { kAffine = 0, kTable = 1, kInt = 2 };
 
 struct SgdArgs {
     const uint32_t *p1, *p2;
@@ -28,7 +39,7 @@ struct SgdArgs {
     const uint16_t *grid;
     const float *b;
     float *x;
-    int64_t n_pad, n32;
+    int64_t nb64, n32;     // sample blocks of copy 2 (64 rows), sample groups of copy 1 (32 rows)
     int d, d32;
     int B;                 // batch
     int64_t step0;         // first step of this launch
@@ -39,53 +50,55 @@ struct SgdArgs {
     uint64_t seed;
     uint32_t epoch;
     int GQ, W;             // feature groups per workgroup, workgroups
+    int lds_levels;        // the workgroup's slice of the level table fits in LDS
     int seg_first, seg_last;   // segments of a step run by this launch (0..3)
     int persistent;        // 1: segments are separated by in-kernel grid barriers
-    int depth;             // LDS slots for packed data
     int slot_bytes;
     // workspace
     int *status;
     uint32_t *sync;
-    double *nrm;           // [2 kinds][2 slots][512]
+    double *nrm;           // [2 kinds][2 slots][512] (+ 1024 spare)
     float *acc;            // [3][acc_words]
     int acc_words;
-    float *gbuf;           // [d_pad] gradient carried between launches (stepwise, grad_bits > 0)
+    float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     // debug outputs (may be null)
     int32_t *dbg_m, *dbg_acc, *dbg_gq;
     float *dbg_r, *dbg_g;
 };
 
-// ---------------------------------------------------------------------------------------------
-// Grid-wide barrier: one monotonically increasing arrival counter.  Data exchanged across it is
-// written and read with device-scope accesses only (add_dev / store_dev / load_dev).
-// ---------------------------------------------------------------------------------------------
-struct GridBarrier {
-    uint32_t *ctr;
-    int *status;
-    uint32_t W;
-    uint32_t passed;   // barriers completed so far
-    bool dead;
-
-    __device__ void arrive_and_wait()
-    {
-        release_dev();           // this wave's device-scope writes are performed
-        __syncthreads();
-        ++passed;
-        if (threadIdx.x == 0) {
-            add_dev(ctr, 1u);
-            const uint32_t target = passed * W;
-            uint32_t spins = 0;
-            while (!dead && load_dev(ctr) < target) {
-                __builtin_amdgcn_s_sleep(1);
-                if (++spins > kSpinLimit) {
-                    store_dev(status, (int)ZIPML_ETIMEOUT);
-                    dead = true;
-                }
-            }
-        }
-        __syncthreads();
-    }
+// LDS arrays of one workgroup.
+struct Lds {
+    uint32_t *ring;   // two packed-data slots
+    float *Ls;        // level slice [CW][K]        (lds_levels only)
+    uint16_t *Gs;     // grid-index slice [CW][K]   (integer mode with a non-identity grid)
+    float *xs, *ys, *los, *dls, *gs;   // model slice, delta*x, lo, delta, gradient slice  [CW]
+    int *ms;          // model codes [CW]
+    float *rs;        // residuals [Rlen]
+    float *zl;        // local dot products [B+4]   (single workgroup only)
+    float *gpart;     // gradient partial sums [kThreads]
+    double *red;      // reduction scratch [512]
+    float *wsum;      // [0..kWaves): residual sum parts, [kWaves..2kWaves): parts of sum_j lo_j x_j
+    int *isum;        // [kWaves]
 };
+
+// Optional per-phase timing of workgroup 0 (development builds only: -DZIPML_PHASE_TIMING).
+#ifdef ZIPML_PHASE_TIMING
+#define ZIPML_TICK(k)                                                      \
+    do {                                                                   \
+        if (w == 0 && tid == 0) {                                          \
+            const long long now_ = wall_clock64();                         \
+            prof_[k] += now_ - last_;                                      \
+            last_ = now_;                                                  \
+        }                                                                  \
+    } while (0)
+#else
+#define ZIPML_TICK(k) do { } while (0)
+#endif
+
+__device__ __forceinline__ void vm_wait_all()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads, stores and atomics are done
+}
 
 // Adjacent-pair tree sum of `len` (power of two) doubles in LDS; result in a[0].
 __device__ __forceinline__ void lds_tree_sum(double *a, int len)
@@ -112,15 +125,16 @@ __device__ __forceinline__ int qvec_code(float v, float M, int s, float u)
     return v < 0.0f ? -mag : mag;
 }
 
-// Asynchronous copy of `dwords` (multiple of 4) dwords from global to LDS, 16 B per lane,
-// issued by the whole workgroup.  Completion: s_waitcnt vmcnt(0) in every wave, then a barrier.
+// Asynchronous copy of `dwords` (multiple of 4) dwords from global to LDS, 16 B per lane, issued by
+// waves 1.. of the workgroup.  Completion: vm_wait_all() in those waves, then a barrier.
 __device__ __forceinline__ void async_copy(const uint32_t *__restrict__ src, uint32_t *dst_lds,
                                            int dwords)
 {
     const int chunks = dwords >> 2;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave_first = threadIdx.x - lane;
-    for (int c0 = 0; c0 < chunks; c0 += kThreads) {
+    const int ft = (int)threadIdx.x - kWave;          // 0 .. kFetchThreads-1
+    const int lane = ft & (kWave - 1);
+    const int wave_first = ft - lane;
+    for (int c0 = 0; c0 < chunks; c0 += kFetchThreads) {
         const int c = c0 + wave_first + lane;
         if (c0 + wave_first < chunks) {
             uint32_t *wave_dst = dst_lds + (size_t)(c0 + wave_first) * 4;
@@ -132,139 +146,205 @@ __device__ __forceinline__ void async_copy(const uint32_t *__restrict__ src, uin
     }
 }
 
-__device__ __forceinline__ void async_wait_all()
-{
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
-}
-
+// One packed unit from the dword-planar LDS slot: dword q sits `stride` dwords after dword q-1.
 template <int BITS>
-__device__ __forceinline__ void lds_unit(const uint32_t *p, uint32_t (&u)[BITS])
+__device__ __forceinline__ void planar_unit(const uint32_t *p, int stride, uint32_t (&u)[BITS])
 {
 #pragma unroll
-    for (int q = 0; q < BITS; ++q) u[q] = p[q];
+    for (int q = 0; q < BITS; ++q) u[q] = p[q * stride];
+}
+
+// ---- inner loops over the 32 codes of a unit (v: 32 wave-uniform fp32/int32 values in LDS) ----
+template <int BITS>
+__device__ __forceinline__ float unit_fma_codes(const uint32_t (&u)[BITS], const float *v, float acc)
+{
+    // all 32 broadcast values first (8 LDS reads in flight), then four independent fma chains
+    const float4 *v4 = reinterpret_cast<const float4 *>(v);
+    float4 y[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) y[m] = v4[m];
+    float a0 = acc, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+        a0 = fmaf((float)unit_code<BITS>(u, 4 * m + 0), y[m].x, a0);
+        a1 = fmaf((float)unit_code<BITS>(u, 4 * m + 1), y[m].y, a1);
+        a2 = fmaf((float)unit_code<BITS>(u, 4 * m + 2), y[m].z, a2);
+        a3 = fmaf((float)unit_code<BITS>(u, 4 * m + 3), y[m].w, a3);
+    }
+    return (a0 + a1) + (a2 + a3);
+}
+
+// Dot pass, table levels: acc += L[feature jb+k][code_k] * x[jb+k].  L points at feature jb.
+template <int BITS>
+__device__ __forceinline__ float unit_dot_table(const uint32_t (&u)[BITS], const float *L,
+                                                const float *x, float acc)
+{
+    constexpr int K = 1 << BITS;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) acc = fmaf(L[k * K + unit_code<BITS>(u, k)], x[k], acc);
+    return acc;
+}
+
+// Gradient pass, table levels: acc = fma(L[code_k], r[k], acc) for k = 0..31 in this order.
+// L points at the levels of the one feature this unit belongs to.
+template <int BITS>
+__device__ __forceinline__ float unit_grad_table(const uint32_t (&u)[BITS], const float *L,
+                                                 const float *r, float acc)
+{
+#pragma unroll
+    for (int k = 0; k < 32; ++k) acc = fmaf(L[unit_code<BITS>(u, k)], r[k], acc);
+    return acc;
+}
+
+// Integer dot pass: acc += G[jb+k][code_k] * m[jb+k]; G == nullptr means the identity grid.
+template <int BITS>
+__device__ __forceinline__ int unit_dot_int(const uint32_t (&u)[BITS], const uint16_t *G,
+                                            const int *m, int acc)
+{
+    constexpr int K = 1 << BITS;
+    if (G) {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) acc += (int)G[k * K + unit_code<BITS>(u, k)] * m[k];
+    } else {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) acc += (int)unit_code<BITS>(u, k) * m[k];
+    }
+    return acc;
 }
 
 // ---------------------------------------------------------------------------------------------
-// The epoch kernel.
+// The step loop, specialised on how a code becomes a value.
 // ---------------------------------------------------------------------------------------------
-template <int BITS>
-__global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
+// FAST: the production configuration (whole steps inside one persistent launch, no debug
+// outputs); everything that only the stepwise / debug launches need folds away at compile time.
+template <int BITS, int MODE, bool FAST>
+__device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 {
     constexpr int K = 1 << BITS;
-    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr bool kIsInt = MODE == kInt;
+    const bool persistent = FAST ? true : a.persistent != 0;
+    const int seg_first = FAST ? 0 : a.seg_first;
+    const int seg_last = FAST ? 3 : a.seg_last;
+    int32_t *const dbg_m = FAST ? nullptr : a.dbg_m;
+    int32_t *const dbg_acc = FAST ? nullptr : a.dbg_acc;
+    int32_t *const dbg_gq = FAST ? nullptr : a.dbg_gq;
+    float *const dbg_r = FAST ? nullptr : a.dbg_r;
+    float *const dbg_g = FAST ? nullptr : a.dbg_g;
     const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
     const int w = blockIdx.x;
-    const int CW = 32 * a.GQ;
+    const int W = a.W;
+    const int GQ = a.GQ;
+    const int CW = 32 * GQ;
     const int B = a.B;
-    const int nrg = B >= 32 ? B / 32 : 1;          // sample groups per step
-    const int Rlen = nrg * 32;                     // residual slots (zero outside the batch)
-    const bool int_mode = a.model_bits > 0;
-    const bool seq_grad = int_mode;                // gradient in a fixed fp32 order
+    const int nrg = B >= 32 ? B / 32 : 1;          // sample groups of copy 1 per step
+    const int nblk = (B + 63) / 64;                // sample blocks of copy 2 per step
+    const bool solo = W == 1;
+    const bool local = solo && persistent;         // no other workgroup or launch: all stays in LDS
+    const bool grid_sync = persistent && !solo;
     const int j0 = w * CW;                         // first feature of this workgroup
+    const int ngroups = (a.d32 - w * GQ) < GQ ? (a.d32 - w * GQ) : GQ;   // owned feature groups
+    const float *Lg = a.levels + (size_t)j0 * K;   // global view of the owned level slice
+    float *const xs = L.xs, *const ys = L.ys, *const gs = L.gs, *const rs = L.rs;
+    double *const red = L.red;
 
-    // ---- LDS carve
-    size_t off = 0;
-    auto carve = [&](size_t bytes) { void *p = smem + off; off += (bytes + 15) & ~(size_t)15; return p; };
-    // the packed-data slots come first so that their LDS addresses stay below 64 KiB
-    uint32_t *ring = (uint32_t *)carve((size_t)a.depth * a.slot_bytes);
-    float *Ls = (float *)carve((size_t)CW * K * 4);
-    uint16_t *Gs = (uint16_t *)carve(int_mode && !a.ident_grid ? (size_t)CW * K * 2 : 0);
-    float *xs = (float *)carve(CW * 4);
-    float *ys = (float *)carve(CW * 4);
-    float *los = (float *)carve(CW * 4);
-    float *dls = (float *)carve(CW * 4);
-    float *gs = (float *)carve(CW * 4);
-    int *ms = (int *)carve(CW * 4);
-    float *rs = (float *)carve((size_t)Rlen * 4);
-    float *gpart = (float *)carve(kThreads * 4);
-    double *red = (double *)carve(512 * 8);
-    float *fscr = (float *)carve(16 * 4);
-
-    // ---- one-time set-up: level slice, model slice
-    for (int e = tid; e < CW * K; e += kThreads) {
-        const int jj = e / K, j = j0 + jj;
-        Ls[e] = j < a.d ? a.levels[(size_t)j * K + (e % K)] : 0.0f;
-        if (int_mode && !a.ident_grid) Gs[e] = j < a.d ? a.grid[(size_t)j * K + (e % K)] : (uint16_t)0;
-    }
-    for (int c = tid; c < CW; c += kThreads) xs[c] = (j0 + c < a.d) ? a.x[j0 + c] : 0.0f;
-    __syncthreads();
-    // Are the levels of every owned feature evenly spaced (fp64 formula, rounded once)?  Then a
-    // value is lo + code * delta and the table look-up is replaced by arithmetic.
-    int ok = 1;
-    for (int e = tid; e < CW * K; e += kThreads) {
-        const int jj = e / K, c = e % K;
-        const double lo = (double)Ls[jj * K], wdt = (double)Ls[jj * K + K - 1] - lo;
-        ok &= (Ls[e] == (float)(lo + ((double)c * wdt) / (double)(K - 1)));
-    }
-    const bool affine = __syncthreads_and(ok) && !int_mode;
-    for (int c = tid; c < CW; c += kThreads) {
-        los[c] = Ls[c * K];
-        dls[c] = (float)(((double)Ls[c * K + K - 1] - (double)Ls[c * K]) / (double)(K - 1));
-        ys[c] = dls[c] * xs[c];
-        gs[c] = 0.0f;
-        ms[c] = 0;
-    }
-    for (int i = tid; i < Rlen; i += kThreads) rs[i] = 0.0f;
-    __syncthreads();
-    float Cq = 0.0f;   // sum_j lo_j x_j over the owned features (affine mode)
-    if (affine) Cq = block_sum<float>(tid < CW ? los[tid] * xs[tid] : 0.0f, fscr);
-
-    GridBarrier bar{a.sync, a.status, (uint32_t)a.W, 0u, false};
-
-    // ---- packed-data slots
-    const int r2_dw = B * BITS;                 // one feature group of copy 2 for one step
-    const int r1_dw = nrg * 32 * BITS;          // one feature group of copy 1 for one step
-    const int b_dw = (B + 3) & ~3;
-    const int slot_dw = a.slot_bytes / 4;
-    auto fetch = [&](int64_t t, int slot) {
-        uint32_t *s = ring + (size_t)slot * slot_dw;
-        for (int gq = 0; gq < a.GQ; ++gq) {
-            const int64_t g = (int64_t)w * a.GQ + gq;
-            if (g >= a.d32) break;
-            async_copy(a.p2 + (g * a.n_pad + t * B) * BITS, s + gq * r2_dw, r2_dw);
-            async_copy(a.p1 + ((g * a.n32 + (t * B) / 32) * 32) * BITS,
-                       s + a.GQ * r2_dw + gq * r1_dw, r1_dw);
+    // ---- grid barrier state (one monotonically increasing arrival counter)
+    uint32_t passed = 0;
+    bool dead = false;
+    auto arrive_and_poll = [&]() {   // lane 0 of wave 0, after the workgroup's atomics are done
+        ++passed;
+        add_dev(a.sync, 1u);
+        const uint32_t target = passed * (uint32_t)W;
+        uint32_t spins = 0;
+#pragma unroll 1
+        while (!dead && load_dev(a.sync) < target) {
+            if (++spins > kSpinLimit) {
+                store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                dead = true;
+            }
         }
-        async_copy((const uint32_t *)(a.b + t * B), s + a.GQ * (r2_dw + r1_dw), b_dw);
+    };
+
+    // ---- packed-data slots: [GQ][nblk][BITS][64] copy 2 | [GQ][nrg][BITS][32] copy 1 | labels
+    const int r2_dw = nblk * 64 * BITS;
+    const int r1_dw = nrg * 32 * BITS;
+    const int slot_dw = a.slot_bytes / 4;
+    auto fetch = [&](int64_t t, int slot) {     // waves 1.. only
+        uint32_t *s = L.ring + (size_t)slot * slot_dw;
+        const int64_t row = t * B;
+        for (int gq = 0; gq < ngroups; ++gq) {
+            const int64_t g = (int64_t)w * GQ + gq;
+            async_copy(a.p2 + ((g * a.nb64 + row / 64) * BITS) * 64, s + gq * r2_dw, r2_dw);
+            async_copy(a.p1 + ((g * a.n32 + row / 32) * BITS) * 32, s + GQ * r2_dw + gq * r1_dw, r1_dw);
+        }
+        async_copy((const uint32_t *)(a.b + row), s + GQ * (r2_dw + r1_dw), (B + 3) & ~3);
     };
     const int64_t t_end = a.step0 + a.nsteps;
-    fetch(a.step0, 0);
+#ifdef ZIPML_PHASE_TIMING
+    long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long last_ = wall_clock64();
+#endif
+    if (wave > 0) fetch(a.step0, 0);
+    int Wp = 1;
+    while (Wp < W) Wp <<= 1;
+    const int s_m = (1 << (a.model_bits > 0 ? a.model_bits - 1 : 1)) - 1;
+
+    // Combine the W per-workgroup sums of squares (fixed tree) into an fp32 l2 norm.
+    auto combined_norm = [&](const double *part, double own) -> float {
+        if (local) return (float)sqrt(own);
+        if (wave == 0)
+            for (int i = lane; i < Wp; i += kWave) red[i] = i < W ? load_dev(part + i) : 0.0;
+        lds_tree_sum(red, Wp);
+        const float M = (float)sqrt(red[0]);
+        __syncthreads();
+        return M;
+    };
 
     for (int64_t t = a.step0; t < t_end; ++t) {
-        const int it = (int)(t - a.step0);
-        const int slot = it % a.depth;
-        const uint32_t *S = ring + (size_t)slot * slot_dw;
-        const uint32_t *S2 = S, *S1 = S + a.GQ * r2_dw;
-        const float *bS = (const float *)(S + a.GQ * (r2_dw + r1_dw));
+        const int slot = (int)(t - a.step0) & 1;
+        const uint32_t *S2 = L.ring + (size_t)slot * slot_dw;
+        const uint32_t *S1 = S2 + GQ * r2_dw;
+        const float *bS = (const float *)(S1 + GQ * r1_dw);
         float *accf = a.acc + (size_t)(t % 3) * a.acc_words;
         int *acci = (int *)accf;
+        const int roff = (int)((t * B) % 64);              // first batch row inside the fetched blocks
+        const int k0 = B >= 32 ? 0 : (int)((t * B) % 32);  // ... inside the fetched sample group
+        bool prefetched = !(persistent && t + 1 < t_end);   // nothing (more) to prefetch this step
+        auto prefetch_once = [&]() {
+            if (!prefetched && wave > 0) fetch(t + 1, slot ^ 1);
+            prefetched = true;
+        };
 
-        async_wait_all();                                    // slot `slot` has landed
-        if (a.persistent && t + 1 < t_end) fetch(t + 1, (it + 1) % a.depth);
+        ZIPML_TICK(7);
+        vm_wait_all();       // this step's slot has landed (issued during the previous step)
+        __syncthreads();     // ... and the model slice written at the end of the previous step is visible
+        ZIPML_TICK(0);
 
         // ================= segment 0: ||x||_2 partial (model quantisation only) =================
         float Mx = 0.0f, sigma = 0.0f;
-        const int s_m = (1 << (a.model_bits > 0 ? a.model_bits - 1 : 1)) - 1;
+        double own_sq = 0.0;
         double *nx = a.nrm + (size_t)(t & 1) * 512;
-        if (int_mode && a.seg_first <= 0) {
+        if (kIsInt && seg_first <= 0) {
             if (tid < CW) red[tid] = (double)xs[tid] * (double)xs[tid];
             lds_tree_sum(red, CW);
-            if (tid == 0) store_dev(nx + w, red[0]);
-            if (a.persistent) bar.arrive_and_wait();
+            own_sq = red[0];
+            __syncthreads();
+            if (!local && tid == 0) store_dev(nx + w, own_sq);
+            if (grid_sync) {
+                vm_wait_all();
+                __syncthreads();
+                if (wave == 0) { if (lane == 0) arrive_and_poll(); }
+                else prefetch_once();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // no load moves above the poll
+            }
         }
-        if (a.seg_last < 1) continue;
+        if (seg_last < 1) continue;
 
         // ================= segment 1: model codes, dot pass =====================================
-        if (a.seg_first <= 1) {
-            if (int_mode) {
-                int Wp = 1;
-                while (Wp < a.W) Wp <<= 1;
-                for (int i = tid; i < Wp; i += kThreads) red[i] = i < a.W ? load_dev(nx + i) : 0.0;
-                lds_tree_sum(red, Wp);
-                Mx = (float)sqrt(red[0]);
+        if (seg_first <= 1) {
+            if (kIsInt) {
+                Mx = combined_norm(nx, own_sq);
                 sigma = Mx > 0.0f ? __fdiv_rn(Mx, (float)s_m) : 0.0f;
-                __syncthreads();
                 int mine = 0;
                 if (tid < CW) {
                     const int j = j0 + tid;
@@ -272,101 +352,142 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
                         const Philox4 r = philox_block(a.seed, a.epoch, (uint64_t)t, (uint32_t)j >> 2, 3u);
                         mine = qvec_code(xs[tid], Mx, s_m, u24(r.w[j & 3]));
                     }
-                    ms[tid] = mine;
-                    if (a.dbg_m && j < a.d) a.dbg_m[j] = mine;
+                    L.ms[tid] = mine;
+                    if (dbg_m && j < a.d) dbg_m[j] = mine;
                 }
-                const int part = block_sum<int>(mine, (int *)fscr);   // also publishes ms[]
-                if (tid == 0 && part != 0) add_dev(acci + B, part);
+                const int part = wave_sum_dpp(mine);
+                if (lane == 0) L.isum[wave] = part;
+                __syncthreads();   // publishes ms[] and isum[]
+                if (tid == 0) {
+                    int tot = 0;
+                    for (int q = 0; q < kWaves; ++q) tot += L.isum[q];
+                    if (local) ((int *)L.zl)[B] = tot;
+                    else if (tot != 0) add_dev(acci + B, tot);
+                }
             }
             // dot pass: one sample per thread, all owned feature groups
+            float Cq = 0.0f;
+            if (MODE == kAffine)
+                for (int q = 0; q < kWaves; ++q) Cq += L.wsum[kWaves + q];
             for (int i = tid; i < B; i += kThreads) {
+                const int r = roff + i;
+                const uint32_t *row = S2 + (r >> 6) * (64 * BITS) + (r & 63);
                 float pf = Cq;
                 int pi = 0;
-                for (int gq = 0; gq < a.GQ; ++gq) {
-                    if ((int64_t)w * a.GQ + gq >= a.d32) break;
+                for (int gq = 0; gq < ngroups; ++gq) {
                     uint32_t u[BITS];
-                    lds_unit<BITS>(S2 + (size_t)(gq * B + i) * BITS, u);
+                    planar_unit<BITS>(row + gq * r2_dw, 64, u);
                     const int jb = gq * 32;
+                    if (MODE == kAffine) {
+                        pf = unit_fma_codes<BITS>(u, ys + jb, pf);
+                    } else if (MODE == kTable) {
+                        if (a.lds_levels) pf = unit_dot_table<BITS>(u, L.Ls + jb * K, xs + jb, pf);
+                        else pf = unit_dot_table<BITS>(u, Lg + (size_t)jb * K, xs + jb, pf);
+                    } else {
+                        pi = unit_dot_int<BITS>(u, a.ident_grid ? nullptr : L.Gs + jb * K, L.ms + jb, pi);
+                    }
+                }
+                if (local) {
+                    if (kIsInt) ((int *)L.zl)[i] = pi; else L.zl[i] = pf;
+                } else {
+                    if (kIsInt) add_dev(acci + i, pi); else add_dev(accf + i, pf);
+                }
+            }
+            ZIPML_TICK(1);
+            if (grid_sync) {
+                vm_wait_all();      // this wave's atomics have been performed
+                __syncthreads();    // ... and so have those of the whole workgroup
+                ZIPML_TICK(2);
+                if (wave == 0) { if (lane == 0) arrive_and_poll(); }
+                else prefetch_once();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // no load moves above the poll
+            } else {
+                prefetch_once();
+            }
+        }
+        if (seg_last < 2) continue;
+
+        // ================= segment 2: residuals, gradient pass ==================================
+        if (seg_first <= 2) {
+            if (kIsInt && seg_first == 2) {
+                // stepwise launch: recompute the scale of the model quantiser
+                Mx = combined_norm(nx, 0.0);
+                sigma = Mx > 0.0f ? __fdiv_rn(Mx, (float)s_m) : 0.0f;
+            }
+            ZIPML_TICK(3);
+            // wave 0 (no prefetch in flight) reads the sums and forms the residuals
+            if (local) __syncthreads();   // zl[] written by all waves
+            if (wave == 0 || local) {
+                double summ = 0.0;
+                if (kIsInt) summ = local ? (double)((int *)L.zl)[B] : (double)load_dev(acci + B);
+                float rsum = 0.0f;
+                const int stride = local ? kThreads : kWave;
+                constexpr int kBatchLoads = 4;   // device-scope loads in flight per lane
+                for (int base = local ? tid : lane; base < B; base += stride * kBatchLoads) {
+                    // issue all loads first: each costs a full trip to the coherence point
+                    uint32_t raw[kBatchLoads];
 #pragma unroll
-                    for (int k = 0; k < 32; ++k) {
-                        const uint32_t code = unit_code<BITS>(u, k);
-                        if (int_mode) {
-                            const int gidx = a.ident_grid ? (int)code : (int)Gs[(jb + k) * K + code];
-                            pi += gidx * ms[jb + k];
-                        } else if (affine) {
-                            pf = fmaf((float)code, ys[jb + k], pf);
-                        } else {
-                            pf = fmaf(Ls[(jb + k) * K + code], xs[jb + k], pf);
+                    for (int q = 0; q < kBatchLoads; ++q) {
+                        const int i = base + q * stride;
+                        raw[q] = 0u;
+                        if (i < B) {
+                            if (local) raw[q] = ((const uint32_t *)L.zl)[i];
+                            else raw[q] = load_dev((const uint32_t *)accf + i);
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < kBatchLoads; ++q) {
+                        const int i = base + q * stride;
+                        if (i < B) {
+                            float r;
+                            if (kIsInt) {
+                                const int av = (int)raw[q];
+                                const double z = (double)sigma * ((double)a.grid_lo * summ +
+                                                                  (double)a.grid_step * (double)av);
+                                r = (float)z - bS[i];
+                                if (dbg_acc && w == 0) dbg_acc[i] = av;
+                            } else {
+                                r = __uint_as_float(raw[q]) - bS[i];
+                            }
+                            rs[k0 + i] = r;
+                            rsum += r;
+                            if (dbg_r && w == 0) dbg_r[i] = r;
                         }
                     }
                 }
-                if (int_mode) add_dev(acci + i, pi);
-                else add_dev(accf + i, pf);
-            }
-            if (a.persistent) bar.arrive_and_wait();
-        }
-        if (a.seg_last < 2) continue;
-
-        // ================= segment 2: residuals, gradient pass ==================================
-        if (a.seg_first <= 2) {
-            if (int_mode && a.seg_first == 2) {
-                // stepwise launch: recompute the scale of the model quantiser
-                int Wp = 1;
-                while (Wp < a.W) Wp <<= 1;
-                for (int i = tid; i < Wp; i += kThreads) red[i] = i < a.W ? load_dev(nx + i) : 0.0;
-                lds_tree_sum(red, Wp);
-                Mx = (float)sqrt(red[0]);
-                sigma = Mx > 0.0f ? __fdiv_rn(Mx, (float)s_m) : 0.0f;
-                __syncthreads();
-            }
-            // the accumulator of step t+2 is free once every workgroup has passed this point of
-            // step t-1; workgroup 0 clears it now
-            if (a.persistent && w == 0) {
-                float *nxt = a.acc + (size_t)((t + 2) % 3) * a.acc_words;
-                for (int i = tid; i < B + 1; i += kThreads) store_dev(nxt + i, 0.0f);
-            }
-            const int k0 = B >= 32 ? 0 : (int)((t * B) % 32);   // batch offset inside the sample group
-            double summ = 0.0;
-            if (int_mode) summ = (double)load_dev(acci + B);
-            float rsum = 0.0f;
-            for (int i = tid; i < B; i += kThreads) {
-                float r;
-                if (int_mode) {
-                    const int av = load_dev(acci + i);
-                    const double z = (double)sigma * ((double)a.grid_lo * summ +
-                                                      (double)a.grid_step * (double)av);
-                    r = (float)z - bS[i];
-                    if (a.dbg_acc && w == 0) a.dbg_acc[i] = av;
-                } else {
-                    r = load_dev(accf + i) - bS[i];
+                if (MODE == kAffine) {
+                    rsum = wave_sum_dpp(rsum);
+                    if (lane == 0) L.wsum[wave] = rsum;
+                    if (!local && lane == 0)
+                        for (int q = 1; q < kWaves; ++q) L.wsum[q] = 0.0f;
                 }
-                rs[k0 + i] = r;
-                rsum += r;
-                if (a.dbg_r && w == 0) a.dbg_r[i] = r;
+                // the accumulator of step t+2 is free once every workgroup has passed the barrier
+                // of step t; workgroup 0 clears it now
+                if (grid_sync && w == 0) {
+                    float *nxt = a.acc + (size_t)((t + 2) % 3) * a.acc_words;
+                    for (int i = lane; i < B + 1; i += kWave) store_dev(nxt + i, 0.0f);
+                }
             }
-            float Rtot = 0.0f;
-            if (affine) Rtot = block_sum<float>(rsum, fscr);
-            __syncthreads();
+            __syncthreads();    // rs[], wsum[] ready
+            ZIPML_TICK(4);
 
-            if (seq_grad) {
+            if (kIsInt) {
                 // fixed order: one feature per thread, samples in batch order, fp32 fma chain
                 if (tid < CW) {
                     const int gq = tid >> 5, cin = tid & 31;
                     float acc = 0.0f;
-                    if ((int64_t)w * a.GQ + gq < a.d32) {
+                    if (gq < ngroups) {
+                        const uint32_t *col = S1 + gq * r1_dw + cin;
                         for (int rgl = 0; rgl < nrg; ++rgl) {
                             uint32_t u[BITS];
-                            lds_unit<BITS>(S1 + (size_t)gq * r1_dw + (size_t)(rgl * 32 + cin) * BITS, u);
-#pragma unroll
-                            for (int k = 0; k < 32; ++k) {
-                                if (B < 32 && (k < k0 || k >= k0 + B)) continue;
-                                acc = fmaf(Ls[tid * K + unit_code<BITS>(u, k)], rs[rgl * 32 + k], acc);
-                            }
+                            planar_unit<BITS>(col + rgl * (32 * BITS), 32, u);
+                            if (a.lds_levels) acc = unit_grad_table<BITS>(u, L.Ls + tid * K, rs + rgl * 32, acc);
+                            else acc = unit_grad_table<BITS>(u, Lg + (size_t)tid * K, rs + rgl * 32, acc);
                         }
                     }
                     const float g = (j0 + tid < a.d) ? __fdiv_rn(acc, (float)B) : 0.0f;
                     gs[tid] = g;
-                    if (a.dbg_g && j0 + tid < a.d) a.dbg_g[j0 + tid] = g;
+                    if (dbg_g && j0 + tid < a.d) dbg_g[j0 + tid] = g;
                 }
             } else {
                 // free order: (feature, slice of the sample groups) per thread, then reduce slices
@@ -374,85 +495,182 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
                 const int c = tid % CW, sl = tid / CW;
                 const int gq = c >> 5, cin = c & 31;
                 float acc = 0.0f;
-                if (sl < nsl && (int64_t)w * a.GQ + gq < a.d32) {
+                if (gq < ngroups) {
+                    const uint32_t *col = S1 + gq * r1_dw + cin;
                     for (int rgl = sl; rgl < nrg; rgl += nsl) {
                         uint32_t u[BITS];
-                        lds_unit<BITS>(S1 + (size_t)gq * r1_dw + (size_t)(rgl * 32 + cin) * BITS, u);
-                        const float *rr = rs + rgl * 32;
-#pragma unroll
-                        for (int k = 0; k < 32; ++k) {
-                            const uint32_t code = unit_code<BITS>(u, k);
-                            if (affine) acc = fmaf((float)code, rr[k], acc);
-                            else acc = fmaf(Ls[c * K + code], rr[k], acc);
-                        }
+                        planar_unit<BITS>(col + rgl * (32 * BITS), 32, u);
+                        if (MODE == kAffine) acc = unit_fma_codes<BITS>(u, rs + rgl * 32, acc);
+                        else if (a.lds_levels) acc = unit_grad_table<BITS>(u, L.Ls + c * K, rs + rgl * 32, acc);
+                        else acc = unit_grad_table<BITS>(u, Lg + (size_t)c * K, rs + rgl * 32, acc);
                     }
                 }
-                gpart[tid] = acc;
+                L.gpart[tid] = acc;
                 __syncthreads();
                 if (tid < CW) {
                     float sacc = 0.0f;
-                    for (int q = 0; q < nsl; ++q) sacc += gpart[q * CW + tid];
-                    float g = affine ? (los[tid] * Rtot + dls[tid] * sacc) : sacc;
+                    for (int q = 0; q < nsl; ++q) sacc += L.gpart[q * CW + tid];
+                    float g = sacc;
+                    if (MODE == kAffine) {
+                        float Rtot = 0.0f;
+                        for (int q = 0; q < kWaves; ++q) Rtot += L.wsum[q];
+                        g = L.los[tid] * Rtot + L.dls[tid] * sacc;
+                    }
                     g = (j0 + tid < a.d) ? g / (float)B : 0.0f;
                     gs[tid] = g;
-                    if (a.dbg_g && j0 + tid < a.d) a.dbg_g[j0 + tid] = g;
+                    if (dbg_g && j0 + tid < a.d) dbg_g[j0 + tid] = g;
                 }
             }
-            __syncthreads();
-            // clear the residual slots that belong to this (short) batch for the next step
-            if (B < 32) for (int i = tid; i < B; i += kThreads) rs[k0 + i] = 0.0f;
+            if (B < 32) {
+                // a short batch shares its sample group with its neighbours: clear its residuals
+                __syncthreads();
+                for (int i = tid; i < B; i += kThreads) rs[k0 + i] = 0.0f;
+            }
             if (a.grad_bits > 0) {
                 double *ng = a.nrm + 1024 + (size_t)(t & 1) * 512;
+                __syncthreads();
                 if (tid < CW) red[tid] = (double)gs[tid] * (double)gs[tid];
                 lds_tree_sum(red, CW);
-                if (tid == 0) store_dev(ng + w, red[0]);
-                if (!a.persistent && tid < CW && j0 + tid < a.d) a.gbuf[j0 + tid] = gs[tid];
-                if (a.persistent) bar.arrive_and_wait();
+                own_sq = red[0];
+                __syncthreads();
+                if (!local && tid == 0) store_dev(ng + w, own_sq);
+                if (!persistent && tid < CW && j0 + tid < a.d) a.gbuf[j0 + tid] = gs[tid];
+                if (grid_sync) {
+                    vm_wait_all();
+                    __syncthreads();
+                    if (wave == 0 && lane == 0) arrive_and_poll();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                }
             }
         }
-        if (a.seg_last < 3) continue;
+        ZIPML_TICK(5);
+        if (seg_last < 3) continue;
 
         // ================= segment 3: gradient quantisation, update ==============================
-        {
-            if (a.grad_bits > 0) {
-                if (!a.persistent && a.seg_first == 3 && tid < CW)
-                    gs[tid] = (j0 + tid < a.d) ? a.gbuf[j0 + tid] : 0.0f;
-                double *ng = a.nrm + 1024 + (size_t)(t & 1) * 512;
-                int Wp = 1;
-                while (Wp < a.W) Wp <<= 1;
-                __syncthreads();
-                for (int i = tid; i < Wp; i += kThreads) red[i] = i < a.W ? load_dev(ng + i) : 0.0;
-                lds_tree_sum(red, Wp);
-                const float Mg = (float)sqrt(red[0]);
-                const int s_g = (1 << (a.grad_bits - 1)) - 1;
-                const float sg = Mg > 0.0f ? __fdiv_rn(Mg, (float)s_g) : 0.0f;
-                if (tid < CW) {
-                    const int j = j0 + tid;
-                    if (j < a.d) {
-                        const Philox4 r = philox_block(a.seed, a.epoch, (uint64_t)t, (uint32_t)j >> 2, 4u);
-                        const int code = qvec_code(gs[tid], Mg, s_g, u24(r.w[j & 3]));
-                        if (a.dbg_gq) a.dbg_gq[j] = code;
-                        const float gh = sg * (float)code;
-                        const float stp = a.lr * gh;
-                        xs[tid] = xs[tid] - stp;
-                    }
+        if (a.grad_bits > 0) {
+            if (!persistent && seg_first == 3 && tid < CW)
+                gs[tid] = (j0 + tid < a.d) ? a.gbuf[j0 + tid] : 0.0f;
+            double *ng = a.nrm + 1024 + (size_t)(t & 1) * 512;
+            const float Mg = combined_norm(ng, own_sq);
+            const int s_g = (1 << (a.grad_bits - 1)) - 1;
+            const float sg = Mg > 0.0f ? __fdiv_rn(Mg, (float)s_g) : 0.0f;
+            if (tid < CW) {
+                const int j = j0 + tid;
+                if (j < a.d) {
+                    const Philox4 r = philox_block(a.seed, a.epoch, (uint64_t)t, (uint32_t)j >> 2, 4u);
+                    const int code = qvec_code(gs[tid], Mg, s_g, u24(r.w[j & 3]));
+                    if (dbg_gq) dbg_gq[j] = code;
+                    const float gh = sg * (float)code;
+                    const float stp = a.lr * gh;
+                    xs[tid] = xs[tid] - stp;
                 }
-            } else if (tid < CW) {
-                const float stp = a.lr * gs[tid];
-                xs[tid] = xs[tid] - stp;
             }
-            __syncthreads();
-            if (affine) {
-                if (tid < CW) ys[tid] = dls[tid] * xs[tid];
-                Cq = block_sum<float>(tid < CW ? los[tid] * xs[tid] : 0.0f, fscr);
+        } else if (tid < CW) {
+            const float stp = a.lr * gs[tid];
+            xs[tid] = xs[tid] - stp;
+        }
+        if (MODE == kAffine) {
+            // the owner threads refresh y = delta * x and the per-wave parts of sum_j lo_j x_j
+            float part = 0.0f;
+            if (tid < CW) {
+                ys[tid] = L.dls[tid] * xs[tid];
+                part = L.los[tid] * xs[tid];
             }
-            __syncthreads();
+            part = wave_sum_dpp(part);
+            if (lane == 0) L.wsum[kWaves + wave] = part;
+        }
+        // the barrier at the top of the next step publishes xs, ys, wsum
+        ZIPML_TICK(6);
+    }
+    __syncthreads();
+#ifdef ZIPML_PHASE_TIMING
+    if (w == 0 && tid == 0)
+        for (int k = 0; k < 8; ++k) ((long long *)(a.nrm + 2048))[k] = prof_[k];
+#endif
+}
+
+// ---------------------------------------------------------------------------------------------
+// The epoch kernel: LDS carve, one-time set-up, then the step loop of the right mode.
+// ---------------------------------------------------------------------------------------------
+template <int BITS, bool INT, bool FAST>
+__global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
+{
+    constexpr int K = 1 << BITS;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int w = blockIdx.x;
+    const int CW = 32 * a.GQ;
+    const int B = a.B;
+    const int nrg = B >= 32 ? B / 32 : 1;
+    const int Rlen = nrg * 32;                     // residual slots (zero outside the batch)
+    const int j0 = w * CW;
+
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { void *p = smem + off; off += (bytes + 15) & ~(size_t)15; return p; };
+    Lds L;
+    L.ring = (uint32_t *)carve((size_t)2 * a.slot_bytes);
+    L.Ls = (float *)carve(a.lds_levels ? (size_t)CW * K * 4 : 0);
+    L.Gs = (uint16_t *)carve(INT && !a.ident_grid ? (size_t)CW * K * 2 : 0);
+    L.xs = (float *)carve(CW * 4);
+    L.ys = (float *)carve(CW * 4);
+    L.los = (float *)carve(CW * 4);
+    L.dls = (float *)carve(CW * 4);
+    L.gs = (float *)carve(CW * 4);
+    L.ms = (int *)carve(CW * 4);
+    L.rs = (float *)carve((size_t)Rlen * 4);
+    L.zl = (float *)carve(a.W == 1 ? (size_t)(B + 4) * 4 : 0);
+    L.gpart = (float *)carve(kThreads * 4);
+    L.red = (double *)carve(512 * 8);
+    L.wsum = (float *)carve(2 * kWaves * 4);
+    L.isum = (int *)carve(kWaves * 4);
+
+    // ---- one-time set-up: level slice, model slice
+    const float *Lg = a.levels + (size_t)j0 * K;
+    if (a.lds_levels)
+        for (int e = tid; e < CW * K; e += kThreads) L.Ls[e] = (j0 + e / K < a.d) ? Lg[e] : 0.0f;
+    if (INT && !a.ident_grid)
+        for (int e = tid; e < CW * K; e += kThreads)
+            L.Gs[e] = (j0 + e / K < a.d) ? a.grid[(size_t)j0 * K + e] : (uint16_t)0;
+    for (int c = tid; c < CW; c += kThreads) L.xs[c] = (j0 + c < a.d) ? a.x[j0 + c] : 0.0f;
+    // Are the levels of every owned feature evenly spaced (fp64 formula, rounded once)?  Then a
+    // value is lo + code * delta and the table look-up is replaced by arithmetic.
+    int ok = 1;
+    if (!INT) {
+        for (int e = tid; e < CW * K; e += kThreads) {
+            const int jj = e / K, c = e % K;
+            if (j0 + jj < a.d) {
+                const double lo = (double)Lg[(size_t)jj * K], wdt = (double)Lg[(size_t)jj * K + K - 1] - lo;
+                ok &= (Lg[e] == (float)(lo + ((double)c * wdt) / (double)(K - 1)));
+            }
         }
     }
+    const bool affine = __syncthreads_and(ok) && !INT;
+    for (int c = tid; c < CW; c += kThreads) {
+        const bool live = j0 + c < a.d;
+        const float lo = live ? Lg[(size_t)c * K] : 0.0f, hi = live ? Lg[(size_t)c * K + K - 1] : 0.0f;
+        L.los[c] = lo;
+        L.dls[c] = (float)(((double)hi - (double)lo) / (double)(K - 1));
+        L.ys[c] = L.dls[c] * L.xs[c];
+        L.gs[c] = 0.0f;
+        L.ms[c] = 0;
+    }
+    for (int i = tid; i < Rlen; i += kThreads) L.rs[i] = 0.0f;
+    if (tid < 2 * kWaves) L.wsum[tid] = 0.0f;
+    __syncthreads();
+    if (affine) {
+        const float part = wave_sum_dpp(tid < CW ? L.los[tid] * L.xs[tid] : 0.0f);
+        if (lane == 0) L.wsum[kWaves + wave] = part;
+    }
+
+    if (INT) sgd_steps<BITS, kInt, FAST>(a, L);
+    else if (affine) sgd_steps<BITS, kAffine, FAST>(a, L);
+    else sgd_steps<BITS, kTable, FAST>(a, L);
+
     // ---- write the model slice back
-    if (a.seg_last >= 3)
+    if (FAST || a.seg_last >= 3)
         for (int c = tid; c < CW; c += kThreads)
-            if (j0 + c < a.d) a.x[j0 + c] = xs[c];
+            if (j0 + c < a.d) a.x[j0 + c] = L.xs[c];
 }
 
 // Clears the barrier counter, the status word and the three accumulators.
@@ -464,54 +682,76 @@ __global__ void k_sgd_reset(int *status, uint32_t *sync, float *acc, int words, 
 }
 
 struct Plan {
-    int GQ, W, depth, slot_bytes;
+    int GQ, W, slot_bytes, lds_levels;
     size_t shmem;
 };
 
 static int device_limits(int &cus, int &lds)
 {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return ZIPML_ELAUNCH;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
+    if (HIP_FAILED(hipGetDevice(&dev))) return ZIPML_ELAUNCH;
+    if (HIP_FAILED(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) ||
+        HIP_FAILED(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev)))
         return ZIPML_ELAUNCH;
     return ZIPML_OK;
 }
 
+static size_t up16(size_t v) { return (v + 15) & ~(size_t)15; }
+
+// LDS needed for GQ feature groups per workgroup; 0 if it does not fit.
+static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool solo, int lds_limit,
+                       int &slot_bytes, int &lds_levels)
+{
+    const int K = 1 << bits, CW = 32 * GQ;
+    const int nrg = batch >= 32 ? (int)(batch / 32) : 1;
+    const int nblk = (int)((batch + 63) / 64);
+    const size_t slot = (size_t)GQ * ((size_t)nblk * 64 * bits + (size_t)nrg * 32 * bits) * 4 +
+                        (size_t)((batch + 3) & ~3) * 4;
+    if (slot > (size_t)lds_limit) return 0;
+    slot_bytes = (int)up16(slot);
+    lds_levels = (size_t)CW * K * 4 <= 32768 ? 1 : 0;
+    const size_t fixed = (lds_levels ? up16((size_t)CW * K * 4) : 0) +
+                         (int_table ? up16((size_t)CW * K * 2) : 0) + 6 * up16((size_t)CW * 4) +
+                         up16((size_t)nrg * 32 * 4) + (solo ? up16((size_t)(batch + 4) * 4) : 0) +
+                         up16(kThreads * 4) + up16(512 * 8) + up16(2 * kWaves * 4) + up16(kWaves * 4);
+    const size_t total = 2 * (size_t)slot_bytes + fixed;
+    return total <= (size_t)lds_limit ? total : 0;
+}
+
+// Chooses how many feature groups a workgroup owns.  A step costs one device-wide exchange whose
+// latency grows with the number of workgroups, so small steps want few, fat workgroups; the two
+// LDS slots and the number of compute units bound the choice from both sides.
 static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, Plan &p)
 {
     int cus = 0, lds = 0;
     if (int rc = device_limits(cus, lds)) return rc;
-    const int K = 1 << bits;
-    int GQ = 1;
-    while ((d32 + GQ - 1) / GQ > cus && GQ < 8) GQ <<= 1;
-    if ((d32 + GQ - 1) / GQ > cus) return ZIPML_EUNSUPPORTED;       // d > 32 * 8 * CUs
-    p.GQ = GQ;
-    p.W = (int)((d32 + GQ - 1) / GQ);
-    if (p.W > 512) return ZIPML_EUNSUPPORTED;
-    const int CW = 32 * GQ;
-    const int nrg = batch >= 32 ? (int)(batch / 32) : 1;
-    auto up = [](size_t v) { return (v + 15) & ~(size_t)15; };
-    size_t fixed = up((size_t)CW * K * 4) + (int_table ? up((size_t)CW * K * 2) : 0) +
-                   6 * up((size_t)CW * 4) + up((size_t)nrg * 32 * 4) + up(kThreads * 4) +
-                   up(512 * 8) + up(16 * 4);
-    const size_t slot = (size_t)GQ * ((size_t)batch * bits + (size_t)nrg * 32 * bits) * 4 +
-                        (size_t)((batch + 3) & ~3) * 4;
-    p.slot_bytes = (int)up(slot);
-    // two slots (this step and the next); the slots must stay within the first 64 KiB of LDS
-    if (fixed + 2 * (size_t)p.slot_bytes > (size_t)lds || 2 * (size_t)p.slot_bytes > 65536)
-        return ZIPML_EUNSUPPORTED;   // batch too large for the persistent kernel
-    p.depth = 2;
-    p.shmem = fixed + (size_t)p.depth * p.slot_bytes;
-    return ZIPML_OK;
+    int kTargetW = 32;
+    if (const char *env = getenv("ZIPML_TARGET_W")) {   // tuning override: preferred workgroup count
+        const int v = atoi(env);
+        if (v >= 1 && v <= 512) kTargetW = v;
+    }
+    int best = 0;
+    for (int GQ = 1; GQ <= 8; GQ <<= 1) {
+        const int64_t W = (d32 + GQ - 1) / GQ;
+        if (W > cus || W > 512) continue;
+        int slot = 0, ll = 0;
+        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, lds, slot, ll);
+        if (!sh) break;                    // larger GQ only needs more LDS
+        best = GQ;
+        p.GQ = GQ; p.W = (int)W; p.slot_bytes = slot; p.lds_levels = ll; p.shmem = sh;
+        if (W <= kTargetW) break;
+    }
+    return best ? ZIPML_OK : ZIPML_EUNSUPPORTED;   // batch too large for LDS, or d too large
 }
 
-template <int BITS>
+template <int BITS, bool INT>
 static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
 {
-    auto kern = k_sgd<BITS>;
-    if (HIP_FAILED(hipFuncSetAttribute((const void *)kern,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.shmem)))
+    const bool debug = a.dbg_m || a.dbg_acc || a.dbg_gq || a.dbg_r || a.dbg_g;
+    const bool fast = !stepwise && !debug;
+    const void *kern = fast ? (const void *)k_sgd<BITS, INT, true> : (const void *)k_sgd<BITS, INT, false>;
+    if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)p.shmem)))
         return ZIPML_ELAUNCH;
     const int words = 3 * a.acc_words;
     hipLaunchKernelGGL(k_sgd_reset, dim3((words + 255) / 256), dim3(256), 0, s, a.status, a.sync,
@@ -522,8 +762,8 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         a.seg_first = 0;
         a.seg_last = 3;
         void *params[] = {&a};
-        if (HIP_FAILED(hipLaunchCooperativeKernel((const void *)kern, dim3(a.W), dim3(kThreads),
-                                                  params, (unsigned)p.shmem, s)))
+        if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(a.W), dim3(kThreads), params,
+                                                  (unsigned)p.shmem, s)))
             return ZIPML_ELAUNCH;
         return ZIPML_OK;
     }
@@ -543,11 +783,19 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
             a.seg_first = seg;
             a.seg_last = seg;
             if (seg == 2 && a.grad_bits == 0) a.seg_last = 3;
-            hipLaunchKernelGGL(kern, dim3(a.W), dim3(kThreads), p.shmem, s, a);
-            if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+            void *params[] = {&a};
+            if (HIP_FAILED(hipLaunchKernel(kern, dim3(a.W), dim3(kThreads), params, p.shmem, s)))
+                return ZIPML_ELAUNCH;
         }
     }
     return ZIPML_OK;
+}
+
+template <int BITS>
+static int launch_sgd_mode(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
+{
+    return a.model_bits > 0 ? launch_sgd<BITS, true>(s, a, p, stepwise)
+                            : launch_sgd<BITS, false>(s, a, p, stepwise);
 }
 
 static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_dev,
@@ -582,9 +830,10 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
         return ZIPML_EWORKSPACE;
     if (nsteps == 0) return ZIPML_OK;
 
+    hipStream_t s = entry_stream(stream);
     const Layout lay = make_layout(n, d, bits);
     const bool ident = model_bits > 0 && grid_max == (1 << bits) - 1;
-    Plan p;
+    Plan p{};
     if (int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, p)) return rc;
 
     unsigned char *ws = (unsigned char *)workspace_dev;
@@ -595,7 +844,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.grid = grid_idx_dev;
     a.b = b_dev;
     a.x = x_dev;
-    a.n_pad = lay.n_pad;
+    a.nb64 = lay.nb64;
     a.n32 = lay.n32;
     a.d = (int)d;
     a.d32 = (int)lay.d32;
@@ -612,7 +861,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.epoch = epoch;
     a.GQ = p.GQ;
     a.W = p.W;
-    a.depth = p.depth;
+    a.lds_levels = p.lds_levels;
     a.slot_bytes = p.slot_bytes;
     a.status = (int *)(ws + Workspace::kStatus);
     a.sync = (uint32_t *)(ws + Workspace::kSync);
@@ -621,17 +870,16 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.acc_words = (int)Workspace::acc_words(batch);
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
-    hipStream_t s = entry_stream(stream);
     const bool stepwise = (flags & ZIPML_SGD_STEPWISE) != 0;
     switch (bits) {
-        case 1: return launch_sgd<1>(s, a, p, stepwise);
-        case 2: return launch_sgd<2>(s, a, p, stepwise);
-        case 3: return launch_sgd<3>(s, a, p, stepwise);
-        case 4: return launch_sgd<4>(s, a, p, stepwise);
-        case 5: return launch_sgd<5>(s, a, p, stepwise);
-        case 6: return launch_sgd<6>(s, a, p, stepwise);
-        case 7: return launch_sgd<7>(s, a, p, stepwise);
-        case 8: return launch_sgd<8>(s, a, p, stepwise);
+        case 1: return launch_sgd_mode<1>(s, a, p, stepwise);
+        case 2: return launch_sgd_mode<2>(s, a, p, stepwise);
+        case 3: return launch_sgd_mode<3>(s, a, p, stepwise);
+        case 4: return launch_sgd_mode<4>(s, a, p, stepwise);
+        case 5: return launch_sgd_mode<5>(s, a, p, stepwise);
+        case 6: return launch_sgd_mode<6>(s, a, p, stepwise);
+        case 7: return launch_sgd_mode<7>(s, a, p, stepwise);
+        case 8: return launch_sgd_mode<8>(s, a, p, stepwise);
     }
     return ZIPML_EINVAL;
 }
@@ -676,9 +924,9 @@ extern "C" int zipml_sgd_status(void *stream, const void *workspace_dev, size_t 
     if (!workspace_dev || workspace_bytes < 4096) return ZIPML_EWORKSPACE;
     int st = 0;
     hipStream_t s = entry_stream(stream);
-    if (hipMemcpyAsync(&st, (const unsigned char *)workspace_dev + Workspace::kStatus, sizeof(int),
-                       hipMemcpyDeviceToHost, s) != hipSuccess)
+    if (HIP_FAILED(hipMemcpyAsync(&st, (const unsigned char *)workspace_dev + Workspace::kStatus,
+                                  sizeof(int), hipMemcpyDeviceToHost, s)))
         return ZIPML_ELAUNCH;
-    if (hipStreamSynchronize(s) != hipSuccess) return ZIPML_ELAUNCH;
+    if (HIP_FAILED(hipStreamSynchronize(s))) return ZIPML_ELAUNCH;
     return st;
 }
