@@ -430,8 +430,9 @@ void zo_sgd_epoch(const uint8_t *codes1, const uint8_t *codes2, const float *lev
 /*     so the dot is an exact integer sum  acc_i = sum_j G[j][c2_ij] * m_j;  */
 /*   - z_i = fp32( sigma * (lo * sum_j m_j + step * acc_i) ) in fp64;        */
 /*   - r_i = z_i - b_i in fp32;                                              */
-/*   - g_j: fp32 fused multiply-adds over the batch in row order, then one   */
-/*     fp32 division by the batch size;                                      */
+/*   - g_j: per block of 32 consecutive samples one chain of fp32 fused     */
+/*     multiply-adds in sample order, block sums added in block order, then  */
+/*     one fp32 division by the batch size;                                  */
 /*   - Q4 and the update in fp32, multiply then subtract.                    */
 /* Optional debug outputs (any may be NULL) capture the LAST step:           */
 /*   dbg_m[d] model codes, dbg_acc[batch] integer dots, dbg_r[batch],        */
@@ -471,11 +472,18 @@ int zo_sgd_epoch_e2e(const uint8_t *codes1, const uint8_t *codes2, const float *
                        ((double)grid_lo * (double)summ + (double)grid_step * (double)a);
             r[i] = (float)z - bb[i];
         }
-        /* gradient pass on copy 1 */
+        /* gradient pass on copy 1: blocks of 32 consecutive samples of the batch; inside a
+         * block one fp32 fused-multiply-add chain in sample order starting from zero; the block
+         * sums are added in block order; one fp32 division by the batch size */
         for (int64_t j = 0; j < d; ++j) {
-            float a = 0.0f;
-            for (int64_t i = 0; i < batch; ++i) a = fmaf(levels[j * K + c1[i * d + j]], r[i], a);
-            g[j] = a / (float)batch;
+            float sum = 0.0f;
+            for (int64_t blk = 0; blk < batch; blk += 32) {
+                float a = 0.0f;
+                for (int64_t i = blk; i < blk + 32 && i < batch; ++i)
+                    a = fmaf(levels[j * K + c1[i * d + j]], r[i], a);
+                sum = sum + a;
+            }
+            g[j] = sum / (float)batch;
         }
         /* Q4: quantise the gradient (Supp. D), then full-precision update */
         if (grad_bits > 0) {

@@ -91,6 +91,16 @@ __device__ __forceinline__ void release_dev()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load, store and atomic of the wave (s_waitcnt vmcnt(0)), which would stall a wave on the
+// prefetch it has just issued; this one waits for LDS operations (lgkmcnt) and nothing else.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---------------------------------------------------------------------------------------------
 // Wave and block reductions.
 // ---------------------------------------------------------------------------------------------

@@ -14,12 +14,12 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline bool valid_bits(int bits) { return bits >= 1 && bits <= 8; }
 
 // Packed layout (private).  A unit is 32 codes of `bits` bits: a little-endian bit string of
-// `bits` dwords.  n is padded to a multiple of 64, d to a multiple of 32.  Units are stored
-// dword-planar, so that the lanes of a wave read consecutive dwords (global memory and LDS alike):
+// `bits` dwords, stored contiguously so that a thread fetches its unit with the widest loads its
+// alignment allows.  n is padded to a multiple of 64, d to a multiple of 32.
 //   copy 2 (dot pass):      unit = one sample x 32 features
-//                           [feature group g][block of 64 samples][dword q][sample in block]
+//                           [feature group g][sample i][bits dwords]
 //   copy 1 (gradient pass): unit = one feature x 32 samples
-//                           [feature group g][group of 32 samples][dword q][feature in group]
+//                           [feature group g][group of 32 samples][feature in group][bits dwords]
 struct Layout {
     int64_t n, d, n_pad, d_pad;
     int64_t d32;    // feature groups

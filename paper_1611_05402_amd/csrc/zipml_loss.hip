@@ -63,8 +63,7 @@ __global__ __launch_bounds__(kLossThreads) void k_loss_copy2(
         for (int64_t g = 0; g < d32; ++g) {
             uint32_t u[BITS];
 #pragma unroll
-            for (int q = 0; q < BITS; ++q)
-                u[q] = p2[((g * (n_pad / 64) + i / 64) * BITS + q) * 64 + (i % 64)];
+            for (int q = 0; q < BITS; ++q) u[q] = p2[(g * n_pad + i) * BITS + q];
 #pragma unroll
             for (int k = 0; k < 32; ++k) {
                 const int64_t j = g * 32 + k;
@@ -97,7 +96,7 @@ __global__ __launch_bounds__(kLossThreads) void k_loss_copy1(
             const int64_t g = j / 32, cin = j % 32;
             uint32_t u[BITS];
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) u[q] = p1[((g * n32 + rg) * BITS + q) * 32 + cin];
+            for (int q = 0; q < BITS; ++q) u[q] = p1[((g * n32 + rg) * 32 + cin) * BITS + q];
             const float xj = x[j];
 #pragma unroll
             for (int k = 0; k < 32; ++k) z[k] = fmaf(levels[j * K + unit_code<BITS>(u, k)], xj, z[k]);

@@ -100,9 +100,9 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
                 unit_set<BITS>(unit, k, (w >> (8 * (k & 3))) & 0xFFu);
             }
             const int64_t i = rg * 32 + r;
-            uint32_t *dst = p2 + ((g * nb64 + i / 64) * BITS) * 64 + (i % 64);
+            uint32_t *dst = p2 + (g * nb64 * 64 + i) * BITS;
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) dst[q * 64] = unit[q];
+            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
         }
     } else {
         // copy 1: one unit = feature c, the 32 samples of this group
@@ -117,9 +117,9 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
                 const uint32_t w = c1w[k * kLdsRow + (c >> 2)];
                 unit_set<BITS>(unit, k, (w >> (8 * (c & 3))) & 0xFFu);
             }
-            uint32_t *dst = p1 + ((g * n32 + rg) * BITS) * 32 + cin;
+            uint32_t *dst = p1 + ((g * n32 + rg) * 32 + cin) * BITS;
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) dst[q * 32] = unit[q];
+            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
         }
     }
 }
@@ -135,9 +135,9 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
     if (copy == 2) {
         const int64_t g = u / n_pad, i = u % n_pad;
         if (i >= n) return;
-        const uint32_t *src = packed + ((g * (n_pad / 64) + i / 64) * BITS) * 64 + (i % 64);
+        const uint32_t *src = packed + (g * n_pad + i) * BITS;
 #pragma unroll
-        for (int q = 0; q < BITS; ++q) unit[q] = src[q * 64];
+        for (int q = 0; q < BITS; ++q) unit[q] = src[q];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             const int64_t j = g * 32 + k;
@@ -147,9 +147,9 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
         const int64_t g = u / n_pad, rem = u % n_pad, rg = rem / 32, cin = rem % 32;
         const int64_t j = g * 32 + cin;
         if (j >= d) return;
-        const uint32_t *src = packed + ((g * n32 + rg) * BITS) * 32 + cin;
+        const uint32_t *src = packed + ((g * n32 + rg) * 32 + cin) * BITS;
 #pragma unroll
-        for (int q = 0; q < BITS; ++q) unit[q] = src[q * 32];
+        for (int q = 0; q < BITS; ++q) unit[q] = src[q];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             const int64_t i = rg * 32 + k;

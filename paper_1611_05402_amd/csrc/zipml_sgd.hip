@@ -4,19 +4,23 @@
 //
 // Decomposition (feature-owner): workgroup w owns a block of 32*GQ features for the whole epoch and
 // keeps its slice of the model in LDS.  Per step it
-//   1. reads its slice of copy 2 (sample-major units) and adds the partial dot products of the
-//      `batch` samples into a device-wide accumulator (device-scope atomics),
+//   1. takes the partial dot products of the `batch` samples over its features from copy 2
+//      (sample-major units) and adds them into a device-wide accumulator (device-scope atomics),
 //   2. meets the other workgroups at ONE grid-wide barrier,
-//   3. reads the `batch` sums, forms the residuals, reads its slice of copy 1 (feature-major
-//      units), forms its slice of the mean gradient and updates its slice of the model, locally.
-// A step is bound by the latency of that one device-wide exchange, not by bandwidth, so the kernel
-// is organised around it:
-//   - the packed data does not depend on the model: the slice for step t+1 is fetched straight
-//     into LDS (global_load_lds) while step t waits at the barrier;
-//   - loads of one wave return in order, so a wave with a prefetch in flight cannot do a
-//     latency-critical load: wave 0 never prefetches, it polls the barrier and reads the sums;
+//   3. reads the `batch` sums, forms the residuals, takes its slice of the mean gradient from
+//      copy 1 (feature-major units) and updates its slice of the model, locally.
+// A step moves little data and is bound by the latency of that one device-wide exchange, so the
+// kernel is organised around the exchange:
+//   - the packed data does not depend on the model.  Every thread owns the same units (sample x
+//     feature group for the dot pass, feature x sample group for the gradient pass) in every
+//     step and fetches them into registers ahead of time: right after the sums of step t have
+//     been read it requests copy 1 of step t+1 and copy 2 of step t+2.  That is the one point of
+//     a step from which no latency-critical memory operation follows for about a microsecond
+//     (loads of a wave, and of a compute unit's memory pipeline, return in order, so a long load
+//     in flight would hold back the atomics' acknowledgement, the barrier poll and the sums);
 //   - exchanged data moves only through device-scope atomics / loads, so the barrier needs no
-//     cache write-back, only "my atomics have been performed" (s_waitcnt vmcnt(0)).
+//     cache write-back, only "my atomics have been performed" (s_waitcnt vmcnt(0));
+//   - workgroup barriers inside a step order LDS traffic only (lds_barrier).
 // End-to-end mode adds two small exchanges per step (the l2 norms of model and gradient).
 #include "zipml_device.h"
 #include "zipml_host.h"
@@ -26,9 +30,9 @@
 
 namespace zipml {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kFetchThreads = kThreads - kWave;   // waves 1.. issue the prefetch
+constexpr int kMaxUpt = 4;                        // units per thread and pass that fit in registers
 constexpr uint32_t kSpinLimit = 1u << 24;         // bounded wait: a lost workgroup ends in ZIPML_ETIMEOUT
 
 enum Mode { kAffine = 0, kTable = 1, kInt = 2 };
@@ -53,7 +57,6 @@ struct SgdArgs {
     int lds_levels;        // the workgroup's slice of the level table fits in LDS
     int seg_first, seg_last;   // segments of a step run by this launch (0..3)
     int persistent;        // 1: segments are separated by in-kernel grid barriers
-    int slot_bytes;
     // workspace
     int *status;
     uint32_t *sync;
@@ -68,14 +71,15 @@ struct SgdArgs {
 
 // LDS arrays of one workgroup.
 struct Lds {
-    uint32_t *ring;   // two packed-data slots
     float *Ls;        // level slice [CW][K]        (lds_levels only)
     uint16_t *Gs;     // grid-index slice [CW][K]   (integer mode with a non-identity grid)
     float *xs, *ys, *los, *dls, *gs;   // model slice, delta*x, lo, delta, gradient slice  [CW]
     int *ms;          // model codes [CW]
     float *rs;        // residuals [Rlen]
+    float *bs;        // labels of the current step [B]
     float *zl;        // local dot products [B+4]   (single workgroup only)
-    float *gpart;     // gradient partial sums [kThreads]
+    uint32_t *zp;     // per-unit partial dot products [GQ][B]  (GQ > 1 only)
+    float *gpart;     // gradient partial sums [kMaxUpt * kThreads]
     double *red;      // reduction scratch [512]
     float *wsum;      // [0..kWaves): residual sum parts, [kWaves..2kWaves): parts of sum_j lo_j x_j
     int *isum;        // [kWaves]
@@ -104,11 +108,11 @@ __device__ __forceinline__ void vm_wait_all()
 __device__ __forceinline__ void lds_tree_sum(double *a, int len)
 {
     for (int stride = 1; stride < len; stride <<= 1) {
-        __syncthreads();
+        lds_barrier();
         for (int i = threadIdx.x * 2 * stride; i + stride < len; i += kThreads * 2 * stride)
             a[i] = a[i] + a[i + stride];
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 // Signed code of the row-scaled quantiser (Supp. A.3 eq. (quant2)), fp32 decisions.
@@ -125,33 +129,15 @@ __device__ __forceinline__ int qvec_code(float v, float M, int s, float u)
     return v < 0.0f ? -mag : mag;
 }
 
-// Asynchronous copy of `dwords` (multiple of 4) dwords from global to LDS, 16 B per lane, issued by
-// waves 1.. of the workgroup.  Completion: vm_wait_all() in those waves, then a barrier.
-__device__ __forceinline__ void async_copy(const uint32_t *__restrict__ src, uint32_t *dst_lds,
-                                           int dwords)
-{
-    const int chunks = dwords >> 2;
-    const int ft = (int)threadIdx.x - kWave;          // 0 .. kFetchThreads-1
-    const int lane = ft & (kWave - 1);
-    const int wave_first = ft - lane;
-    for (int c0 = 0; c0 < chunks; c0 += kFetchThreads) {
-        const int c = c0 + wave_first + lane;
-        if (c0 + wave_first < chunks) {
-            uint32_t *wave_dst = dst_lds + (size_t)(c0 + wave_first) * 4;
-            if (c < chunks)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(src + (size_t)c * 4),
-                    (__attribute__((address_space(3))) void *)wave_dst, 16, 0, 0);
-        }
-    }
-}
-
-// One packed unit from the dword-planar LDS slot: dword q sits `stride` dwords after dword q-1.
+// One packed unit (BITS contiguous dwords) from global memory, with the widest loads that the
+// unit's alignment (the largest power of two dividing 4*BITS bytes, at most 16) allows.
 template <int BITS>
-__device__ __forceinline__ void planar_unit(const uint32_t *p, int stride, uint32_t (&u)[BITS])
+__device__ __forceinline__ void load_unit(const uint32_t *__restrict__ p, uint32_t (&u)[BITS])
 {
+    constexpr int kAlign = (BITS % 4 == 0) ? 16 : (BITS % 2 == 0) ? 8 : 4;
+    const uint32_t *q = static_cast<const uint32_t *>(__builtin_assume_aligned(p, kAlign));
 #pragma unroll
-    for (int q = 0; q < BITS; ++q) u[q] = p[q * stride];
+    for (int k = 0; k < BITS; ++k) u[k] = q[k];
 }
 
 // ---- inner loops over the 32 codes of a unit (v: 32 wave-uniform fp32/int32 values in LDS) ----
@@ -213,11 +199,12 @@ __device__ __forceinline__ int unit_dot_int(const uint32_t (&u)[BITS], const uin
 }
 
 // ---------------------------------------------------------------------------------------------
-// The step loop, specialised on how a code becomes a value.
-// ---------------------------------------------------------------------------------------------
+// The step loop, specialised on how a code becomes a value (MODE) and on the number of units a
+// thread owns per pass (UPT).
 // FAST: the production configuration (whole steps inside one persistent launch, no debug
 // outputs); everything that only the stepwise / debug launches need folds away at compile time.
-template <int BITS, int MODE, bool FAST>
+// ---------------------------------------------------------------------------------------------
+template <int BITS, int MODE, bool FAST, int UPT>
 __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 {
     constexpr int K = 1 << BITS;
@@ -238,7 +225,6 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
     const int CW = 32 * GQ;
     const int B = a.B;
     const int nrg = B >= 32 ? B / 32 : 1;          // sample groups of copy 1 per step
-    const int nblk = (B + 63) / 64;                // sample blocks of copy 2 per step
     const bool solo = W == 1;
     const bool local = solo && persistent;         // no other workgroup or launch: all stays in LDS
     const bool grid_sync = persistent && !solo;
@@ -247,6 +233,54 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
     const float *Lg = a.levels + (size_t)j0 * K;   // global view of the owned level slice
     float *const xs = L.xs, *const ys = L.ys, *const gs = L.gs, *const rs = L.rs;
     double *const red = L.red;
+
+    // ---- the units this thread owns, the same in every step
+    // dot pass:      unit k = (sample d_i[k] of the batch, owned feature group d_g[k])
+    // gradient pass: unit k = (owned feature g_c, sample group g_rg[k] of the batch)
+    const int n_dot = B * ngroups;
+    int d_i[UPT], d_g[UPT];
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+        int i = tid + k * kThreads, g = 0;
+        while (i >= B && g < GQ) { i -= B; ++g; }
+        d_i[k] = i;
+        d_g[k] = g;       // g >= ngroups: no such unit
+    }
+    const int nsl = kThreads / CW;                 // threads per owned feature
+    const int g_c = tid % CW, g_sl = tid / CW;
+    const int g_gq = g_c >> 5, g_cin = g_c & 31;
+    const bool g_live = g_gq < ngroups;
+
+    auto load_dot_units = [&](int64_t t, uint32_t (&dst)[UPT][BITS]) {
+        const int64_t row0 = t * B;
+#pragma unroll
+        for (int k = 0; k < UPT; ++k) {
+            if (d_g[k] < ngroups) {
+                const int64_t row = row0 + d_i[k];
+                const int64_t g = (int64_t)w * GQ + d_g[k];
+                load_unit<BITS>(a.p2 + (g * a.nb64 * 64 + row) * BITS, dst[k]);
+            }
+        }
+    };
+    auto load_grad_units = [&](int64_t t, uint32_t (&dst)[UPT][BITS]) {
+        const int64_t rg0 = (t * B) / 32;
+#pragma unroll
+        for (int k = 0; k < UPT; ++k) {
+            const int rgl = g_sl + k * nsl;
+            if (g_live && rgl < nrg) {
+                const int64_t g = (int64_t)w * GQ + g_gq;
+                load_unit<BITS>(a.p1 + ((g * a.n32 + rg0 + rgl) * 32 + g_cin) * BITS, dst[k]);
+            }
+        }
+    };
+    constexpr int kBpt = kMaxUpt;                  // labels per thread (batch <= kMaxUpt * kThreads)
+    auto load_labels = [&](int64_t t, float (&dst)[kBpt]) {
+#pragma unroll
+        for (int k = 0; k < kBpt; ++k) {
+            const int i = tid + k * kThreads;
+            if (i < B) dst[k] = a.b[t * B + i];
+        }
+    };
 
     // ---- grid barrier state (one monotonically increasing arrival counter)
     uint32_t passed = 0;
@@ -265,26 +299,11 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
         }
     };
 
-    // ---- packed-data slots: [GQ][nblk][BITS][64] copy 2 | [GQ][nrg][BITS][32] copy 1 | labels
-    const int r2_dw = nblk * 64 * BITS;
-    const int r1_dw = nrg * 32 * BITS;
-    const int slot_dw = a.slot_bytes / 4;
-    auto fetch = [&](int64_t t, int slot) {     // waves 1.. only
-        uint32_t *s = L.ring + (size_t)slot * slot_dw;
-        const int64_t row = t * B;
-        for (int gq = 0; gq < ngroups; ++gq) {
-            const int64_t g = (int64_t)w * GQ + gq;
-            async_copy(a.p2 + ((g * a.nb64 + row / 64) * BITS) * 64, s + gq * r2_dw, r2_dw);
-            async_copy(a.p1 + ((g * a.n32 + row / 32) * BITS) * 32, s + GQ * r2_dw + gq * r1_dw, r1_dw);
-        }
-        async_copy((const uint32_t *)(a.b + row), s + GQ * (r2_dw + r1_dw), (B + 3) & ~3);
-    };
     const int64_t t_end = a.step0 + a.nsteps;
 #ifdef ZIPML_PHASE_TIMING
     long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = wall_clock64();
 #endif
-    if (wave > 0) fetch(a.step0, 0);
     int Wp = 1;
     while (Wp < W) Wp <<= 1;
     const int s_m = (1 << (a.model_bits > 0 ? a.model_bits - 1 : 1)) - 1;
@@ -296,28 +315,31 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
             for (int i = lane; i < Wp; i += kWave) red[i] = i < W ? load_dev(part + i) : 0.0;
         lds_tree_sum(red, Wp);
         const float M = (float)sqrt(red[0]);
-        __syncthreads();
+        lds_barrier();
         return M;
     };
 
+    // ---- register-resident packed data: copy 2 of this step and the next, copy 1 of this step
+    // and the next, labels of the next step
+    uint32_t c2cur[UPT][BITS], c2nxt[UPT][BITS], c1cur[UPT][BITS], c1nxt[UPT][BITS];
+    float bnext[kBpt];
+    load_dot_units(a.step0, c2cur);
+    if (a.step0 + 1 < t_end) load_dot_units(a.step0 + 1, c2nxt);
+    load_grad_units(a.step0, c1nxt);
+    load_labels(a.step0, bnext);
+
     for (int64_t t = a.step0; t < t_end; ++t) {
-        const int slot = (int)(t - a.step0) & 1;
-        const uint32_t *S2 = L.ring + (size_t)slot * slot_dw;
-        const uint32_t *S1 = S2 + GQ * r2_dw;
-        const float *bS = (const float *)(S1 + GQ * r1_dw);
         float *accf = a.acc + (size_t)(t % 3) * a.acc_words;
         int *acci = (int *)accf;
-        const int roff = (int)((t * B) % 64);              // first batch row inside the fetched blocks
-        const int k0 = B >= 32 ? 0 : (int)((t * B) % 32);  // ... inside the fetched sample group
-        bool prefetched = !(persistent && t + 1 < t_end);   // nothing (more) to prefetch this step
-        auto prefetch_once = [&]() {
-            if (!prefetched && wave > 0) fetch(t + 1, slot ^ 1);
-            prefetched = true;
-        };
+        const int k0 = B >= 32 ? 0 : (int)((t * B) % 32);  // batch offset inside its sample group
 
         ZIPML_TICK(7);
-        vm_wait_all();       // this step's slot has landed (issued during the previous step)
-        __syncthreads();     // ... and the model slice written at the end of the previous step is visible
+#pragma unroll
+        for (int k = 0; k < kBpt; ++k) {
+            const int i = tid + k * kThreads;
+            if (i < B) L.bs[i] = bnext[k];
+        }
+        lds_barrier();     // labels, and the model slice written at the end of the previous step
         ZIPML_TICK(0);
 
         // ================= segment 0: ||x||_2 partial (model quantisation only) =================
@@ -328,13 +350,12 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
             if (tid < CW) red[tid] = (double)xs[tid] * (double)xs[tid];
             lds_tree_sum(red, CW);
             own_sq = red[0];
-            __syncthreads();
+            lds_barrier();
             if (!local && tid == 0) store_dev(nx + w, own_sq);
             if (grid_sync) {
                 vm_wait_all();
-                __syncthreads();
-                if (wave == 0) { if (lane == 0) arrive_and_poll(); }
-                else prefetch_once();
+                lds_barrier();
+                if (wave == 0 && lane == 0) arrive_and_poll();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // no load moves above the poll
             }
         }
@@ -357,7 +378,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 }
                 const int part = wave_sum_dpp(mine);
                 if (lane == 0) L.isum[wave] = part;
-                __syncthreads();   // publishes ms[] and isum[]
+                lds_barrier();   // publishes ms[] and isum[]
                 if (tid == 0) {
                     int tot = 0;
                     for (int q = 0; q < kWaves; ++q) tot += L.isum[q];
@@ -365,44 +386,57 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     else if (tot != 0) add_dev(acci + B, tot);
                 }
             }
-            // dot pass: one sample per thread, all owned feature groups
+            // dot pass: the partial sums of a sample over the owned feature groups are combined in
+            // LDS before they are published
             float Cq = 0.0f;
             if (MODE == kAffine)
                 for (int q = 0; q < kWaves; ++q) Cq += L.wsum[kWaves + q];
-            for (int i = tid; i < B; i += kThreads) {
-                const int r = roff + i;
-                const uint32_t *row = S2 + (r >> 6) * (64 * BITS) + (r & 63);
-                float pf = Cq;
-                int pi = 0;
-                for (int gq = 0; gq < ngroups; ++gq) {
-                    uint32_t u[BITS];
-                    planar_unit<BITS>(row + gq * r2_dw, 64, u);
-                    const int jb = gq * 32;
-                    if (MODE == kAffine) {
-                        pf = unit_fma_codes<BITS>(u, ys + jb, pf);
-                    } else if (MODE == kTable) {
-                        if (a.lds_levels) pf = unit_dot_table<BITS>(u, L.Ls + jb * K, xs + jb, pf);
-                        else pf = unit_dot_table<BITS>(u, Lg + (size_t)jb * K, xs + jb, pf);
-                    } else {
-                        pi = unit_dot_int<BITS>(u, a.ident_grid ? nullptr : L.Gs + jb * K, L.ms + jb, pi);
-                    }
-                }
+            auto publish = [&](int i, float pf, int pi) {
                 if (local) {
                     if (kIsInt) ((int *)L.zl)[i] = pi; else L.zl[i] = pf;
                 } else {
                     if (kIsInt) add_dev(acci + i, pi); else add_dev(accf + i, pf);
                 }
+            };
+            const bool combine = ngroups > 1;
+#pragma unroll
+            for (int k = 0; k < UPT; ++k) {
+                if (d_g[k] < ngroups) {
+                    const int jb = d_g[k] * 32;
+                    float pf = 0.0f;
+                    int pi = 0;
+                    if (MODE == kAffine) {
+                        pf = unit_fma_codes<BITS>(c2cur[k], ys + jb, pf);
+                    } else if (MODE == kTable) {
+                        if (a.lds_levels) pf = unit_dot_table<BITS>(c2cur[k], L.Ls + jb * K, xs + jb, pf);
+                        else pf = unit_dot_table<BITS>(c2cur[k], Lg + (size_t)jb * K, xs + jb, pf);
+                    } else {
+                        pi = unit_dot_int<BITS>(c2cur[k], a.ident_grid ? nullptr : L.Gs + jb * K,
+                                                L.ms + jb, pi);
+                    }
+                    if (combine) L.zp[d_g[k] * B + d_i[k]] = kIsInt ? (uint32_t)pi : __float_as_uint(pf);
+                    else publish(d_i[k], Cq + pf, pi);
+                }
+            }
+            if (combine) {
+                lds_barrier();
+                for (int i = tid; i < B; i += kThreads) {
+                    float pf = Cq;
+                    int pi = 0;
+                    for (int gq = 0; gq < ngroups; ++gq) {
+                        const uint32_t v = L.zp[gq * B + i];
+                        if (kIsInt) pi += (int)v; else pf += __uint_as_float(v);
+                    }
+                    publish(i, pf, pi);
+                }
             }
             ZIPML_TICK(1);
             if (grid_sync) {
                 vm_wait_all();      // this wave's atomics have been performed
-                __syncthreads();    // ... and so have those of the whole workgroup
+                lds_barrier();      // ... and so have those of the whole workgroup
                 ZIPML_TICK(2);
-                if (wave == 0) { if (lane == 0) arrive_and_poll(); }
-                else prefetch_once();
+                if (wave == 0 && lane == 0) arrive_and_poll();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // no load moves above the poll
-            } else {
-                prefetch_once();
             }
         }
         if (seg_last < 2) continue;
@@ -415,8 +449,8 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 sigma = Mx > 0.0f ? __fdiv_rn(Mx, (float)s_m) : 0.0f;
             }
             ZIPML_TICK(3);
-            // wave 0 (no prefetch in flight) reads the sums and forms the residuals
-            if (local) __syncthreads();   // zl[] written by all waves
+            // wave 0 reads the sums and forms the residuals
+            if (local) lds_barrier();   // zl[] written by all waves
             if (wave == 0 || local) {
                 double summ = 0.0;
                 if (kIsInt) summ = local ? (double)((int *)L.zl)[B] : (double)load_dev(acci + B);
@@ -425,14 +459,19 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 constexpr int kBatchLoads = 4;   // device-scope loads in flight per lane
                 for (int base = local ? tid : lane; base < B; base += stride * kBatchLoads) {
                     // issue all loads first: each costs a full trip to the coherence point
+                    // (indices are clamped, not branched on, so that the loads issue back to back)
                     uint32_t raw[kBatchLoads];
+                    if (local) {
 #pragma unroll
-                    for (int q = 0; q < kBatchLoads; ++q) {
-                        const int i = base + q * stride;
-                        raw[q] = 0u;
-                        if (i < B) {
-                            if (local) raw[q] = ((const uint32_t *)L.zl)[i];
-                            else raw[q] = load_dev((const uint32_t *)accf + i);
+                        for (int q = 0; q < kBatchLoads; ++q) {
+                            const int i = base + q * stride;
+                            raw[q] = ((const uint32_t *)L.zl)[i < B ? i : B - 1];
+                        }
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < kBatchLoads; ++q) {
+                            const int i = base + q * stride;
+                            raw[q] = load_dev((const uint32_t *)accf + (i < B ? i : B - 1));
                         }
                     }
 #pragma unroll
@@ -444,10 +483,10 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                                 const int av = (int)raw[q];
                                 const double z = (double)sigma * ((double)a.grid_lo * summ +
                                                                   (double)a.grid_step * (double)av);
-                                r = (float)z - bS[i];
+                                r = (float)z - L.bs[i];
                                 if (dbg_acc && w == 0) dbg_acc[i] = av;
                             } else {
-                                r = __uint_as_float(raw[q]) - bS[i];
+                                r = __uint_as_float(raw[q]) - L.bs[i];
                             }
                             rs[k0 + i] = r;
                             rsum += r;
@@ -468,76 +507,78 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     for (int i = lane; i < B + 1; i += kWave) store_dev(nxt + i, 0.0f);
                 }
             }
-            __syncthreads();    // rs[], wsum[] ready
+            lds_barrier();    // rs[], wsum[] ready
             ZIPML_TICK(4);
 
-            if (kIsInt) {
-                // fixed order: one feature per thread, samples in batch order, fp32 fma chain
-                if (tid < CW) {
-                    const int gq = tid >> 5, cin = tid & 31;
-                    float acc = 0.0f;
-                    if (gq < ngroups) {
-                        const uint32_t *col = S1 + gq * r1_dw + cin;
-                        for (int rgl = 0; rgl < nrg; ++rgl) {
-                            uint32_t u[BITS];
-                            planar_unit<BITS>(col + rgl * (32 * BITS), 32, u);
-                            if (a.lds_levels) acc = unit_grad_table<BITS>(u, L.Ls + tid * K, rs + rgl * 32, acc);
-                            else acc = unit_grad_table<BITS>(u, Lg + (size_t)tid * K, rs + rgl * 32, acc);
-                        }
-                    }
-                    const float g = (j0 + tid < a.d) ? __fdiv_rn(acc, (float)B) : 0.0f;
-                    gs[tid] = g;
-                    if (dbg_g && j0 + tid < a.d) dbg_g[j0 + tid] = g;
+            // Rotate the register sets and request what later steps need: copy 1 of step t+1,
+            // copy 2 of step t+2, labels of step t+1.  Nothing latency-critical touches memory
+            // from here until the atomics at the end of the next dot pass.
+#pragma unroll
+            for (int k = 0; k < UPT; ++k)
+#pragma unroll
+                for (int q = 0; q < BITS; ++q) {
+                    c1cur[k][q] = c1nxt[k][q];
+                    c2cur[k][q] = c2nxt[k][q];
                 }
-            } else {
-                // free order: (feature, slice of the sample groups) per thread, then reduce slices
-                const int nsl = kThreads / CW;
-                const int c = tid % CW, sl = tid / CW;
-                const int gq = c >> 5, cin = c & 31;
-                float acc = 0.0f;
-                if (gq < ngroups) {
-                    const uint32_t *col = S1 + gq * r1_dw + cin;
-                    for (int rgl = sl; rgl < nrg; rgl += nsl) {
-                        uint32_t u[BITS];
-                        planar_unit<BITS>(col + rgl * (32 * BITS), 32, u);
-                        if (MODE == kAffine) acc = unit_fma_codes<BITS>(u, rs + rgl * 32, acc);
-                        else if (a.lds_levels) acc = unit_grad_table<BITS>(u, L.Ls + c * K, rs + rgl * 32, acc);
-                        else acc = unit_grad_table<BITS>(u, Lg + (size_t)c * K, rs + rgl * 32, acc);
-                    }
+            if (persistent) {
+                if (t + 1 < t_end) {
+                    load_grad_units(t + 1, c1nxt);
+                    load_labels(t + 1, bnext);
                 }
-                L.gpart[tid] = acc;
-                __syncthreads();
-                if (tid < CW) {
-                    float sacc = 0.0f;
-                    for (int q = 0; q < nsl; ++q) sacc += L.gpart[q * CW + tid];
-                    float g = sacc;
-                    if (MODE == kAffine) {
-                        float Rtot = 0.0f;
-                        for (int q = 0; q < kWaves; ++q) Rtot += L.wsum[q];
-                        g = L.los[tid] * Rtot + L.dls[tid] * sacc;
-                    }
-                    g = (j0 + tid < a.d) ? g / (float)B : 0.0f;
-                    gs[tid] = g;
-                    if (dbg_g && j0 + tid < a.d) dbg_g[j0 + tid] = g;
+                if (t + 2 < t_end) load_dot_units(t + 2, c2nxt);
+            }
+
+            // gradient pass: one partial sum per owned unit (a chain over its 32 samples)
+            float part[UPT];
+#pragma unroll
+            for (int k = 0; k < UPT; ++k) {
+                part[k] = 0.0f;
+                const int rgl = g_sl + k * nsl;
+                if (g_live && rgl < nrg) {
+                    const float *rr = rs + rgl * 32;
+                    if (MODE == kAffine) part[k] = unit_fma_codes<BITS>(c1cur[k], rr, 0.0f);
+                    else if (a.lds_levels) part[k] = unit_grad_table<BITS>(c1cur[k], L.Ls + g_c * K, rr, 0.0f);
+                    else part[k] = unit_grad_table<BITS>(c1cur[k], Lg + (size_t)g_c * K, rr, 0.0f);
                 }
+            }
+            // gpart[sample group][feature]
+#pragma unroll
+            for (int k = 0; k < UPT; ++k) {
+                const int rgl = g_sl + k * nsl;
+                if (rgl < nrg) L.gpart[rgl * CW + g_c] = part[k];
+            }
+            lds_barrier();
+            if (tid < CW) {
+                // the unit sums are added in sample-group order
+                float sacc = 0.0f;
+                for (int rgl = 0; rgl < nrg; ++rgl) sacc += L.gpart[rgl * CW + tid];
+                float g = sacc;
+                if (MODE == kAffine) {
+                    float Rtot = 0.0f;
+                    for (int q = 0; q < kWaves; ++q) Rtot += L.wsum[q];
+                    g = L.los[tid] * Rtot + L.dls[tid] * sacc;
+                }
+                g = (j0 + tid < a.d) ? __fdiv_rn(g, (float)B) : 0.0f;
+                gs[tid] = g;
+                if (dbg_g && j0 + tid < a.d) dbg_g[j0 + tid] = g;
             }
             if (B < 32) {
                 // a short batch shares its sample group with its neighbours: clear its residuals
-                __syncthreads();
+                lds_barrier();
                 for (int i = tid; i < B; i += kThreads) rs[k0 + i] = 0.0f;
             }
             if (a.grad_bits > 0) {
                 double *ng = a.nrm + 1024 + (size_t)(t & 1) * 512;
-                __syncthreads();
+                lds_barrier();
                 if (tid < CW) red[tid] = (double)gs[tid] * (double)gs[tid];
                 lds_tree_sum(red, CW);
                 own_sq = red[0];
-                __syncthreads();
+                lds_barrier();
                 if (!local && tid == 0) store_dev(ng + w, own_sq);
                 if (!persistent && tid < CW && j0 + tid < a.d) a.gbuf[j0 + tid] = gs[tid];
                 if (grid_sync) {
                     vm_wait_all();
-                    __syncthreads();
+                    lds_barrier();
                     if (wave == 0 && lane == 0) arrive_and_poll();
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                 }
@@ -582,7 +623,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
         // the barrier at the top of the next step publishes xs, ys, wsum
         ZIPML_TICK(6);
     }
-    __syncthreads();
+    lds_barrier();
 #ifdef ZIPML_PHASE_TIMING
     if (w == 0 && tid == 0)
         for (int k = 0; k < 8; ++k) ((long long *)(a.nrm + 2048))[k] = prof_[k];
@@ -592,7 +633,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 // ---------------------------------------------------------------------------------------------
 // The epoch kernel: LDS carve, one-time set-up, then the step loop of the right mode.
 // ---------------------------------------------------------------------------------------------
-template <int BITS, bool INT, bool FAST>
+template <int BITS, bool INT, bool FAST, int UPT>
 __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
 {
     constexpr int K = 1 << BITS;
@@ -609,7 +650,6 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     size_t off = 0;
     auto carve = [&](size_t bytes) { void *p = smem + off; off += (bytes + 15) & ~(size_t)15; return p; };
     Lds L;
-    L.ring = (uint32_t *)carve((size_t)2 * a.slot_bytes);
     L.Ls = (float *)carve(a.lds_levels ? (size_t)CW * K * 4 : 0);
     L.Gs = (uint16_t *)carve(INT && !a.ident_grid ? (size_t)CW * K * 2 : 0);
     L.xs = (float *)carve(CW * 4);
@@ -619,8 +659,10 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     L.gs = (float *)carve(CW * 4);
     L.ms = (int *)carve(CW * 4);
     L.rs = (float *)carve((size_t)Rlen * 4);
+    L.bs = (float *)carve((size_t)B * 4);
     L.zl = (float *)carve(a.W == 1 ? (size_t)(B + 4) * 4 : 0);
-    L.gpart = (float *)carve(kThreads * 4);
+    L.zp = (uint32_t *)carve(a.GQ > 1 ? (size_t)a.GQ * B * 4 : 0);
+    L.gpart = (float *)carve((size_t)kMaxUpt * kThreads * 4);
     L.red = (double *)carve(512 * 8);
     L.wsum = (float *)carve(2 * kWaves * 4);
     L.isum = (int *)carve(kWaves * 4);
@@ -663,9 +705,9 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         if (lane == 0) L.wsum[kWaves + wave] = part;
     }
 
-    if (INT) sgd_steps<BITS, kInt, FAST>(a, L);
-    else if (affine) sgd_steps<BITS, kAffine, FAST>(a, L);
-    else sgd_steps<BITS, kTable, FAST>(a, L);
+    if (INT) sgd_steps<BITS, kInt, FAST, UPT>(a, L);
+    else if (affine) sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
+    else sgd_steps<BITS, kTable, FAST, UPT>(a, L);
 
     // ---- write the model slice back
     if (FAST || a.seg_last >= 3)
@@ -682,7 +724,7 @@ __global__ void k_sgd_reset(int *status, uint32_t *sync, float *acc, int words, 
 }
 
 struct Plan {
-    int GQ, W, slot_bytes, lds_levels;
+    int GQ, W, lds_levels, upt;
     size_t shmem;
 };
 
@@ -700,27 +742,25 @@ static size_t up16(size_t v) { return (v + 15) & ~(size_t)15; }
 
 // LDS needed for GQ feature groups per workgroup; 0 if it does not fit.
 static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool solo, int lds_limit,
-                       int &slot_bytes, int &lds_levels)
+                       int &lds_levels)
 {
     const int K = 1 << bits, CW = 32 * GQ;
     const int nrg = batch >= 32 ? (int)(batch / 32) : 1;
-    const int nblk = (int)((batch + 63) / 64);
-    const size_t slot = (size_t)GQ * ((size_t)nblk * 64 * bits + (size_t)nrg * 32 * bits) * 4 +
-                        (size_t)((batch + 3) & ~3) * 4;
-    if (slot > (size_t)lds_limit) return 0;
-    slot_bytes = (int)up16(slot);
-    lds_levels = (size_t)CW * K * 4 <= 32768 ? 1 : 0;
-    const size_t fixed = (lds_levels ? up16((size_t)CW * K * 4) : 0) +
+    lds_levels = (size_t)CW * K * 4 <= 65536 ? 1 : 0;
+    const size_t total = (lds_levels ? up16((size_t)CW * K * 4) : 0) +
                          (int_table ? up16((size_t)CW * K * 2) : 0) + 6 * up16((size_t)CW * 4) +
-                         up16((size_t)nrg * 32 * 4) + (solo ? up16((size_t)(batch + 4) * 4) : 0) +
-                         up16(kThreads * 4) + up16(512 * 8) + up16(2 * kWaves * 4) + up16(kWaves * 4);
-    const size_t total = 2 * (size_t)slot_bytes + fixed;
+                         up16((size_t)nrg * 32 * 4) + up16((size_t)batch * 4) +
+                         (solo ? up16((size_t)(batch + 4) * 4) : 0) +
+                         (GQ > 1 ? up16((size_t)GQ * batch * 4) : 0) +
+                         up16((size_t)kMaxUpt * kThreads * 4) + up16(512 * 8) +
+                         up16(2 * kWaves * 4) + up16(kWaves * 4);
     return total <= (size_t)lds_limit ? total : 0;
 }
 
 // Chooses how many feature groups a workgroup owns.  A step costs one device-wide exchange whose
-// latency grows with the number of workgroups, so small steps want few, fat workgroups; the two
-// LDS slots and the number of compute units bound the choice from both sides.
+// latency grows with the number of workgroups, so small steps want few, fat workgroups; the
+// registers that hold a thread's units (at most kMaxUpt per pass) and the number of compute units
+// bound the choice from both sides.
 static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, Plan &p)
 {
     int cus = 0, lds = 0;
@@ -734,14 +774,17 @@ static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, Plan 
     for (int GQ = 1; GQ <= 8; GQ <<= 1) {
         const int64_t W = (d32 + GQ - 1) / GQ;
         if (W > cus || W > 512) continue;
-        int slot = 0, ll = 0;
-        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, lds, slot, ll);
-        if (!sh) break;                    // larger GQ only needs more LDS
+        if (batch * GQ > (int64_t)kMaxUpt * kThreads) break;   // units per thread
+        int ll = 0;
+        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, lds, ll);
+        if (!sh) break;
         best = GQ;
-        p.GQ = GQ; p.W = (int)W; p.slot_bytes = slot; p.lds_levels = ll; p.shmem = sh;
+        p.GQ = GQ; p.W = (int)W; p.lds_levels = ll; p.shmem = sh;
+        const int64_t units = batch * GQ;
+        p.upt = units <= kThreads ? 1 : units <= 2 * kThreads ? 2 : 4;
         if (W <= kTargetW) break;
     }
-    return best ? ZIPML_OK : ZIPML_EUNSUPPORTED;   // batch too large for LDS, or d too large
+    return best ? ZIPML_OK : ZIPML_EUNSUPPORTED;   // batch too large for one step in registers
 }
 
 template <int BITS, bool INT>
@@ -749,7 +792,12 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
 {
     const bool debug = a.dbg_m || a.dbg_acc || a.dbg_gq || a.dbg_r || a.dbg_g;
     const bool fast = !stepwise && !debug;
-    const void *kern = fast ? (const void *)k_sgd<BITS, INT, true> : (const void *)k_sgd<BITS, INT, false>;
+    const void *kern = (const void *)k_sgd<BITS, INT, false, kMaxUpt>;
+    if (fast) {
+        kern = p.upt == 1 ? (const void *)k_sgd<BITS, INT, true, 1>
+             : p.upt == 2 ? (const void *)k_sgd<BITS, INT, true, 2>
+                          : (const void *)k_sgd<BITS, INT, true, 4>;
+    }
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)p.shmem)))
         return ZIPML_ELAUNCH;
@@ -862,7 +910,6 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.GQ = p.GQ;
     a.W = p.W;
     a.lds_levels = p.lds_levels;
-    a.slot_bytes = p.slot_bytes;
     a.status = (int *)(ws + Workspace::kStatus);
     a.sync = (uint32_t *)(ws + Workspace::kSync);
     a.nrm = (double *)(ws + Workspace::kNorm);
