@@ -301,7 +301,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 
     const int64_t t_end = a.step0 + a.nsteps;
 #ifdef ZIPML_PHASE_TIMING
-    long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long prof_[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = wall_clock64();
 #endif
     int Wp = 1;
@@ -389,8 +389,10 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
             // dot pass: the partial sums of a sample over the owned feature groups are combined in
             // LDS before they are published
             float Cq = 0.0f;
-            if (MODE == kAffine)
+            if (MODE == kAffine) {
+#pragma unroll
                 for (int q = 0; q < kWaves; ++q) Cq += L.wsum[kWaves + q];
+            }
             auto publish = [&](int i, float pf, int pi) {
                 if (local) {
                     if (kIsInt) ((int *)L.zl)[i] = pi; else L.zl[i] = pf;
@@ -429,6 +431,14 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     }
                     publish(i, pf, pi);
                 }
+            }
+            // Workgroup 0 clears the accumulator of step t+1: every workgroup has passed the barrier
+            // of step t-1, so nobody reads the sums of step t-2 any more, and the stores are
+            // acknowledged (together with the atomics) before workgroup 0 arrives at the barrier
+            // of step t, after which the first additions of step t+1 can come.
+            if (grid_sync && w == 0) {
+                float *nxt = a.acc + (size_t)((t + 1) % 3) * a.acc_words;
+                for (int i = tid; i < B + 1; i += kThreads) store_dev(nxt + i, 0.0f);
             }
             ZIPML_TICK(1);
             if (grid_sync) {
@@ -500,12 +510,6 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     if (!local && lane == 0)
                         for (int q = 1; q < kWaves; ++q) L.wsum[q] = 0.0f;
                 }
-                // the accumulator of step t+2 is free once every workgroup has passed the barrier
-                // of step t; workgroup 0 clears it now
-                if (grid_sync && w == 0) {
-                    float *nxt = a.acc + (size_t)((t + 2) % 3) * a.acc_words;
-                    for (int i = lane; i < B + 1; i += kWave) store_dev(nxt + i, 0.0f);
-                }
             }
             lds_barrier();    // rs[], wsum[] ready
             ZIPML_TICK(4);
@@ -528,6 +532,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 if (t + 2 < t_end) load_dot_units(t + 2, c2nxt);
             }
 
+            ZIPML_TICK(8);
             // gradient pass: one partial sum per owned unit (a chain over its 32 samples)
             float part[UPT];
 #pragma unroll
@@ -547,14 +552,24 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 const int rgl = g_sl + k * nsl;
                 if (rgl < nrg) L.gpart[rgl * CW + g_c] = part[k];
             }
+            ZIPML_TICK(9);
             lds_barrier();
+            ZIPML_TICK(10);
             if (tid < CW) {
                 // the unit sums are added in sample-group order
                 float sacc = 0.0f;
-                for (int rgl = 0; rgl < nrg; ++rgl) sacc += L.gpart[rgl * CW + tid];
+                for (int r0 = 0; r0 < nrg; r0 += 8) {
+                    float v[8];     // eight LDS reads in flight, then added in order
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) v[q] = L.gpart[(r0 + q < nrg ? r0 + q : r0) * CW + tid];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (r0 + q < nrg) sacc += v[q];
+                }
                 float g = sacc;
                 if (MODE == kAffine) {
                     float Rtot = 0.0f;
+#pragma unroll
                     for (int q = 0; q < kWaves; ++q) Rtot += L.wsum[q];
                     g = L.los[tid] * Rtot + L.dls[tid] * sacc;
                 }
@@ -626,7 +641,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
     lds_barrier();
 #ifdef ZIPML_PHASE_TIMING
     if (w == 0 && tid == 0)
-        for (int k = 0; k < 8; ++k) ((long long *)(a.nrm + 2048))[k] = prof_[k];
+        for (int k = 0; k < 12; ++k) ((long long *)(a.nrm + 2048))[k] = prof_[k];
 #endif
 }
 
