@@ -31,7 +31,27 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the minibatch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch plain device copies of known size (untimed), so that a "
+                         "rocprofv3 --pmc run of this command yields the HBM counter scale")
     return ap.parse_args()
+
+
+def recorded_traffic(workload, batch):
+    """HBM bytes per epoch launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), as
+    recorded in the text summary under profiles/ for this workload; None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"sgd_epoch_{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    fields = line.split()
+                    if len(fields) >= 4 and fields[2] == "batch" and int(fields[3]) != batch:
+                        return None
+                    return float(fields[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, A_rows, b_rows, L, seconds):
@@ -141,6 +161,14 @@ def main():
     per_epoch_ms = [ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)]
     kern_ms = sum(per_epoch_ms) / len(per_epoch_ms)
 
+    if args.copy_calibration:
+        # a copy of known size on the same stream: 256 MiB read + 256 MiB written per launch
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     loss_ms = timed(lambda: zipml.loss(bd, x, n, d, ws, A=Ad_full, lda=d))
     final_loss = zipml.loss(bd, x, n, d, ws, A=Ad_full, lda=d)
     loss_p_ms = timed(lambda: zipml.loss(bd, x, n, d, ws, packed=p2, copy=2, levels_t=lev, bits=bits))
@@ -159,14 +187,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u8 codes, f32 accumulate",
+        "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: n={n}, d={d}, {bits}-bit uniform levels, batch {B}, "
                                f"lr {w.lr}, fp32 model", "minibatch_steps_per_epoch": n // B,
                    "packed_bytes_per_epoch": int(alg_bytes)},
         "packed_GBps": alg_bytes * args.steps / wall / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(w.name, B),
                      "kernel": f"k_sgd<{bits}> (persistent epoch kernel)",
                      "kernel_ms": kern_ms, "us_per_minibatch_step": kern_ms * 1e3 / (n // B)},
         "other_ms": {"levels": levels_ms, "quantize": quant_ms, "loss_fp32": loss_ms,

@@ -797,7 +797,11 @@ static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, Plan 
         p.GQ = GQ; p.W = (int)W; p.lds_levels = ll; p.shmem = sh;
         const int64_t units = batch * GQ;
         p.upt = units <= kThreads ? 1 : units <= 2 * kThreads ? 2 : 4;
-        if (W <= kTargetW) break;
+        // stop at the preferred workgroup count -- unless a single workgroup is within reach:
+        // it needs no device-wide exchange at all
+        const int64_t gq_solo = d32 <= 8 ? (d32 <= 1 ? 1 : d32 <= 2 ? 2 : d32 <= 4 ? 4 : 8) : 0;
+        const bool solo_possible = gq_solo && batch * gq_solo <= (int64_t)kMaxUpt * kThreads;
+        if (W <= kTargetW && !(solo_possible && W > 1)) break;
     }
     return best ? ZIPML_OK : ZIPML_EUNSUPPORTED;   // batch too large for one step in registers
 }
