@@ -86,3 +86,24 @@ def rel_l2(a, b):
     a = np.asarray(a, np.float64)
     b = np.asarray(b, np.float64)
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def oracle_quantize_rows(A, L, bits, seed, epoch, workers=16, rows_per_task=2048):
+    """The oracle's quantiser over all rows of A, row ranges spread over host threads.
+
+    Every code is a pure function of (seed, epoch, row, column), so splitting by rows changes
+    nothing; the oracle call releases the interpreter lock while it runs.
+    """
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+
+    n = A.shape[0]
+    starts = list(range(0, n, rows_per_task))
+
+    def part(r0):
+        return oracle.quantize(A[r0:r0 + rows_per_task], L, bits, seed, epoch, row0=r0)
+
+    with ThreadPoolExecutor(workers) as ex:
+        res = list(ex.map(part, starts))
+    return (np.concatenate([r[0] for r in res]), np.concatenate([r[1] for r in res]))
