@@ -40,11 +40,13 @@ inline Layout make_layout(int64_t n, int64_t d, int bits)
 // Workspace carving (all offsets 256-byte aligned).
 struct Workspace {
     static constexpr size_t kStatus = 0;          // int32 status word + counters   (4 KiB)
-    static constexpr size_t kSync = 4096;         // grid barrier counters          (4 KiB)
+    static constexpr size_t kSync = 4096;         // grid barrier counter                  (256 B)
+    static constexpr size_t kBound = 4096 + 256;  // magnitude bounds of the dot exchange: 2 doubles
     static constexpr size_t kNorm = 8192;         // norm exchange: 2 x 3 x 512 doubles (24 KiB)
-    static constexpr size_t kAcc = 8192 + 24576;  // 3 reduction buffers of batch_pad + 64 words
+    static constexpr size_t kAcc = 8192 + 24576;  // 4 exchange buffers of acc_words 64-bit words
+    static constexpr int kAccBuffers = 4;
     static size_t acc_words(int64_t batch) { return (size_t)round_up(batch + 64, 64); }
-    static size_t sgd_bytes(int64_t batch) { return kAcc + 3 * acc_words(batch) * 4; }
+    static size_t sgd_bytes(int64_t batch) { return kAcc + kAccBuffers * acc_words(batch) * 8; }
 };
 
 // Called on entry of every API function: hipGetLastError() is sticky per host thread, so an

@@ -6,11 +6,18 @@
 // keeps its slice of the model in LDS.  Per step it
 //   1. takes the partial dot products of the `batch` samples over its features from copy 2
 //      (sample-major units) and adds them into a device-wide accumulator (device-scope atomics),
-//   2. meets the other workgroups at ONE grid-wide barrier,
-//   3. reads the `batch` sums, forms the residuals, takes its slice of the mean gradient from
-//      copy 1 (feature-major units) and updates its slice of the model, locally.
+//   2. polls the accumulator until every workgroup's contribution has arrived,
+//   3. forms the residuals, takes its slice of the mean gradient from copy 1 (feature-major
+//      units) and updates its slice of the model, locally.
 // A step moves little data and is bound by the latency of that one device-wide exchange, so the
 // kernel is organised around the exchange:
+//   - one trip instead of three.  A 64-bit accumulator word carries an arrival count in its top
+//     10 bits and the sum, as a biased fixed-point integer, below: one atomic add per (workgroup,
+//     sample) delivers data and arrival together, so there is no "wait until my atomics are
+//     done", no separate barrier and no read of the sums after it.  Integer addition is
+//     associative, so the sums -- and with them the whole epoch -- do not depend on the order in
+//     which the workgroups arrive.  The fixed-point scale of a step is derived from a bound on
+//     the partial sums that every workgroup tracks identically (see sgd_steps);
 //   - the packed data does not depend on the model.  Every thread owns the same units (sample x
 //     feature group for the dot pass, feature x sample group for the gradient pass) in every
 //     step and fetches them into registers ahead of time: right after the sums of step t have
@@ -18,10 +25,11 @@
 //     a step from which no latency-critical memory operation follows for about a microsecond
 //     (loads of a wave, and of a compute unit's memory pipeline, return in order, so a long load
 //     in flight would hold back the atomics' acknowledgement, the barrier poll and the sums);
-//   - exchanged data moves only through device-scope atomics / loads, so the barrier needs no
-//     cache write-back, only "my atomics have been performed" (s_waitcnt vmcnt(0));
+//   - exchanged data moves only through device-scope atomics / loads, so no cache write-back or
+//     invalidation is ever needed;
 //   - workgroup barriers inside a step order LDS traffic only (lds_barrier).
-// End-to-end mode adds two small exchanges per step (the l2 norms of model and gradient).
+// End-to-end mode adds two small exchanges per step (the l2 norms of model and gradient), each
+// closed by a grid barrier (one monotonically increasing arrival counter).
 #include "zipml_device.h"
 #include "zipml_host.h"
 
@@ -33,7 +41,32 @@ namespace zipml {
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kMaxUpt = 4;                        // units per thread and pass that fit in registers
-constexpr uint32_t kSpinLimit = 1u << 24;         // bounded wait: a lost workgroup ends in ZIPML_ETIMEOUT
+constexpr uint32_t kSpinLimit = 1u << 22;         // bounded wait: a lost workgroup ends in ZIPML_ETIMEOUT
+
+// Exchange word: [63:54] arrival count, [53:0] sum of (value + kBias) over the arrived workgroups.
+// |value| < 2^44 for every contribution, so the low field never carries into the count.
+constexpr int kCountShift = 54;
+constexpr long long kBias = 1ll << 44;
+constexpr uint64_t kPayloadMask = (1ull << kCountShift) - 1ull;
+constexpr int kScaleBits = 41;                    // 2^kexp * (bound on a sum) < 2^kScaleBits
+
+__device__ __forceinline__ uint64_t pack_int(long long q)
+{
+    return (1ull << kCountShift) + (uint64_t)(q + kBias);
+}
+// fp32 value -> fixed point with 2^-kexp resolution (exact unless |p| < 2^(24-kexp)); values
+// outside the field, infinities and NaNs are clamped so that the count stays intact.
+__device__ __forceinline__ uint64_t pack_fp(float p, int kexp)
+{
+    const double lim = (double)(kBias - 1);
+    double q = ldexp((double)p, kexp);
+    q = fmin(fmax(q, -lim), lim);
+    return pack_int(__double2ll_rn(q));
+}
+__device__ __forceinline__ long long unpack_sum(uint64_t v, int W)
+{
+    return (long long)(v & kPayloadMask) - (long long)W * kBias;
+}
 
 enum Mode { kAffine = 0, kTable = 1, kInt = 2 };
 
@@ -61,8 +94,9 @@ struct SgdArgs {
     int *status;
     uint32_t *sync;
     double *nrm;           // [2 kinds][2 slots][512] (+ 1024 spare)
-    float *acc;            // [3][acc_words]
+    uint64_t *acc;         // [4][acc_words] exchange words
     int acc_words;
+    const double *bound;   // [0] sum_j maxabs(L_j)|x_j| at launch, [1] sum_j maxabs(L_j)^2
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     // debug outputs (may be null)
     int32_t *dbg_m, *dbg_acc, *dbg_gq;
@@ -76,12 +110,12 @@ struct Lds {
     float *xs, *ys, *los, *dls, *gs;   // model slice, delta*x, lo, delta, gradient slice  [CW]
     int *ms;          // model codes [CW]
     float *rs;        // residuals [Rlen]
-    float *bs;        // labels of the current step [B]
     float *zl;        // local dot products [B+4]   (single workgroup only)
     uint32_t *zp;     // per-unit partial dot products [GQ][B]  (GQ > 1 only)
     float *gpart;     // gradient partial sums [kMaxUpt * kThreads]
     double *red;      // reduction scratch [512]
-    float *wsum;      // [0..kWaves): residual sum parts, [kWaves..2kWaves): parts of sum_j lo_j x_j
+    float *wsum;      // per wave: [0..kWaves) parts of sum_i r_i, [kWaves..2kWaves) parts of
+                      // sum_j lo_j x_j, [2kWaves..3kWaves) parts of sum_i |r_i|
     int *isum;        // [kWaves]
 };
 
@@ -273,7 +307,8 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
             }
         }
     };
-    constexpr int kBpt = kMaxUpt;                  // labels per thread (batch <= kMaxUpt * kThreads)
+    constexpr int kBpt = UPT;                      // samples per thread (batch <= UPT * kThreads):
+                                                   // thread tid looks after samples tid + k*kThreads
     auto load_labels = [&](int64_t t, float (&dst)[kBpt]) {
 #pragma unroll
         for (int k = 0; k < kBpt; ++k) {
@@ -304,6 +339,12 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
     long long prof_[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = wall_clock64();
 #endif
+    // Bound on the magnitude of any partial or full dot product of the current model,
+    // sum_j maxabs(L_j)|x_j|: exact at launch (host-side pre-pass), then advanced every step by a
+    // bound on the model's change.  Every workgroup computes it from the same numbers in the same
+    // order, so all agree on the fixed-point scale without talking to each other.
+    double bound_hat = a.bound[0];
+    const double lambda = a.bound[1];
     int Wp = 1;
     while (Wp < W) Wp <<= 1;
     const int s_m = (1 << (a.model_bits > 0 ? a.model_bits - 1 : 1)) - 1;
@@ -329,18 +370,20 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
     load_labels(a.step0, bnext);
 
     for (int64_t t = a.step0; t < t_end; ++t) {
-        float *accf = a.acc + (size_t)(t % 3) * a.acc_words;
-        int *acci = (int *)accf;
+        uint64_t *const acc = a.acc + (size_t)(t & 3) * a.acc_words;
         const int k0 = B >= 32 ? 0 : (int)((t * B) % 32);  // batch offset inside its sample group
 
         ZIPML_TICK(7);
-#pragma unroll
-        for (int k = 0; k < kBpt; ++k) {
-            const int i = tid + k * kThreads;
-            if (i < B) L.bs[i] = bnext[k];
-        }
-        lds_barrier();     // labels, and the model slice written at the end of the previous step
+        lds_barrier();     // the model slice written at the end of the previous step
         ZIPML_TICK(0);
+        // fixed-point scale of this step's exchange: 2^kexp * bound_hat < 2^kScaleBits
+        int kexp = 0;
+        if (!kIsInt && !local) {
+            int e = 0;
+            (void)frexp(bound_hat, &e);
+            kexp = kScaleBits - e;
+            kexp = kexp < -1000 ? -1000 : kexp > 1000 ? 1000 : kexp;
+        }
 
         // ================= segment 0: ||x||_2 partial (model quantisation only) =================
         float Mx = 0.0f, sigma = 0.0f;
@@ -383,7 +426,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     int tot = 0;
                     for (int q = 0; q < kWaves; ++q) tot += L.isum[q];
                     if (local) ((int *)L.zl)[B] = tot;
-                    else if (tot != 0) add_dev(acci + B, tot);
+                    else add_dev(acc + B, pack_int(tot));
                 }
             }
             // dot pass: the partial sums of a sample over the owned feature groups are combined in
@@ -397,7 +440,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 if (local) {
                     if (kIsInt) ((int *)L.zl)[i] = pi; else L.zl[i] = pf;
                 } else {
-                    if (kIsInt) add_dev(acci + i, pi); else add_dev(accf + i, pf);
+                    add_dev(acc + i, kIsInt ? pack_int(pi) : pack_fp(pf, kexp));
                 }
             };
             const bool combine = ngroups > 1;
@@ -432,22 +475,19 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     publish(i, pf, pi);
                 }
             }
-            // Workgroup 0 clears the accumulator of step t+1: every workgroup has passed the barrier
-            // of step t-1, so nobody reads the sums of step t-2 any more, and the stores are
-            // acknowledged (together with the atomics) before workgroup 0 arrives at the barrier
-            // of step t, after which the first additions of step t+1 can come.
-            if (grid_sync && w == 0) {
-                float *nxt = a.acc + (size_t)((t + 1) % 3) * a.acc_words;
-                for (int i = tid; i < B + 1; i += kThreads) store_dev(nxt + i, 0.0f);
+            // The last wave of workgroup 0 clears the exchange words of step t+2 (four buffers in
+            // rotation).  Workgroup 0 is past the exchange of step t-1, so every workgroup has
+            // contributed to step t-1 and has therefore finished reading step t-2, the last user of
+            // that buffer.  The wave waits for the stores to be performed before it goes on; its
+            // contributions to step t+1 come after that, and nobody adds to step t+2 before having
+            // seen all contributions to step t+1.  The wait falls into time this wave would spend
+            // waiting for the residuals anyway.
+            if (grid_sync && w == 0 && wave == kWaves - 1) {
+                uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
+                for (int i = lane; i < B + 1; i += kWave) store_dev(nxt + i, (uint64_t)0);
+                vm_wait_all();
             }
             ZIPML_TICK(1);
-            if (grid_sync) {
-                vm_wait_all();      // this wave's atomics have been performed
-                lds_barrier();      // ... and so have those of the whole workgroup
-                ZIPML_TICK(2);
-                if (wave == 0 && lane == 0) arrive_and_poll();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // no load moves above the poll
-            }
         }
         if (seg_last < 2) continue;
 
@@ -459,60 +499,83 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 sigma = Mx > 0.0f ? __fdiv_rn(Mx, (float)s_m) : 0.0f;
             }
             ZIPML_TICK(3);
-            // wave 0 reads the sums and forms the residuals
+            // Every thread looks after the samples tid + q*kThreads: it polls their exchange words
+            // until all W contributions are in, and forms the residuals from the sums and the
+            // labels it holds in registers.  The loads are issued back to back (indices are
+            // clamped, not branched on): each costs a full trip to the coherence point.
             if (local) lds_barrier();   // zl[] written by all waves
-            if (wave == 0 || local) {
-                double summ = 0.0;
-                if (kIsInt) summ = local ? (double)((int *)L.zl)[B] : (double)load_dev(acci + B);
-                float rsum = 0.0f;
-                const int stride = local ? kThreads : kWave;
-                constexpr int kBatchLoads = 4;   // device-scope loads in flight per lane
-                for (int base = local ? tid : lane; base < B; base += stride * kBatchLoads) {
-                    // issue all loads first: each costs a full trip to the coherence point
-                    // (indices are clamped, not branched on, so that the loads issue back to back)
-                    uint32_t raw[kBatchLoads];
-                    if (local) {
+            float rsum = 0.0f, rabs = 0.0f;
+            if (tid < B) {
+                uint64_t raw[kBpt], rawm = 0;
+                if (local) {
 #pragma unroll
-                        for (int q = 0; q < kBatchLoads; ++q) {
-                            const int i = base + q * stride;
-                            raw[q] = ((const uint32_t *)L.zl)[i < B ? i : B - 1];
-                        }
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < kBatchLoads; ++q) {
-                            const int i = base + q * stride;
-                            raw[q] = load_dev((const uint32_t *)accf + (i < B ? i : B - 1));
-                        }
+                    for (int q = 0; q < kBpt; ++q) {
+                        const int i = tid + q * kThreads;
+                        raw[q] = ((const uint32_t *)L.zl)[i < B ? i : B - 1];
                     }
+                    if (kIsInt) rawm = (uint64_t)(uint32_t)((const int *)L.zl)[B];
+                } else {
+                    uint32_t spins = 0;
+#pragma unroll 1
+                    for (;;) {
 #pragma unroll
-                    for (int q = 0; q < kBatchLoads; ++q) {
-                        const int i = base + q * stride;
-                        if (i < B) {
-                            float r;
-                            if (kIsInt) {
-                                const int av = (int)raw[q];
-                                const double z = (double)sigma * ((double)a.grid_lo * summ +
-                                                                  (double)a.grid_step * (double)av);
-                                r = (float)z - L.bs[i];
-                                if (dbg_acc && w == 0) dbg_acc[i] = av;
-                            } else {
-                                r = __uint_as_float(raw[q]) - L.bs[i];
-                            }
-                            rs[k0 + i] = r;
-                            rsum += r;
-                            if (dbg_r && w == 0) dbg_r[i] = r;
+                        for (int q = 0; q < kBpt; ++q) {
+                            const int i = tid + q * kThreads;
+                            raw[q] = load_dev(acc + (i < B ? i : B - 1));
+                        }
+                        if (kIsInt) rawm = load_dev(acc + B);
+                        bool all = !kIsInt || (int)(rawm >> kCountShift) == W;
+#pragma unroll
+                        for (int q = 0; q < kBpt; ++q) all = all && (int)(raw[q] >> kCountShift) == W;
+                        if (all || dead) break;
+                        if (++spins > kSpinLimit) {
+                            store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                            dead = true;
                         }
                     }
                 }
-                if (MODE == kAffine) {
-                    rsum = wave_sum_dpp(rsum);
-                    if (lane == 0) L.wsum[wave] = rsum;
-                    if (!local && lane == 0)
-                        for (int q = 1; q < kWaves; ++q) L.wsum[q] = 0.0f;
+                const double summ = !kIsInt ? 0.0
+                                  : local ? (double)(int)(uint32_t)rawm : (double)unpack_sum(rawm, W);
+#pragma unroll
+                for (int q = 0; q < kBpt; ++q) {
+                    const int i = tid + q * kThreads;
+                    if (i < B) {
+                        float r;
+                        if (kIsInt) {
+                            const int av = local ? (int)(uint32_t)raw[q] : (int)unpack_sum(raw[q], W);
+                            const double z = (double)sigma * ((double)a.grid_lo * summ +
+                                                              (double)a.grid_step * (double)av);
+                            r = (float)z - bnext[q];
+                            if (dbg_acc && w == 0) dbg_acc[i] = av;
+                        } else {
+                            const float z = local ? __uint_as_float((uint32_t)raw[q])
+                                                  : (float)ldexp((double)unpack_sum(raw[q], W), -kexp);
+                            r = z - bnext[q];
+                        }
+                        rs[k0 + i] = r;
+                        rsum += r;
+                        rabs += fabsf(r);
+                        if (dbg_r && w == 0) dbg_r[i] = r;
+                    }
+                }
+            }
+            if (MODE != kInt) {
+                rsum = wave_sum_dpp(rsum);
+                rabs = wave_sum_dpp(rabs);
+                if (lane == 0) {
+                    L.wsum[wave] = rsum;
+                    L.wsum[2 * kWaves + wave] = rabs;
                 }
             }
             lds_barrier();    // rs[], wsum[] ready
             ZIPML_TICK(4);
+            if (!kIsInt && !local) {
+                // |x_j| grows by at most lr * maxabs(L_j) * mean_i |r_i| in this step
+                float Rabs = 0.0f;
+#pragma unroll
+                for (int q = 0; q < kWaves; ++q) Rabs += L.wsum[2 * kWaves + q];
+                bound_hat += fabs((double)a.lr) * lambda * ((double)Rabs / (double)B);
+            }
 
             // Rotate the register sets and request what later steps need: copy 1 of step t+1,
             // copy 2 of step t+2, labels of step t+1.  Nothing latency-critical touches memory
@@ -674,12 +737,11 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     L.gs = (float *)carve(CW * 4);
     L.ms = (int *)carve(CW * 4);
     L.rs = (float *)carve((size_t)Rlen * 4);
-    L.bs = (float *)carve((size_t)B * 4);
     L.zl = (float *)carve(a.W == 1 ? (size_t)(B + 4) * 4 : 0);
     L.zp = (uint32_t *)carve(a.GQ > 1 ? (size_t)a.GQ * B * 4 : 0);
     L.gpart = (float *)carve((size_t)kMaxUpt * kThreads * 4);
     L.red = (double *)carve(512 * 8);
-    L.wsum = (float *)carve(2 * kWaves * 4);
+    L.wsum = (float *)carve(3 * kWaves * 4);
     L.isum = (int *)carve(kWaves * 4);
 
     // ---- one-time set-up: level slice, model slice
@@ -713,7 +775,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         L.ms[c] = 0;
     }
     for (int i = tid; i < Rlen; i += kThreads) L.rs[i] = 0.0f;
-    if (tid < 2 * kWaves) L.wsum[tid] = 0.0f;
+    if (tid < 3 * kWaves) L.wsum[tid] = 0.0f;
     __syncthreads();
     if (affine) {
         const float part = wave_sum_dpp(tid < CW ? L.los[tid] * L.xs[tid] : 0.0f);
@@ -730,12 +792,38 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
             if (j0 + c < a.d) a.x[j0 + c] = L.xs[c];
 }
 
-// Clears the barrier counter, the status word and the three accumulators.
-__global__ void k_sgd_reset(int *status, uint32_t *sync, float *acc, int words, int clear_status)
+// Launch preparation: clears the barrier counter, the status word and exchange words; block 0
+// also takes the two magnitude bounds of the dot exchange from the levels and the current model,
+//   bound[0] = sum_j maxabs(L_j) |x_j|,   bound[1] = sum_j maxabs(L_j)^2,
+// in fp64 with a fixed summation order.
+__global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync, uint64_t *acc,
+                                                      int words, int clear_status,
+                                                      const float *__restrict__ levels,
+                                                      const float *__restrict__ x, int d, int K,
+                                                      double *bound)
 {
+    __shared__ double sb[256], sl[256];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
-    if (i < words) acc[i] = 0.0f;
+    if (i < words) acc[i] = 0ull;
+    if (blockIdx.x != 0) return;
+    double pb = 0.0, pl = 0.0;
+    for (int j = threadIdx.x; j < d; j += 256) {
+        const double m = fmax(fabs((double)levels[(size_t)j * K]), fabs((double)levels[(size_t)j * K + K - 1]));
+        pb += m * fabs((double)x[j]);
+        pl += m * m;
+    }
+    sb[threadIdx.x] = pb;
+    sl[threadIdx.x] = pl;
+    __syncthreads();
+    for (int stride = 128; stride > 0; stride >>= 1) {
+        if ((int)threadIdx.x < stride) {
+            sb[threadIdx.x] += sb[threadIdx.x + stride];
+            sl[threadIdx.x] += sl[threadIdx.x + stride];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) { bound[0] = sb[0]; bound[1] = sl[0]; }
 }
 
 struct Plan {
@@ -764,11 +852,11 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool sol
     lds_levels = (size_t)CW * K * 4 <= 65536 ? 1 : 0;
     const size_t total = (lds_levels ? up16((size_t)CW * K * 4) : 0) +
                          (int_table ? up16((size_t)CW * K * 2) : 0) + 6 * up16((size_t)CW * 4) +
-                         up16((size_t)nrg * 32 * 4) + up16((size_t)batch * 4) +
+                         up16((size_t)nrg * 32 * 4) +
                          (solo ? up16((size_t)(batch + 4) * 4) : 0) +
                          (GQ > 1 ? up16((size_t)GQ * batch * 4) : 0) +
                          up16((size_t)kMaxUpt * kThreads * 4) + up16(512 * 8) +
-                         up16(2 * kWaves * 4) + up16(kWaves * 4);
+                         up16(3 * kWaves * 4) + up16(kWaves * 4);
     return total <= (size_t)lds_limit ? total : 0;
 }
 
@@ -820,9 +908,11 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)p.shmem)))
         return ZIPML_ELAUNCH;
-    const int words = 3 * a.acc_words;
-    hipLaunchKernelGGL(k_sgd_reset, dim3((words + 255) / 256), dim3(256), 0, s, a.status, a.sync,
-                       a.acc, words, 1);
+    const int words = Workspace::kAccBuffers * a.acc_words;
+    const int K = 1 << BITS;
+    double *bound = const_cast<double *>(a.bound);
+    hipLaunchKernelGGL(k_sgd_prepare, dim3((words + 255) / 256), dim3(256), 0, s, a.status, a.sync,
+                       a.acc, words, 1, a.levels, a.x, a.d, K, bound);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (!stepwise) {
         a.persistent = 1;
@@ -840,10 +930,11 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     a.nsteps = 1;
     for (int64_t t = first; t < first + count; ++t) {
         a.step0 = t;
-        // the accumulator that step t uses was last used by step t-3: clear it
-        float *accf = a.acc + (size_t)(t % 3) * a.acc_words;
-        hipLaunchKernelGGL(k_sgd_reset, dim3((a.acc_words + 255) / 256), dim3(256), 0, s, a.status,
-                           a.sync, accf, a.acc_words, 0);
+        // the exchange buffer that step t uses was last used by step t-4: clear it; the magnitude
+        // bounds are taken from the model as it stands before this step
+        uint64_t *acct = a.acc + (size_t)(t & 3) * a.acc_words;
+        hipLaunchKernelGGL(k_sgd_prepare, dim3((a.acc_words + 255) / 256), dim3(256), 0, s, a.status,
+                           a.sync, acct, a.acc_words, 0, a.levels, a.x, a.d, K, bound);
         for (int seg = 0; seg <= 3; ++seg) {
             if (seg == 0 && a.model_bits == 0) continue;
             if (seg == 3 && a.grad_bits == 0) continue;
@@ -932,7 +1023,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.status = (int *)(ws + Workspace::kStatus);
     a.sync = (uint32_t *)(ws + Workspace::kSync);
     a.nrm = (double *)(ws + Workspace::kNorm);
-    a.acc = (float *)(ws + Workspace::kAcc);
+    a.acc = (uint64_t *)(ws + Workspace::kAcc);
+    a.bound = (const double *)(ws + Workspace::kBound);
     a.acc_words = (int)Workspace::acc_words(batch);
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
