@@ -112,28 +112,43 @@ __device__ __forceinline__ T wave_sum(T v)
     return v;
 }
 
-// fp32 / int32 sum over the 64 lanes with DPP row operations (no LDS traffic); every lane gets the
-// result.  Steps: xor 1, xor 2 inside each quad, mirror inside each half row, mirror inside each
-// row of 16, then the four row sums are combined through scalar registers.
-template <typename T>
-__device__ __forceinline__ T wave_sum_dpp(T v)
+// Reductions over lanes with DPP row operations (no LDS traffic); 32-bit types, commutative op.
+// Steps: xor 1, xor 2 inside each quad, mirror inside each half row, mirror inside each row of 16.
+template <int CTRL, typename T>
+__device__ __forceinline__ T dpp_move(T x)
 {
     static_assert(sizeof(T) == 4, "32-bit types only");
-    auto dpp = [](T x, auto ctrl) {
-        int xi = __builtin_bit_cast(int, x);
-        xi = __builtin_amdgcn_update_dpp(0, xi, decltype(ctrl)::value, 0xF, 0xF, true);
-        return __builtin_bit_cast(T, xi);
-    };
-    v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
-    v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
-    v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
-    v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
+    int xi = __builtin_bit_cast(int, x);
+    xi = __builtin_amdgcn_update_dpp(0, xi, CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(T, xi);
+}
+// Every lane gets the result over its row of 16 lanes.
+template <typename T, typename Op>
+__device__ __forceinline__ T row_reduce_dpp(T v, Op op)
+{
+    v = op(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = op(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = op(v, dpp_move<0x141>(v));   // row_half_mirror
+    v = op(v, dpp_move<0x140>(v));   // row_mirror
+    return v;
+}
+// Every lane gets the result over the 64 lanes: the four row results are combined through scalar
+// registers.
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_reduce_dpp(T v, Op op)
+{
+    v = row_reduce_dpp(v, op);
     const int vi = __builtin_bit_cast(int, v);
     const T r0 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 0));
     const T r1 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 16));
     const T r2 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 32));
     const T r3 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(vi, 48));
-    return (r0 + r1) + (r2 + r3);
+    return op(op(r0, r1), op(r2, r3));
+}
+template <typename T>
+__device__ __forceinline__ T wave_sum_dpp(T v)
+{
+    return wave_reduce_dpp(v, [](T x, T y) { return x + y; });
 }
 
 // Sum over the block; every thread gets the result.  scratch: >= blockDim/64 + 1 elements of T.

@@ -96,7 +96,9 @@ struct SgdArgs {
     double *nrm;           // [2 kinds][2 slots][512] (+ 1024 spare)
     uint64_t *acc;         // [4][acc_words] exchange words
     int acc_words;
-    const double *bound;   // [0] sum_j maxabs(L_j)|x_j| at launch, [1] sum_j maxabs(L_j)^2
+    const double *bound;   // at launch: [0] sum_j maxabs(L_j)|x_j|, [1] sum_j maxabs(L_j)^2,
+                           // [2] max_j delta_j|x_j|, [3] max_j delta_j maxabs(L_j)
+    int mfma;              // evenly spaced levels may take the matrix-core step loop
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     // debug outputs (may be null)
     int32_t *dbg_m, *dbg_acc, *dbg_gq;
@@ -117,6 +119,7 @@ struct Lds {
     float *wsum;      // per wave: [0..kWaves) parts of sum_i r_i, [kWaves..2kWaves) parts of
                       // sum_j lo_j x_j, [2kWaves..3kWaves) parts of sum_i |r_i|
     int *isum;        // [kWaves]
+    unsigned char *mf; // arrays of the matrix-core step loop
 };
 
 // Optional per-phase timing of workgroup 0 (development builds only: -DZIPML_PHASE_TIMING).
@@ -173,6 +176,10 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ p, uint32
 #pragma unroll
     for (int k = 0; k < BITS; ++k) u[k] = q[k];
 }
+
+}  // namespace zipml
+#include "zipml_sgd_mfma.h"
+namespace zipml {
 
 // ---- inner loops over the 32 codes of a unit (v: 32 wave-uniform fp32/int32 values in LDS) ----
 template <int BITS>
@@ -478,14 +485,15 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
             // The last wave of workgroup 0 clears the exchange words of step t+2 (four buffers in
             // rotation).  Workgroup 0 is past the exchange of step t-1, so every workgroup has
             // contributed to step t-1 and has therefore finished reading step t-2, the last user of
-            // that buffer.  The wave waits for the stores to be performed before it goes on; its
-            // contributions to step t+1 come after that, and nobody adds to step t+2 before having
-            // seen all contributions to step t+1.  The wait falls into time this wave would spend
-            // waiting for the residuals anyway.
+            // that buffer.  The stores have been performed before this wave leaves the step: a
+            // wave's memory operations are reported complete in order, so the poll below (or the
+            // explicit wait, if the wave has no samples to poll for) cannot finish before they
+            // have.  The workgroup's contributions to step t+1 come after that, and nobody adds to
+            // step t+2 before having seen all contributions to step t+1.
             if (grid_sync && w == 0 && wave == kWaves - 1) {
                 uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
                 for (int i = lane; i < B + 1; i += kWave) store_dev(nxt + i, (uint64_t)0);
-                vm_wait_all();
+                if (!(tid < B)) vm_wait_all();
             }
             ZIPML_TICK(1);
         }
@@ -743,6 +751,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     L.red = (double *)carve(512 * 8);
     L.wsum = (float *)carve(3 * kWaves * 4);
     L.isum = (int *)carve(kWaves * 4);
+    L.mf = (unsigned char *)carve(a.mfma ? mfma_lds_bytes(a.GQ, B) : 0);
 
     // ---- one-time set-up: level slice, model slice
     const float *Lg = a.levels + (size_t)j0 * K;
@@ -782,9 +791,21 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         if (lane == 0) L.wsum[kWaves + wave] = part;
     }
 
-    if (INT) sgd_steps<BITS, kInt, FAST, UPT>(a, L);
-    else if (affine) sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
-    else sgd_steps<BITS, kTable, FAST, UPT>(a, L);
+    constexpr bool kMfmaBits = BITS == 2 || BITS == 4 || BITS == 8;
+    if constexpr (!INT && FAST && kMfmaBits) {
+        if (affine && a.mfma) {
+            if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1>(a, L, L.mf);
+            else sgd_steps_mfma<BITS, UPT, 2>(a, L, L.mf);
+        } else if (affine) {
+            sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
+        } else {
+            sgd_steps<BITS, kTable, FAST, UPT>(a, L);
+        }
+    } else {
+        if (INT) sgd_steps<BITS, kInt, FAST, UPT>(a, L);
+        else if (affine) sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
+        else sgd_steps<BITS, kTable, FAST, UPT>(a, L);
+    }
 
     // ---- write the model slice back
     if (FAST || a.seg_last >= 3)
@@ -795,39 +816,54 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
 // Launch preparation: clears the barrier counter, the status word and exchange words; block 0
 // also takes the two magnitude bounds of the dot exchange from the levels and the current model,
 //   bound[0] = sum_j maxabs(L_j) |x_j|,   bound[1] = sum_j maxabs(L_j)^2,
-// in fp64 with a fixed summation order.
+//   bound[2] = max_j delta_j |x_j|,       bound[3] = max_j delta_j maxabs(L_j),
+// (delta_j: spacing of evenly spaced levels) in fp64 with a fixed order.
 __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync, uint64_t *acc,
                                                       int words, int clear_status,
                                                       const float *__restrict__ levels,
                                                       const float *__restrict__ x, int d, int K,
                                                       double *bound)
 {
-    __shared__ double sb[256], sl[256];
+    __shared__ double sb[256], sl[256], sy[256], sm[256];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
     if (i < words) acc[i] = 0ull;
     if (blockIdx.x != 0) return;
-    double pb = 0.0, pl = 0.0;
+    double pb = 0.0, pl = 0.0, py = 0.0, pm = 0.0;
     for (int j = threadIdx.x; j < d; j += 256) {
-        const double m = fmax(fabs((double)levels[(size_t)j * K]), fabs((double)levels[(size_t)j * K + K - 1]));
+        const double lo = (double)levels[(size_t)j * K], hi = (double)levels[(size_t)j * K + K - 1];
+        const double m = fmax(fabs(lo), fabs(hi));
+        const double delta = (double)(float)((hi - lo) / (double)(K - 1));
         pb += m * fabs((double)x[j]);
         pl += m * m;
+        py = fmax(py, delta * fabs((double)x[j]));
+        pm = fmax(pm, delta * m);
     }
     sb[threadIdx.x] = pb;
     sl[threadIdx.x] = pl;
+    sy[threadIdx.x] = py;
+    sm[threadIdx.x] = pm;
     __syncthreads();
     for (int stride = 128; stride > 0; stride >>= 1) {
         if ((int)threadIdx.x < stride) {
             sb[threadIdx.x] += sb[threadIdx.x + stride];
             sl[threadIdx.x] += sl[threadIdx.x + stride];
+            sy[threadIdx.x] = fmax(sy[threadIdx.x], sy[threadIdx.x + stride]);
+            sm[threadIdx.x] = fmax(sm[threadIdx.x], sm[threadIdx.x + stride]);
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) { bound[0] = sb[0]; bound[1] = sl[0]; }
+    if (threadIdx.x == 0) {
+        bound[0] = sb[0];
+        bound[1] = sl[0];
+        bound[2] = sy[0] * 1.000001;
+        bound[3] = sm[0];
+    }
 }
 
 struct Plan {
     int GQ, W, lds_levels, upt;
+    int mfma;          // the plan leaves room for the matrix-core step loop
     size_t shmem;
 };
 
@@ -844,8 +880,8 @@ static int device_limits(int &cus, int &lds)
 static size_t up16(size_t v) { return (v + 15) & ~(size_t)15; }
 
 // LDS needed for GQ feature groups per workgroup; 0 if it does not fit.
-static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool solo, int lds_limit,
-                       int &lds_levels)
+static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool solo, bool mfma,
+                       int lds_limit, int &lds_levels)
 {
     const int K = 1 << bits, CW = 32 * GQ;
     const int nrg = batch >= 32 ? (int)(batch / 32) : 1;
@@ -856,7 +892,8 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool sol
                          (solo ? up16((size_t)(batch + 4) * 4) : 0) +
                          (GQ > 1 ? up16((size_t)GQ * batch * 4) : 0) +
                          up16((size_t)kMaxUpt * kThreads * 4) + up16(512 * 8) +
-                         up16(3 * kWaves * 4) + up16(kWaves * 4);
+                         up16(3 * kWaves * 4) + up16(kWaves * 4) +
+                         (mfma ? up16(mfma_lds_bytes(GQ, batch)) : 0);
     return total <= (size_t)lds_limit ? total : 0;
 }
 
@@ -864,7 +901,7 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool sol
 // latency grows with the number of workgroups, so small steps want few, fat workgroups; the
 // registers that hold a thread's units (at most kMaxUpt per pass) and the number of compute units
 // bound the choice from both sides.
-static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, Plan &p)
+static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool fp32_model, Plan &p)
 {
     int cus = 0, lds = 0;
     if (int rc = device_limits(cus, lds)) return rc;
@@ -879,10 +916,15 @@ static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, Plan 
         if (W > cus || W > 512) continue;
         if (batch * GQ > (int64_t)kMaxUpt * kThreads) break;   // units per thread
         int ll = 0;
-        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, lds, ll);
+        // the matrix-core step loop: 2/4/8-bit codes, fp32 model, whole 64-sample blocks, more
+        // than one workgroup, at most 8 feature tiles of 16 (whether the levels are evenly
+        // spaced is found out by the kernel)
+        const bool mfma = fp32_model && (bits == 2 || bits == 4 || bits == 8) && batch % 64 == 0 &&
+                          W > 1 && GQ <= 4 && !getenv("ZIPML_NO_MFMA");
+        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, mfma, lds, ll);
         if (!sh) break;
         best = GQ;
-        p.GQ = GQ; p.W = (int)W; p.lds_levels = ll; p.shmem = sh;
+        p.GQ = GQ; p.W = (int)W; p.lds_levels = ll; p.shmem = sh; p.mfma = mfma ? 1 : 0;
         const int64_t units = batch * GQ;
         p.upt = units <= kThreads ? 1 : units <= 2 * kThreads ? 2 : 4;
         // stop at the preferred workgroup count -- unless a single workgroup is within reach:
@@ -992,7 +1034,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     const Layout lay = make_layout(n, d, bits);
     const bool ident = model_bits > 0 && grid_max == (1 << bits) - 1;
     Plan p{};
-    if (int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, p)) return rc;
+    if (int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, model_bits == 0, p))
+        return rc;
 
     unsigned char *ws = (unsigned char *)workspace_dev;
     SgdArgs a{};
@@ -1020,6 +1063,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.GQ = p.GQ;
     a.W = p.W;
     a.lds_levels = p.lds_levels;
+    a.mfma = p.mfma;
     a.status = (int *)(ws + Workspace::kStatus);
     a.sync = (uint32_t *)(ws + Workspace::kSync);
     a.nrm = (double *)(ws + Workspace::kNorm);

@@ -1,0 +1,519 @@
+// Step loop of the epoch kernel on the matrix cores: evenly spaced levels, fp32 model, 2-, 4- or
+// 8-bit codes (included by zipml_sgd.hip; uses its SgdArgs / Lds / exchange-word helpers).
+//
+// With evenly spaced levels a value is lo_j + code * delta_j = mid_j + (code - off) * delta_j
+// (off = 128 for 8-bit codes, which re-centres them into a signed byte, else 0), so both passes of
+// eq. (5), Sec. 2.2, are integer-weighted sums:
+//     z_i = sum_j mid_j x_j + sum_j (code2_ij - off) y_j,        y_j = delta_j x_j,
+//     g_j = (mid_j sum_i r_i + delta_j sum_i (code1_ij - off) r_i) / B.
+// The vectors y and r are turned into 32-bit fixed point (one common power-of-two scale per step)
+// and split into four signed base-256 digits; the packed codes, expanded to one byte each, are the
+// other operand of v_mfma_i32_16x16x64_i8:
+//     dot pass       C[digit][sample]  += Ydigits[digit][64 features] * codes2[64 features][sample]
+//     gradient pass  C[digit][feature] += Rdigits[digit][64 samples]  * codes1[64 samples][feature]
+// Only 4 of the 16 rows of the digit operand are used; the instruction still does in one issue
+// what takes 128 convert + multiply-add instructions per lane on the vector ALU.  All sums are
+// exact integers: the result does not depend on the order of anything, and the only roundings are
+// the conversions of y_j, r_i to fixed point (relative 2^-29 of the largest element) and of the
+// sums back to fp32.
+//
+// Operand layout of the instruction (checked against a host reference on the device):
+//   A: lane l holds row l%16, k = 16*(l/16) .. +15 (16 bytes);  B: lane l holds column l%16, same k;
+//   C: lane l holds column l%16, rows 4*(l/16) .. +3.
+// A lane's 16 code bytes come from 16*BITS/8 packed bytes; code_slot() says which byte a code of
+// the packed unit lands in, and the digit operands are laid out in LDS with the same map.
+//
+// The vector ALU is left with bookkeeping, and at small batches that is what a step costs besides
+// the exchange, so only as many waves work in the loop as have samples or features to look after
+// (4 of the 8 when the batch has at most 256 samples; the others only keep the workgroup barriers
+// company), and everything uniform is done in fp32.
+#pragma once
+
+namespace zipml {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Code f (0..31) of a packed unit -> (half: which lane operand of 16 codes, byte inside it).
+template <int BITS>
+__device__ __forceinline__ void code_slot(int f, int &half, int &byte)
+{
+    if (BITS == 8) {            // 4 dwords per half, code = 16*half + byte
+        half = f >> 4;
+        byte = f & 15;
+    } else if (BITS == 4) {     // packed dword pd holds codes 8pd..8pd+7; low nibbles -> one operand
+        const int pd = f >> 3, e = f & 7;    // dword, high nibbles -> the next
+        half = pd >> 1;
+        byte = (2 * (pd & 1) + (e & 1)) * 4 + (e >> 1);
+    } else {                    // BITS == 2: one packed dword per half; operand dword D = (p >> 2D) & 0x03..
+        const int e = f & 15;
+        half = f >> 4;
+        byte = (e & 3) * 4 + (e >> 2);
+    }
+}
+
+// 16 packed codes (BITS/2 dwords) -> 16 signed bytes (code - off).
+template <int BITS>
+__device__ __forceinline__ v4i expand_codes(const uint32_t (&p)[BITS / 2])
+{
+    v4i r;
+    if constexpr (BITS == 8) {
+        r[0] = (int)(p[0] ^ 0x80808080u);
+        r[1] = (int)(p[1] ^ 0x80808080u);
+        r[2] = (int)(p[2] ^ 0x80808080u);
+        r[3] = (int)(p[3] ^ 0x80808080u);
+    } else if constexpr (BITS == 4) {
+        r[0] = (int)(p[0] & 0x0F0F0F0Fu);
+        r[1] = (int)((p[0] >> 4) & 0x0F0F0F0Fu);
+        r[2] = (int)(p[1] & 0x0F0F0F0Fu);
+        r[3] = (int)((p[1] >> 4) & 0x0F0F0F0Fu);
+    } else {
+        r[0] = (int)(p[0] & 0x03030303u);
+        r[1] = (int)((p[0] >> 2) & 0x03030303u);
+        r[2] = (int)((p[0] >> 4) & 0x03030303u);
+        r[3] = (int)((p[0] >> 6) & 0x03030303u);
+    }
+    return r;
+}
+
+// v = d0 + 256 d1 + 65536 d2 + 2^24 d3 with signed bytes d_k (|v| < 2^30): adding 128 to each of
+// the three low bytes (carries included) leaves d_k + 128 in byte k, and x + 128 -> x is a flip of
+// the top bit.  Returns the four digits as the bytes of one dword.
+__device__ __forceinline__ uint32_t signed_digits(int v)
+{
+    return ((uint32_t)v + 0x00808080u) ^ 0x00808080u;
+}
+// Digit k of an element goes to plane k: 64 bytes apart.
+__device__ __forceinline__ void store_digits(int8_t *plane0, uint32_t dg)
+{
+    plane0[0] = (int8_t)(dg & 0xFF);
+    plane0[64] = (int8_t)((dg >> 8) & 0xFF);
+    plane0[128] = (int8_t)((dg >> 16) & 0xFF);
+    plane0[192] = (int8_t)(dg >> 24);
+}
+
+__device__ __forceinline__ long long combine_digits(const v4i &c)
+{
+    return (long long)c[0] + ((long long)c[1] << 8) + ((long long)c[2] << 16) + ((long long)c[3] << 24);
+}
+
+// int64 (|v| < 2^53) times 2^-k as fp32, rounded once.
+__device__ __forceinline__ float fixed_to_float(long long v, int k)
+{
+    const double d = (double)(int)(v >> 32) * 4294967296.0 + (double)(uint32_t)v;
+    return (float)ldexp(d, -k);
+}
+
+// Largest k (clamped to +-60) with 2^k * v < 2^bits, for finite v >= 0.
+__device__ __forceinline__ int scale_exponent(float v, int bits)
+{
+    if (!(v > 0.0f)) return 60;
+    int e = 0;
+    (void)frexpf(v, &e);     // v = m 2^e, 0.5 <= m < 1
+    const int k = bits - e;
+    return k < -60 ? -60 : k > 60 ? 60 : k;
+}
+
+// LDS bytes of the matrix-core path for a plan.
+__host__ __device__ inline size_t mfma_lds_bytes(int GQ, int64_t batch)
+{
+    const size_t KB = (size_t)(GQ + 1) / 2;
+    return KB * 256 + (size_t)(batch / 64) * 256 + (size_t)4 * 32 * GQ * 8 + 512;
+}
+
+constexpr int kRefresh = 16;   // steps between exact refreshes of the magnitude bounds
+
+// KB: 64-feature blocks per workgroup (1: GQ <= 2, 2: GQ == 4).
+template <int BITS, int UPT, int KB>
+__device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, unsigned char *mf)
+{
+    constexpr int HW = BITS / 2;                       // packed dwords per lane operand
+    constexpr int kSlots = KB == 1 ? UPT : (UPT + 3) / 4;   // groups of four 16-sample tiles per wave
+    constexpr int kTiles = 4 * kSlots;                 // 16-sample tiles per wave, at most
+    constexpr int kNG = 4 * UPT;                       // gradient instructions per wave, at most
+    constexpr int kBpt = UPT;                          // samples per thread in the residual phase
+    constexpr float kOff = BITS == 8 ? 128.0f : 0.0f;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int n16 = lane & 15, q4 = lane >> 4;
+    const int w = blockIdx.x, W = a.W, GQ = a.GQ, CW = 32 * GQ, B = a.B;
+    const int j0 = w * CW;
+    const int ngroups = (a.d32 - w * GQ) < GQ ? (a.d32 - w * GQ) : GQ;
+    const int ntile = B / 16, NKS = B / 64;
+    const int FT = 2 * GQ;                              // 16-feature tiles (2, 4 or 8)
+    const int nw = (UPT == 1 && B <= 256 && FT <= 4) ? 4 : kWaves;   // waves that work in the loop
+    const int nthr = nw * kWave;
+    const int KSS = nw / FT;                            // waves that share a feature tile
+    const int g_ft = wave % FT, g_kh = wave / FT;
+    const bool owner = g_kh == 0 && lane < 16;          // this lane updates feature 16*g_ft + lane
+    const int oc = 16 * g_ft + n16;                     // that feature, inside the workgroup
+    float *const xs = L.xs;
+    const int64_t t_end = a.step0 + a.nsteps;
+
+    // ---- LDS of this path
+    int8_t *const ydig = (int8_t *)mf;                              // [KB][4 digits][4 q][16]
+    int8_t *const rdig = ydig + KB * 256;                           // [NKS][4 digits][4 q][16]
+    long long *const gpart = (long long *)(rdig + (size_t)NKS * 256);   // [4][CW]
+    unsigned char *misc = (unsigned char *)(gpart + 4 * CW);
+    float *const cqs = (float *)misc;                               // [8] per tile: sum_j mid_j x_j
+    float *const bws = (float *)(misc + 32);                        // [8] sum_j maxabs(L_j)|x_j|
+    int *const ymx = (int *)(misc + 64);                            // [8] max_j |Y_j|
+    float *const wmax = (float *)(misc + 96);                       // [8] per wave max_i |r_i|
+    float *const wsum = (float *)(misc + 128);                      // [8] per wave sum_i r_i
+    float *const side = (float *)(misc + 160);                      // [2] decoded side words
+
+    for (int e = tid; e < KB * 256 + NKS * 256; e += kThreads) ydig[e] = 0;
+    if (tid < 8) { cqs[tid] = 0.0f; bws[tid] = 0.0f; ymx[tid] = 0; wmax[tid] = 0.0f; wsum[tid] = 0.0f; }
+    lds_barrier();
+
+    if (wave >= nw) {
+        // nothing to look after: meet the others at their barriers, step by step
+        for (int64_t t = a.step0; t < t_end; ++t) {
+            lds_barrier();
+            if (w == 0 && wave == kWaves - 1) {
+                // clear the exchange words of step t+2 (see zipml_sgd.hip for why now)
+                uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
+                for (int i = lane; i < B + 2; i += kWave) store_dev(nxt + i, (uint64_t)0);
+                vm_wait_all();
+            }
+            lds_barrier();
+            lds_barrier();
+            if (KSS > 1) lds_barrier();
+        }
+        lds_barrier();
+        return;
+    }
+
+    // ---- bounds that fix the fixed-point scale of a step; every workgroup computes the same
+    // numbers in the same order.  beta_hat >= sum_j maxabs(L_j)|x_j| bounds every partial and full
+    // dot product; ymax_hat >= max_j |y_j| keeps the digits of y inside 32 bits.  Both are exact
+    // at launch, grow every step by a bound on the model's change (|dx_j| <= lr maxabs(L_j) max_i
+    // |r_i|), and are refreshed from exact per-workgroup values every kRefresh steps.
+    float beta_hat = (float)a.bound[0] * 1.00001f;
+    const float lambda = (float)a.bound[1] * 1.00001f;   // sum_j maxabs(L_j)^2
+    float ymax_hat = (float)a.bound[2] * 1.00001f;
+    const float mu = (float)a.bound[3] * 1.00001f;       // max_j delta_j maxabs(L_j)
+    const float lr_abs = fabsf(a.lr) * 1.00001f;
+    auto scale_of = [&]() {
+        const int k1 = scale_exponent(beta_hat, 42), k2 = scale_exponent(ymax_hat, 29);
+        return k1 < k2 ? k1 : k2;
+    };
+    int ky = scale_of();
+
+    // ---- owner lanes: per-feature constants, and where the digits of y_j go
+    const float o_lo = owner ? L.los[oc] : 0.0f, o_dl = owner ? L.dls[oc] : 0.0f;
+    const float o_mid = o_lo + kOff * o_dl;
+    const float o_maxl = fmaxf(fabsf(o_lo), fabsf(o_lo + o_dl * (float)((1 << BITS) - 1))) * 1.00001f;
+    const bool o_live = owner && (j0 + oc < a.d);
+    int y_pos = 0;
+    {
+        int half, byte;
+        code_slot<BITS>(oc & 31, half, byte);
+        const int gq = oc >> 5;
+        y_pos = ((gq >> 1) * 4) * 64 + (2 * (gq & 1) + half) * 16 + byte;   // digit plane 0
+    }
+    // y_j -> digits in LDS, and the per-tile sums the next exchange needs (all 64 lanes of an
+    // owner wave take part in the row reductions; only lanes 0..15 hold real values)
+    auto refresh_y = [&](float x, int kscale, bool with_bounds) {
+        const float y = o_dl * x;
+        const int Y = owner ? __float2int_rn(ldexpf(y, kscale)) : 0;
+        if (owner) store_digits(ydig + y_pos, signed_digits(Y));
+        const float cq = row_reduce_dpp(owner ? o_mid * x : 0.0f, [](float p, float q) { return p + q; });
+        if (lane == 0) cqs[g_ft] = cq;
+        if (with_bounds) {
+            const float bw = row_reduce_dpp(owner ? o_maxl * fabsf(x) : 0.0f, [](float p, float q) { return p + q; });
+            const int amx = row_reduce_dpp(Y < 0 ? -Y : Y, [](int p, int q) { return p > q ? p : q; });
+            if (lane == 0) { bws[g_ft] = bw; ymx[g_ft] = amx; }
+        }
+    };
+    if (g_kh == 0) refresh_y(owner ? xs[oc] : 0.0f, ky, true);
+
+    // ---- packed data held in registers; the addresses advance by a fixed stride per step
+    const int64_t step_dwords = (int64_t)B * BITS;      // both copies: B samples x BITS dwords per group
+    uint32_t c2cur[kTiles][KB][HW], c2nxt[kTiles][KB][HW], c1[kNG][HW], c1nxt[kNG][HW];
+    const uint32_t *p2ptr[kTiles][KB], *p1ptr[kNG];
+    bool p2ok[kTiles][KB], p1ok[kNG];
+    float bnext[kBpt], bfut[kBpt];
+#pragma unroll
+    for (int ti = 0; ti < kTiles; ++ti) {
+        const int tile = wave + nw * ti;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int gq = 2 * kb + (q4 >> 1);
+            p2ok[ti][kb] = tile < ntile && gq < ngroups;
+            const int64_t row = a.step0 * B + 16 * tile + n16;
+            const int64_t g = (int64_t)w * GQ + gq;
+            p2ptr[ti][kb] = p2ok[ti][kb] ? a.p2 + (g * a.nb64 * 64 + row) * BITS + (q4 & 1) * HW : a.p2;
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < kNG; ++m) {
+        const int ks = g_kh + KSS * m;
+        const int gq = g_ft >> 1, cin = 16 * (g_ft & 1) + n16;
+        p1ok[m] = ks < NKS && gq < ngroups;
+        const int64_t g = (int64_t)w * GQ + gq;
+        const int64_t rg = (a.step0 * B) / 32 + 2 * ks + (q4 >> 1);
+        p1ptr[m] = p1ok[m] ? a.p1 + ((g * a.n32 + rg) * 32 + cin) * BITS + (q4 & 1) * HW : a.p1;
+    }
+    // loads of the step `ahead` steps after the one the pointers stand at
+    auto load_dot = [&](int ahead, uint32_t (&dst)[kTiles][KB][HW]) {
+#pragma unroll
+        for (int ti = 0; ti < kTiles; ++ti)
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const uint32_t *q = static_cast<const uint32_t *>(
+                    __builtin_assume_aligned(p2ptr[ti][kb] + ahead * step_dwords, 4 * HW));
+                if (p2ok[ti][kb]) {
+#pragma unroll
+                    for (int k = 0; k < HW; ++k) dst[ti][kb][k] = q[k];
+                }
+            }
+    };
+    auto load_grad = [&](int ahead, uint32_t (&dst)[kNG][HW]) {
+#pragma unroll
+        for (int m = 0; m < kNG; ++m) {
+            const uint32_t *q = static_cast<const uint32_t *>(
+                __builtin_assume_aligned(p1ptr[m] + ahead * step_dwords, 4 * HW));
+            if (p1ok[m]) {
+#pragma unroll
+                for (int k = 0; k < HW; ++k) dst[m][k] = q[k];
+            }
+        }
+    };
+    auto load_labels = [&](int64_t t, float (&dst)[kBpt]) {
+#pragma unroll
+        for (int k = 0; k < kBpt; ++k) {
+            const int i = tid + k * nthr;
+            if (i < B) dst[k] = a.b[t * B + i];
+        }
+    };
+    // operands that are never loaded multiply digit rows that are zero; give them a value anyway
+#pragma unroll
+    for (int ti = 0; ti < kTiles; ++ti)
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int k = 0; k < HW; ++k) c2cur[ti][kb][k] = c2nxt[ti][kb][k] = 0u;
+#pragma unroll
+    for (int m = 0; m < kNG; ++m)
+#pragma unroll
+        for (int k = 0; k < HW; ++k) c1[m][k] = c1nxt[m][k] = 0u;
+#pragma unroll
+    for (int k = 0; k < kBpt; ++k) bnext[k] = bfut[k] = 0.0f;
+    load_dot(0, c2cur);
+    if (a.step0 + 1 < t_end) load_dot(1, c2nxt);
+    load_grad(0, c1);
+    load_labels(a.step0, bnext);
+
+    // where the digits of this thread's residuals go: sample i -> k-step i/64, q, byte
+    int r_pos[kBpt];
+#pragma unroll
+    for (int k = 0; k < kBpt; ++k) {
+        const int i = tid + k * nthr;
+        int half, byte;
+        code_slot<BITS>(i & 31, half, byte);
+        r_pos[k] = ((i >> 6) * 4) * 64 + (2 * ((i >> 5) & 1) + half) * 16 + byte;
+    }
+
+    bool dead = false;
+#ifdef ZIPML_PHASE_TIMING
+    long long prof_[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    long long last_ = wall_clock64();
+#endif
+
+    for (int64_t t = a.step0; t < t_end; ++t) {
+        uint64_t *const acc = a.acc + (size_t)(t & 3) * a.acc_words;
+        const bool side_step = (t % kRefresh) == 0;            // bounds travel with this step's exchange
+        const bool side_next = ((t + 1) % kRefresh) == 0;
+        ZIPML_TICK(7);
+        lds_barrier();          // digits of y and the per-tile sums of the current model
+        ZIPML_TICK(0);
+
+        // ============ dot pass: one instruction per (16 samples, 64 features)
+        {
+            // what every sample of this workgroup gets on top of sum_j (code - off) * Y_j
+            const float4 c0 = *reinterpret_cast<const float4 *>(cqs);
+            const float4 c1v = *reinterpret_cast<const float4 *>(cqs + 4);
+            const float cq = ((c0.x + c0.y) + (c0.z + c0.w)) + ((c1v.x + c1v.y) + (c1v.z + c1v.w));
+            const long long kconst = __double2ll_rn(ldexp((double)cq, ky));
+            // Four sample tiles share one accumulator: the digits of tile slot s sit in rows
+            // 4s..4s+3 of its digit operand (zeros elsewhere), so its sums land in lanes
+            // 16s..16s+15 and one combine / one atomic instruction serves all 64 lanes.
+            const v4i zero = {0, 0, 0, 0};
+            v4i afull[KB];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+                afull[kb] = *reinterpret_cast<const v4i *>(ydig + (kb * 4 + (n16 & 3)) * 64 + q4 * 16);
+#pragma unroll
+            for (int gi = 0; gi < kSlots; ++gi) {
+                if (wave + nw * 4 * gi < ntile) {
+                    v4i c = {0, 0, 0, 0};
+#pragma unroll
+                    for (int sl = 0; sl < 4; ++sl) {
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) {
+                            const v4i as = (n16 >> 2) == sl ? afull[kb] : zero;
+                            c = __builtin_amdgcn_mfma_i32_16x16x64_i8(as, expand_codes<BITS>(c2cur[4 * gi + sl][kb]), c, 0, 0, 0);
+                        }
+                    }
+                    const int tile = wave + nw * (4 * gi + q4);
+                    if (tile < ntile) add_dev(acc + 16 * tile + n16, pack_int(combine_digits(c) + kconst));
+                }
+            }
+            if (side_step && wave == 0 && lane < 2) {
+                // side words: this workgroup's share of the two bounds, rounded up
+                float bw = 0.0f;
+                int mx = 0;
+                for (int f = 0; f < FT; ++f) {
+                    bw += bws[f];
+                    mx = ymx[f] > mx ? ymx[f] : mx;
+                }
+                const long long v = lane == 0 ? __double2ll_ru(ldexp((double)bw, ky)) + 1 : (long long)mx;
+                add_dev(acc + B + lane, pack_int(v));
+            }
+        }
+        // The last wave of workgroup 0 clears the exchange words of step t+2 (see zipml_sgd.hip
+        // for why that is the right moment and why no wait is needed here); with idle waves
+        // around, one of them does it instead.
+        if (nw == kWaves && w == 0 && wave == kWaves - 1) {
+            uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
+            for (int i = lane; i < B + 2; i += kWave) store_dev(nxt + i, (uint64_t)0);
+            if (!(tid < B)) vm_wait_all();
+        }
+        // Rotate copy 2 and request what later steps need, now: the loads travel while the
+        // exchange is under way.  (A wave's memory operations complete in order and the compute
+        // unit's memory pipeline keeps that order too, so the poll below cannot return before
+        // these loads have; issued anywhere else their latency would add to the exchange's
+        // instead of hiding behind it.)
+#pragma unroll
+        for (int ti = 0; ti < kTiles; ++ti)
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+                for (int k = 0; k < HW; ++k) c2cur[ti][kb][k] = c2nxt[ti][kb][k];
+                p2ptr[ti][kb] += step_dwords;          // now stands at step t+1
+            }
+        if (t + 2 < t_end) load_dot(1, c2nxt);
+        if (t + 1 < t_end) {
+            load_grad(1, c1nxt);
+            load_labels(t + 1, bfut);
+        }
+        ZIPML_TICK(1);
+
+        // ============ residuals: poll the sums of this thread's samples
+        float r[kBpt];
+        float rmax = 0.0f, rsum = 0.0f;
+        {
+            uint64_t raw[kBpt], rawx = 0;
+            const bool want_side = side_step && wave == 0;     // wave 0 also fetches the side words
+            uint32_t spins = 0;
+            if (tid < B || want_side) {
+#pragma unroll 1
+                for (;;) {
+#pragma unroll
+                    for (int q = 0; q < kBpt; ++q) {
+                        const int i = tid + q * nthr;
+                        raw[q] = load_dev(acc + (i < B ? i : B - 1));
+                    }
+                    if (want_side) rawx = load_dev(acc + B + (lane & 1));
+                    bool all = !want_side || (int)(rawx >> kCountShift) == W;
+#pragma unroll
+                    for (int q = 0; q < kBpt; ++q) all = all && (int)(raw[q] >> kCountShift) == W;
+                    if (all || dead) break;
+                    if (++spins > kSpinLimit) {
+                        store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                        dead = true;
+                    }
+                }
+            }
+            if (want_side && lane < 2) side[lane] = fixed_to_float(unpack_sum(rawx, W), ky) * 1.00001f;
+#pragma unroll
+            for (int q = 0; q < kBpt; ++q) {
+                const int i = tid + q * nthr;
+                r[q] = 0.0f;
+                if (i < B) {
+                    r[q] = fixed_to_float(unpack_sum(raw[q], W), ky) - bnext[q];
+                    rmax = fmaxf(rmax, fabsf(r[q]));
+                    rsum += r[q];
+                }
+                bnext[q] = bfut[q];
+            }
+        }
+        rmax = wave_reduce_dpp(rmax, [](float p, float q) { return fmaxf(p, q); });
+        rsum = wave_sum_dpp(rsum);
+        if (lane == 0) { wmax[wave] = rmax; wsum[wave] = rsum; }
+        lds_barrier();
+        ZIPML_TICK(4);
+
+        // scale of the residuals, and the bounds for the next step's scale
+        const float4 m0 = *reinterpret_cast<const float4 *>(wmax), m1 = *reinterpret_cast<const float4 *>(wmax + 4);
+        const float4 s0 = *reinterpret_cast<const float4 *>(wsum), s1 = *reinterpret_cast<const float4 *>(wsum + 4);
+        const float Rmax = fmaxf(fmaxf(fmaxf(m0.x, m0.y), fmaxf(m0.z, m0.w)), fmaxf(fmaxf(m1.x, m1.y), fmaxf(m1.z, m1.w)));
+        const float Rtot = ((s0.x + s0.y) + (s0.z + s0.w)) + ((s1.x + s1.y) + (s1.z + s1.w));
+        const int kr = Rmax < 3.0e38f ? scale_exponent(Rmax, 29) : 0;
+        if (side_step) {
+            beta_hat = side[0];
+            ymax_hat = side[1] + ldexpf((float)W, -ky);     // |y_j| 2^ky <= |Y_j| + 1/2
+        }
+        beta_hat += lr_abs * lambda * Rmax;
+        ymax_hat += lr_abs * mu * Rmax;
+        const int ky_next = scale_of();
+        // residual digits
+#pragma unroll
+        for (int q = 0; q < kBpt; ++q) {
+            const int i = tid + q * nthr;
+            if (i < B) store_digits(rdig + r_pos[q], signed_digits(__float2int_rn(ldexpf(r[q], kr))));
+        }
+        lds_barrier();
+        ZIPML_TICK(8);
+
+        // ============ gradient pass: one instruction per (16 features, 64 samples)
+        {
+            v4i c = {0, 0, 0, 0};
+#pragma unroll
+            for (int m = 0; m < kNG; ++m) {
+                const int ks = g_kh + KSS * m;
+                if (ks < NKS) {
+                    v4i ad = {0, 0, 0, 0};
+                    if (n16 < 4) ad = *reinterpret_cast<const v4i *>(rdig + (ks * 4 + n16) * 64 + q4 * 16);
+                    c = __builtin_amdgcn_mfma_i32_16x16x64_i8(ad, expand_codes<BITS>(c1[m]), c, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int m = 0; m < kNG; ++m) {
+                p1ptr[m] += step_dwords;
+#pragma unroll
+                for (int k = 0; k < HW; ++k) c1[m][k] = c1nxt[m][k];
+            }
+            long long G = combine_digits(c);
+            if (KSS > 1) {
+                if (g_kh > 0 && lane < 16) gpart[g_kh * CW + oc] = G;
+                lds_barrier();
+                if (owner)
+                    for (int kh = 1; kh < KSS; ++kh) G += gpart[kh * CW + oc];
+            }
+            ZIPML_TICK(9);
+            // owners: gradient, update, next step's digits
+            if (g_kh == 0) {
+                float xnew = 0.0f;
+                if (owner) {
+                    const float S = fixed_to_float(G, kr);
+                    float g = o_mid * Rtot + o_dl * S;
+                    g = o_live ? __fdiv_rn(g, (float)B) : 0.0f;
+                    const float stp = a.lr * g;
+                    xnew = xs[oc] - stp;
+                    xs[oc] = xnew;
+                }
+                refresh_y(xnew, ky_next, side_next);
+            }
+        }
+        ky = ky_next;
+        ZIPML_TICK(6);
+    }
+    lds_barrier();
+#ifdef ZIPML_PHASE_TIMING
+    if (w == 0 && tid == 0)
+        for (int k = 0; k < 12; ++k) ((long long *)(a.nrm + 2048))[k] = prof_[k];
+#endif
+}
+
+}  // namespace zipml
