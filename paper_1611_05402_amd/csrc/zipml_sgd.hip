@@ -370,7 +370,9 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
     // ---- register-resident packed data: copy 2 of this step and the next, copy 1 of this step
     // and the next, labels of the next step
     uint32_t c2cur[UPT][BITS], c2nxt[UPT][BITS], c1cur[UPT][BITS], c1nxt[UPT][BITS];
-    float bnext[kBpt];
+    float bnext[kBpt], bfut[kBpt];
+#pragma unroll
+    for (int k = 0; k < kBpt; ++k) bnext[k] = bfut[k] = 0.0f;
     load_dot_units(a.step0, c2cur);
     if (a.step0 + 1 < t_end) load_dot_units(a.step0 + 1, c2nxt);
     load_grad_units(a.step0, c1nxt);
@@ -499,6 +501,27 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
         }
         if (seg_last < 2) continue;
 
+        // Rotate the register sets and request what later steps need (copy 1 of step t+1, copy 2
+        // of step t+2, labels of step t+1) now, right behind the atomics: the loads travel while
+        // the exchange is under way.  A wave's memory operations complete in order, and the
+        // compute unit's memory pipeline keeps that order too, so the poll below cannot return
+        // before these loads have; issued anywhere else their latency would add to the
+        // exchange's instead of hiding behind it.
+#pragma unroll
+        for (int k = 0; k < UPT; ++k)
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) {
+                c1cur[k][q] = c1nxt[k][q];
+                c2cur[k][q] = c2nxt[k][q];
+            }
+        if (persistent) {
+            if (t + 1 < t_end) {
+                load_grad_units(t + 1, c1nxt);
+                load_labels(t + 1, bfut);
+            }
+            if (t + 2 < t_end) load_dot_units(t + 2, c2nxt);
+        }
+
         // ================= segment 2: residuals, gradient pass ==================================
         if (seg_first <= 2) {
             if (kIsInt && seg_first == 2) {
@@ -567,6 +590,8 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     }
                 }
             }
+#pragma unroll
+            for (int q = 0; q < kBpt; ++q) bnext[q] = bfut[q];
             if (MODE != kInt) {
                 rsum = wave_sum_dpp(rsum);
                 rabs = wave_sum_dpp(rabs);
@@ -583,24 +608,6 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 #pragma unroll
                 for (int q = 0; q < kWaves; ++q) Rabs += L.wsum[2 * kWaves + q];
                 bound_hat += fabs((double)a.lr) * lambda * ((double)Rabs / (double)B);
-            }
-
-            // Rotate the register sets and request what later steps need: copy 1 of step t+1,
-            // copy 2 of step t+2, labels of step t+1.  Nothing latency-critical touches memory
-            // from here until the atomics at the end of the next dot pass.
-#pragma unroll
-            for (int k = 0; k < UPT; ++k)
-#pragma unroll
-                for (int q = 0; q < BITS; ++q) {
-                    c1cur[k][q] = c1nxt[k][q];
-                    c2cur[k][q] = c2nxt[k][q];
-                }
-            if (persistent) {
-                if (t + 1 < t_end) {
-                    load_grad_units(t + 1, c1nxt);
-                    load_labels(t + 1, bnext);
-                }
-                if (t + 2 < t_end) load_dot_units(t + 2, c2nxt);
             }
 
             ZIPML_TICK(8);

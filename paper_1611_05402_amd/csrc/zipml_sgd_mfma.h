@@ -129,7 +129,11 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     constexpr int HW = BITS / 2;                       // packed dwords per lane operand
     constexpr int kSlots = KB == 1 ? UPT : (UPT + 3) / 4;   // groups of four 16-sample tiles per wave
     constexpr int kTiles = 4 * kSlots;                 // 16-sample tiles per wave, at most
-    constexpr int kNG = 4 * UPT;                       // gradient instructions per wave, at most
+    constexpr int kNG = UPT == 1 ? 4 : 2 * UPT;        // gradient instructions per wave, at most
+    // Small steps hold two steps of packed data in registers (the loads need more than a step to
+    // arrive); large steps are long enough for loads issued one step ahead, and need the registers.
+    constexpr bool kDouble = UPT <= 2;
+    constexpr int kT2 = kDouble ? kTiles : 1, kG2 = kDouble ? kNG : 1;
     constexpr int kBpt = UPT;                          // samples per thread in the residual phase
     constexpr float kOff = BITS == 8 ? 128.0f : 0.0f;
     const int tid = threadIdx.x;
@@ -229,7 +233,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 
     // ---- packed data held in registers; the addresses advance by a fixed stride per step
     const int64_t step_dwords = (int64_t)B * BITS;      // both copies: B samples x BITS dwords per group
-    uint32_t c2cur[kTiles][KB][HW], c2nxt[kTiles][KB][HW], c1[kNG][HW], c1nxt[kNG][HW];
+    uint32_t c2cur[kTiles][KB][HW], c2nxt[kT2][KB][HW], c1[kNG][HW], c1nxt[kG2][HW];
     const uint32_t *p2ptr[kTiles][KB], *p1ptr[kNG];
     bool p2ok[kTiles][KB], p1ok[kNG];
     float bnext[kBpt], bfut[kBpt];
@@ -255,7 +259,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         p1ptr[m] = p1ok[m] ? a.p1 + ((g * a.n32 + rg) * 32 + cin) * BITS + (q4 & 1) * HW : a.p1;
     }
     // loads of the step `ahead` steps after the one the pointers stand at
-    auto load_dot = [&](int ahead, uint32_t (&dst)[kTiles][KB][HW]) {
+    auto load_dot = [&](int ahead, auto &dst) {
 #pragma unroll
         for (int ti = 0; ti < kTiles; ++ti)
 #pragma unroll
@@ -268,7 +272,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 }
             }
     };
-    auto load_grad = [&](int ahead, uint32_t (&dst)[kNG][HW]) {
+    auto load_grad = [&](int ahead, auto &dst) {
 #pragma unroll
         for (int m = 0; m < kNG; ++m) {
             const uint32_t *q = static_cast<const uint32_t *>(
@@ -292,15 +296,23 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int k = 0; k < HW; ++k) c2cur[ti][kb][k] = c2nxt[ti][kb][k] = 0u;
+            for (int k = 0; k < HW; ++k) {
+                c2cur[ti][kb][k] = 0u;
+                if constexpr (kDouble) c2nxt[ti][kb][k] = 0u;
+            }
 #pragma unroll
     for (int m = 0; m < kNG; ++m)
 #pragma unroll
-        for (int k = 0; k < HW; ++k) c1[m][k] = c1nxt[m][k] = 0u;
+        for (int k = 0; k < HW; ++k) {
+            c1[m][k] = 0u;
+            if constexpr (kDouble) c1nxt[m][k] = 0u;
+        }
 #pragma unroll
     for (int k = 0; k < kBpt; ++k) bnext[k] = bfut[k] = 0.0f;
     load_dot(0, c2cur);
-    if (a.step0 + 1 < t_end) load_dot(1, c2nxt);
+    if constexpr (kDouble) {
+        if (a.step0 + 1 < t_end) load_dot(1, c2nxt);
+    }
     load_grad(0, c1);
     load_labels(a.step0, bnext);
 
@@ -388,15 +400,19 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         for (int ti = 0; ti < kTiles; ++ti)
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
+                if constexpr (kDouble) {
 #pragma unroll
-                for (int k = 0; k < HW; ++k) c2cur[ti][kb][k] = c2nxt[ti][kb][k];
+                    for (int k = 0; k < HW; ++k) c2cur[ti][kb][k] = c2nxt[ti][kb][k];
+                }
                 p2ptr[ti][kb] += step_dwords;          // now stands at step t+1
             }
-        if (t + 2 < t_end) load_dot(1, c2nxt);
-        if (t + 1 < t_end) {
-            load_grad(1, c1nxt);
-            load_labels(t + 1, bfut);
+        if constexpr (kDouble) {
+            if (t + 2 < t_end) load_dot(1, c2nxt);
+            if (t + 1 < t_end) load_grad(1, c1nxt);
+        } else {
+            if (t + 1 < t_end) load_dot(0, c2cur);
         }
+        if (t + 1 < t_end) load_labels(t + 1, bfut);
         ZIPML_TICK(1);
 
         // ============ residuals: poll the sums of this thread's samples
@@ -481,8 +497,13 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 #pragma unroll
             for (int m = 0; m < kNG; ++m) {
                 p1ptr[m] += step_dwords;
+                if constexpr (kDouble) {
 #pragma unroll
-                for (int k = 0; k < HW; ++k) c1[m][k] = c1nxt[m][k];
+                    for (int k = 0; k < HW; ++k) c1[m][k] = c1nxt[m][k];
+                }
+            }
+            if constexpr (!kDouble) {
+                if (t + 1 < t_end) load_grad(0, c1);
             }
             long long G = combine_digits(c);
             if (KSS > 1) {
