@@ -10,23 +10,107 @@
 
 namespace zipml {
 
-// Largest l <= K-2 with L[l] <= v (v already clamped to the level range) and the probability of
-// rounding up to L[l+1]: three correctly rounded fp32 operations.
-__device__ __forceinline__ int bracket(const float *__restrict__ L, int K, float v, float &frac)
+// Bracketing of a value by two neighbouring levels: l = largest c <= K-2 with L[c] <= v (v clamped
+// to the level range), and the probability of rounding up to L[l+1] from three correctly rounded
+// fp32 operations.
+// The index is first guessed from the ends of the table, as if the levels were evenly spaced, and
+// then checked against the table itself (L[l] <= v, and l == K-2 or L[l+1] > v: for a
+// non-decreasing table that is the definition).  Evenly spaced tables pass at once or after one
+// step to a neighbour; any other table falls back to a binary search.  The two table probes are
+// branch-free so that the loads of the four elements a thread handles together overlap.
+struct Column {
+    const float *L;      // levels of this feature
+    float L0, Lk, scale; // ends of the table, (K-1) / (Lk - L0) or 0
+};
+__device__ __forceinline__ Column make_column(const float *__restrict__ L, int K)
 {
-    const float L0 = L[0], Lk = L[K - 1];
-    if (v < L0) v = L0;
-    if (v > Lk) v = Lk;
-    int l = 0;
-    for (int s = K >> 1; s >= 1; s >>= 1) {
-        const int c = l + s;
-        if (c <= K - 2 && L[c] <= v) l = c;
+    Column c;
+    c.L = L;
+    c.L0 = L[0];
+    c.Lk = L[K - 1];
+    const float span = c.Lk - c.L0;
+    c.scale = span > 0.0f ? __fdividef((float)(K - 1), span) : 0.0f;
+    return c;
+}
+__device__ __forceinline__ bool bracket_ok(int l, int K, float base, float next, float v)
+{
+    return base <= v && (l == K - 2 || next > v);
+}
+// Two neighbouring levels with one 8-byte load (4-byte aligned).
+typedef float pair_f32 __attribute__((ext_vector_type(2), aligned(4)));
+__device__ __forceinline__ void load_pair(const float *__restrict__ p, float &lo, float &hi)
+{
+    const pair_f32 v = *reinterpret_cast<const pair_f32 *>(p);
+    lo = v.x;
+    hi = v.y;
+}
+// Four elements at once; live[e] == false: the element does not exist (l = 0, frac = 0).
+// Table probes are gathers (every lane reads another feature's table), which the compute unit
+// serves at about one lane per cycle: one 8-byte probe per element, and the second probe only for
+// waves in which some lane's guess was off.
+__device__ __forceinline__ void bracket4(const Column (&col)[4], const bool (&live)[4], int K,
+                                         const float (&vin)[4], int (&l)[4], float (&frac)[4])
+{
+    float v[4], base[4], next[4];
+    bool ok[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[e] = fminf(fmaxf(vin[e], col[e].L0), col[e].Lk);
+        int g = (int)((v[e] - col[e].L0) * col[e].scale);
+        l[e] = g < 0 ? 0 : g > K - 2 ? K - 2 : g;
     }
-    const float base = L[l];
-    const float w = L[l + 1] - base;
-    const float num = v - base;
-    frac = (w > 0.0f) ? __fdiv_rn(num, w) : 0.0f;
-    return l;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        base[e] = next[e] = 0.0f;
+        if (live[e]) load_pair(col[e].L + l[e], base[e], next[e]);
+    }
+    bool all_ok = true;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        ok[e] = !live[e] || bracket_ok(l[e], K, base[e], next[e], v[e]);
+        all_ok = all_ok && ok[e];
+    }
+    if (__any(!all_ok)) {
+        // one step towards the value, then the check again; whatever still fails is searched for
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int g = ok[e] ? l[e] : (base[e] > v[e] ? l[e] - 1 : l[e] + 1);
+            l[e] = g < 0 ? 0 : g > K - 2 ? K - 2 : g;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (live[e]) load_pair(col[e].L + l[e], base[e], next[e]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (live[e] && !bracket_ok(l[e], K, base[e], next[e], v[e])) {
+                int b = 0;
+                for (int s = K >> 1; s >= 1; s >>= 1) {
+                    const int c = b + s;
+                    if (c <= K - 2 && col[e].L[c] <= v[e]) b = c;
+                }
+                l[e] = b;
+                load_pair(col[e].L + b, base[e], next[e]);
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float w = next[e] - base[e];
+        const float num = v[e] - base[e];
+        frac[e] = (live[e] && w > 0.0f) ? __fdiv_rn(num, w) : 0.0f;
+        if (!live[e]) l[e] = 0;
+    }
+}
+
+// One packed unit (BITS contiguous dwords) to global memory, with the widest stores its alignment
+// (the largest power of two dividing 4*BITS bytes, at most 16) allows.
+template <int BITS>
+__device__ __forceinline__ void store_unit(uint32_t *__restrict__ p, const uint32_t (&u)[BITS])
+{
+    constexpr int kAlign = (BITS % 4 == 0) ? 16 : (BITS % 2 == 0) ? 8 : 4;
+    uint32_t *q = static_cast<uint32_t *>(__builtin_assume_aligned(p, kAlign));
+#pragma unroll
+    for (int k = 0; k < BITS; ++k) q[k] = u[k];
 }
 
 constexpr int kTileCols = 128;   // 4 feature groups
@@ -48,6 +132,13 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
     // ---- phase 1: decide both codes of every element of the tile
     const int cq = tid & 31;
     const int64_t col = col0 + 4 * cq;
+    Column cols[4];
+    bool live_col[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        live_col[e] = col + e < d;
+        cols[e] = make_column(levels + (live_col[e] ? col + e : 0) * K, K);
+    }
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
         const int r = pass * 8 + (tid >> 5);
@@ -67,13 +158,14 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
             const uint64_t row = (uint64_t)(row0 + i);
             const Philox4 r1 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 1u);
             const Philox4 r2 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 2u);
+            int l[4];
+            float frac[4];
+            bracket4(cols, live_col, K, v, l, frac);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (col + e < d) {
-                    float frac;
-                    const int l = bracket(levels + (col + e) * K, K, v[e], frac);
-                    const uint32_t a = (uint32_t)l + (u24(r1.w[e]) < frac ? 1u : 0u);
-                    const uint32_t b = (uint32_t)l + (u24(r2.w[e]) < frac ? 1u : 0u);
+                if (live_col[e]) {
+                    const uint32_t a = (uint32_t)l[e] + (u24(r1.w[e]) < frac[e] ? 1u : 0u);
+                    const uint32_t b = (uint32_t)l[e] + (u24(r2.w[e]) < frac[e] ? 1u : 0u);
                     w1 |= a << (8 * e);
                     w2 |= b << (8 * e);
                 }
@@ -100,9 +192,7 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
                 unit_set<BITS>(unit, k, (w >> (8 * (k & 3))) & 0xFFu);
             }
             const int64_t i = rg * 32 + r;
-            uint32_t *dst = p2 + (g * nb64 * 64 + i) * BITS;
-#pragma unroll
-            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
+            store_unit<BITS>(p2 + (g * nb64 * 64 + i) * BITS, unit);
         }
     } else {
         // copy 1: one unit = feature c, the 32 samples of this group
@@ -117,9 +207,7 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
                 const uint32_t w = c1w[k * kLdsRow + (c >> 2)];
                 unit_set<BITS>(unit, k, (w >> (8 * (c & 3))) & 0xFFu);
             }
-            uint32_t *dst = p1 + ((g * n32 + rg) * 32 + cin) * BITS;
-#pragma unroll
-            for (int q = 0; q < BITS; ++q) dst[q] = unit[q];
+            store_unit<BITS>(p1 + ((g * n32 + rg) * 32 + cin) * BITS, unit);
         }
     }
 }
