@@ -119,7 +119,8 @@ def main():
         bd[r0:r1].copy_(torch.from_numpy(b))
     gen_s = time.perf_counter() - t0
 
-    def timed(fn, reps=1):
+    def timed(fn, reps=3):
+        fn()                      # first call: code object load, not what is being timed
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -187,7 +188,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32 (model, residuals; sums taken exactly on i8 digits)",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: n={n}, d={d}, {bits}-bit uniform levels, batch {B}, "
                                f"lr {w.lr}, fp32 model", "minibatch_steps_per_epoch": n // B,

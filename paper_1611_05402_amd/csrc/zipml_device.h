@@ -44,6 +44,12 @@ __device__ __forceinline__ Philox4 philox_block(uint64_t seed, uint32_t epoch, u
                          (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
+// Word k (0..3) of a block, chosen at run time without indexing the register array.
+__device__ __forceinline__ uint32_t philox_word(const Philox4 &r, uint32_t k)
+{
+    return k == 0 ? r.w[0] : k == 1 ? r.w[1] : k == 2 ? r.w[2] : r.w[3];
+}
+
 // Top 24 bits as a uniform in [0, 1); exact in fp32.
 __device__ __forceinline__ float u24(uint32_t word)
 {

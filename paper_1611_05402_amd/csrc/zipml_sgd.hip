@@ -423,7 +423,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     const int j = j0 + tid;
                     if (j < a.d) {
                         const Philox4 r = philox_block(a.seed, a.epoch, (uint64_t)t, (uint32_t)j >> 2, 3u);
-                        mine = qvec_code(xs[tid], Mx, s_m, u24(r.w[j & 3]));
+                        mine = qvec_code(xs[tid], Mx, s_m, u24(philox_word(r, (uint32_t)j & 3u)));
                     }
                     L.ms[tid] = mine;
                     if (dbg_m && j < a.d) dbg_m[j] = mine;
@@ -692,7 +692,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 const int j = j0 + tid;
                 if (j < a.d) {
                     const Philox4 r = philox_block(a.seed, a.epoch, (uint64_t)t, (uint32_t)j >> 2, 4u);
-                    const int code = qvec_code(gs[tid], Mg, s_g, u24(r.w[j & 3]));
+                    const int code = qvec_code(gs[tid], Mg, s_g, u24(philox_word(r, (uint32_t)j & 3u)));
                     if (dbg_gq) dbg_gq[j] = code;
                     const float gh = sg * (float)code;
                     const float stp = a.lr * gh;
