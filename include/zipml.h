@@ -102,7 +102,11 @@ int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, int64_t d, 
  * (Sec. 2 and eq. (5); the minibatch gradient is the mean over `batch` consecutive samples; the
  * n / batch steps run in storage order).  x_dev[d] is the fp32 master model, updated in place:
  * x <- x - lr * g every step (Supp. E: the update is in full precision).
- *   model_bits = grad_bits = 0: full-precision model and gradient (fp32 arithmetic).
+ *   model_bits = grad_bits = 0: full-precision (fp32) model, residuals and gradient.  The sums
+ *     over features and over samples are accumulated as integers (fixed-point partial sums, and
+ *     for evenly spaced 2-, 4- or 8-bit levels exact integer sums of codes times fixed-point
+ *     digits), so the result does not depend on the order in which workgroups finish: two calls
+ *     with the same arguments give the same bits.
  *   model_bits in 2..8: the model is stochastically quantised each step with row scaling
  *     (Supp. A.3 eq. (quant2), Supp. C), s = 2^(model_bits-1) - 1 magnitude intervals, and the dot
  *     product becomes an exact integer sum of grid_idx * model code; this needs grid_idx_dev and a

@@ -205,6 +205,29 @@ def test_sgd_epochs_match_oracle(name, factory, kw, epochs, lr, flags):
     assert np.linalg.norm(x_ref) > 0
 
 
+@pytest.mark.parametrize("name,factory,kw,lr", [
+    ("dense8_small", synth.dense8, dict(n=8192, d=288, batch=256), 1e-3),     # matrix-core loop
+    ("lowbit_small", synth.lowbit, dict(n=8192, d=96, batch=1024), 0.05),     # 2-bit, per-column ranges
+    ("b5", synth.tiny, dict(n=2048, d=160, batch=64, bits=5), 0.01),          # vector loop
+])
+def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
+    """Sums across workgroups are integer sums: the order of arrival must not show in the result."""
+    say("reproducible", name)
+    w = factory(**kw)
+    A, b = w.full()
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(_levels_for(w, A))
+    p.quantize(3, 0)
+    runs = []
+    for _ in range(3):
+        x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        for _ep in range(3):
+            p.epoch(x, lr)
+        runs.append(x.cpu().numpy().view(np.uint32).copy())
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
+    assert np.isfinite(runs[0].view(np.float32)).all() and np.any(runs[0] != 0)
+
+
 def test_sgd_fp32_with_non_uniform_levels():
     say("sgd fp32, optimal levels (table look-up path)")
     w = synth.e2e(n=2048, d=96, batch=64, n_candidates=128)
