@@ -41,7 +41,7 @@ namespace zipml {
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kMaxUpt = 4;                        // units per thread and pass that fit in registers
-constexpr uint32_t kSpinLimit = 1u << 22;         // bounded wait: a lost workgroup ends in ZIPML_ETIMEOUT
+constexpr uint32_t kSpinLimit = 1u << 22;         // default bound of a wait: a lost workgroup ends in ZIPML_ETIMEOUT
 
 // Exchange word: [63:54] arrival count, [53:0] sum of (value + kBias) over the arrived workgroups.
 // |value| < 2^44 for every contribution, so the low field never carries into the count.
@@ -99,6 +99,7 @@ struct SgdArgs {
     const double *bound;   // at launch: [0] sum_j maxabs(L_j)|x_j|, [1] sum_j maxabs(L_j)^2,
                            // [2] max_j delta_j|x_j|, [3] max_j delta_j maxabs(L_j)
     int mfma;              // evenly spaced levels may take the matrix-core step loop
+    uint32_t spin_limit;   // polls before a wait gives up (ZIPML_ETIMEOUT); the kernel still runs to its end
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     // debug outputs (may be null)
     int32_t *dbg_m, *dbg_acc, *dbg_gq;
@@ -334,7 +335,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
         uint32_t spins = 0;
 #pragma unroll 1
         while (!dead && load_dev(a.sync) < target) {
-            if (++spins > kSpinLimit) {
+            if (++spins > a.spin_limit) {
                 store_dev(a.status, (int)ZIPML_ETIMEOUT);
                 dead = true;
             }
@@ -559,7 +560,7 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 #pragma unroll
                         for (int q = 0; q < kBpt; ++q) all = all && (int)(raw[q] >> kCountShift) == W;
                         if (all || dead) break;
-                        if (++spins > kSpinLimit) {
+                        if (++spins > a.spin_limit) {
                             store_dev(a.status, (int)ZIPML_ETIMEOUT);
                             dead = true;
                         }
@@ -1071,6 +1072,11 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.W = p.W;
     a.lds_levels = p.lds_levels;
     a.mfma = p.mfma;
+    a.spin_limit = kSpinLimit;
+    if (const char *env = getenv("ZIPML_SPIN_LIMIT")) {   // test hook: make every wait give up early
+        const long v = atol(env);
+        if (v >= 0 && v <= (long)kSpinLimit) a.spin_limit = (uint32_t)v;
+    }
     a.status = (int *)(ws + Workspace::kStatus);
     a.sync = (uint32_t *)(ws + Workspace::kSync);
     a.nrm = (double *)(ws + Workspace::kNorm);

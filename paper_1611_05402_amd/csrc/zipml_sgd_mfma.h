@@ -435,7 +435,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 #pragma unroll
                     for (int q = 0; q < kBpt; ++q) all = all && (int)(raw[q] >> kCountShift) == W;
                     if (all || dead) break;
-                    if (++spins > kSpinLimit) {
+                    if (++spins > a.spin_limit) {
                         store_dev(a.status, (int)ZIPML_ETIMEOUT);
                         dead = true;
                     }

@@ -337,6 +337,34 @@ def test_end_to_end_optimal_levels_bit_exact():
     assert np.linalg.norm(x_ref) > 0
 
 
+# ------------------------------------------------------------------ failure handling
+@pytest.mark.parametrize("name,factory,kw", [
+    ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256)),          # matrix-core loop
+    ("b5_wide", synth.tiny, dict(n=2048, d=1056, batch=64, bits=5)),         # vector loop, 33 groups
+])
+def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, monkeypatch):
+    """Every device-wide wait is bounded.  With the bound forced to zero polls from the host, each
+    wait gives up at once: the kernel must still run to its end and leave ZIPML_ETIMEOUT."""
+    say("timeout path", name)
+    w = factory(**kw)
+    A, b = w.full()
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(_levels_for(w, A))
+    p.quantize(3, 0)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    monkeypatch.setenv("ZIPML_SPIN_LIMIT", "0")
+    zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 1e-3, p.ws)
+    st = zipml.sgd_status(p.ws)
+    monkeypatch.delenv("ZIPML_SPIN_LIMIT")
+    assert st == zipml.ETIMEOUT, zipml.strerror(st)
+    # the next call on the same workspace is sound again
+    x.zero_()
+    p.epoch(x, 1e-3)
+    c1, c2 = oracle.quantize(A, _levels_for(w, A), w.bits, 3, 0)
+    x_ref = oracle.sgd_epoch(c1, c2, _levels_for(w, A), b, w.bits, np.zeros(w.d, np.float32), w.batch, 1e-3)
+    assert rel_l2(x.cpu().numpy(), x_ref) <= TOL
+
+
 # ------------------------------------------------------------------ edge cases
 def test_degenerate_inputs():
     say("edge cases")
