@@ -41,7 +41,9 @@ inline Layout make_layout(int64_t n, int64_t d, int bits)
 struct Workspace {
     static constexpr size_t kStatus = 0;          // int32 status word + counters   (4 KiB)
     static constexpr size_t kSync = 4096;         // grid barrier counter                  (256 B)
-    static constexpr size_t kBound = 4096 + 256;  // magnitude bounds of the dot exchange: 2 doubles
+    static constexpr size_t kBound = 4096 + 256;  // magnitude bounds of the dot exchange: 4 doubles
+    static constexpr size_t kEven = 4096 + 1024;  // kEvenBlocks ints: levels evenly spaced, per block of features
+    static constexpr int kEvenBlocks = 64;
     static constexpr size_t kNorm = 8192;         // norm exchange: 2 x 3 x 512 doubles (24 KiB)
     static constexpr size_t kAcc = 8192 + 24576;  // 4 exchange buffers of acc_words 64-bit words
     static constexpr int kAccBuffers = 4;

@@ -99,6 +99,7 @@ struct SgdArgs {
     const double *bound;   // at launch: [0] sum_j maxabs(L_j)|x_j|, [1] sum_j maxabs(L_j)^2,
                            // [2] max_j delta_j|x_j|, [3] max_j delta_j maxabs(L_j)
     int mfma;              // evenly spaced levels may take the matrix-core step loop
+    const int *even;       // [kEvenBlocks] 1: the levels of that block of features are evenly spaced
     uint32_t spin_limit;   // polls before a wait gives up (ZIPML_ETIMEOUT); the kernel still runs to its end
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     // debug outputs (may be null)
@@ -782,6 +783,12 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         }
     }
     const bool affine = __syncthreads_and(ok) && !INT;
+    // ... and of every feature of the problem (found by the preparation kernel)?  Workgroups on
+    // the matrix-core loop and on the vector loop scale their contributions differently, so that
+    // choice has to be the same everywhere.
+    int ok_all = 1;
+    if (!INT && tid < Workspace::kEvenBlocks) ok_all = a.even[tid];
+    const bool affine_all = __syncthreads_and(ok_all) && !INT;
     for (int c = tid; c < CW; c += kThreads) {
         const bool live = j0 + c < a.d;
         const float lo = live ? Lg[(size_t)c * K] : 0.0f, hi = live ? Lg[(size_t)c * K + K - 1] : 0.0f;
@@ -801,7 +808,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
 
     constexpr bool kMfmaBits = BITS == 2 || BITS == 4 || BITS == 8;
     if constexpr (!INT && FAST && kMfmaBits) {
-        if (affine && a.mfma) {
+        if (affine_all && a.mfma) {
             if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1>(a, L, L.mf);
             else sgd_steps_mfma<BITS, UPT, 2>(a, L, L.mf);
         } else if (affine) {
@@ -821,8 +828,8 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
             if (j0 + c < a.d) a.x[j0 + c] = L.xs[c];
 }
 
-// Launch preparation: clears the barrier counter, the status word and exchange words; block 0
-// also takes the two magnitude bounds of the dot exchange from the levels and the current model,
+// Launch preparation: clears the barrier counter, the status word and exchange words, checks
+// block by block whether the levels are evenly spaced; block 0 also takes the two magnitude bounds of the dot exchange from the levels and the current model,
 //   bound[0] = sum_j maxabs(L_j) |x_j|,   bound[1] = sum_j maxabs(L_j)^2,
 //   bound[2] = max_j delta_j |x_j|,       bound[3] = max_j delta_j maxabs(L_j),
 // (delta_j: spacing of evenly spaced levels) in fp64 with a fixed order.
@@ -830,12 +837,28 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
                                                       int words, int clear_status,
                                                       const float *__restrict__ levels,
                                                       const float *__restrict__ x, int d, int K,
-                                                      double *bound)
+                                                      double *bound, int *even)
 {
     __shared__ double sb[256], sl[256], sy[256], sm[256];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
-    if (i < words) acc[i] = 0ull;
+    for (int e = i; e < words; e += gridDim.x * blockDim.x) acc[e] = 0ull;
+    // blocks 0 .. kEvenBlocks-1: are the levels of this block's features evenly spaced (fp64
+    // formula, rounded once)?
+    if (blockIdx.x < Workspace::kEvenBlocks) {
+        const int per = (d + Workspace::kEvenBlocks - 1) / Workspace::kEvenBlocks;
+        const int jb = blockIdx.x * per;
+        int ok = 1;
+        for (int e = threadIdx.x; e < per * K; e += 256) {
+            const int j = jb + e / K, c = e % K;
+            if (j < d) {
+                const double lo = (double)levels[(size_t)j * K], wdt = (double)levels[(size_t)j * K + K - 1] - lo;
+                ok &= (levels[(size_t)j * K + c] == (float)(lo + ((double)c * wdt) / (double)(K - 1)));
+            }
+        }
+        ok = __syncthreads_and(ok);
+        if (threadIdx.x == 0) even[blockIdx.x] = ok;
+    }
     if (blockIdx.x != 0) return;
     double pb = 0.0, pl = 0.0, py = 0.0, pm = 0.0;
     for (int j = threadIdx.x; j < d; j += 256) {
@@ -961,8 +984,8 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     const int words = Workspace::kAccBuffers * a.acc_words;
     const int K = 1 << BITS;
     double *bound = const_cast<double *>(a.bound);
-    hipLaunchKernelGGL(k_sgd_prepare, dim3((words + 255) / 256), dim3(256), 0, s, a.status, a.sync,
-                       a.acc, words, 1, a.levels, a.x, a.d, K, bound);
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, a.status, a.sync,
+                       a.acc, words, 1, a.levels, a.x, a.d, K, bound, const_cast<int *>(a.even));
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (!stepwise) {
         a.persistent = 1;
@@ -983,8 +1006,9 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         // the exchange buffer that step t uses was last used by step t-4: clear it; the magnitude
         // bounds are taken from the model as it stands before this step
         uint64_t *acct = a.acc + (size_t)(t & 3) * a.acc_words;
-        hipLaunchKernelGGL(k_sgd_prepare, dim3((a.acc_words + 255) / 256), dim3(256), 0, s, a.status,
-                           a.sync, acct, a.acc_words, 0, a.levels, a.x, a.d, K, bound);
+        hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, a.status,
+                           a.sync, acct, a.acc_words, 0, a.levels, a.x, a.d, K, bound,
+                           const_cast<int *>(a.even));
         for (int seg = 0; seg <= 3; ++seg) {
             if (seg == 0 && a.model_bits == 0) continue;
             if (seg == 3 && a.grad_bits == 0) continue;
@@ -1082,6 +1106,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.nrm = (double *)(ws + Workspace::kNorm);
     a.acc = (uint64_t *)(ws + Workspace::kAcc);
     a.bound = (const double *)(ws + Workspace::kBound);
+    a.even = (const int *)(ws + Workspace::kEven);
     a.acc_words = (int)Workspace::acc_words(batch);
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;

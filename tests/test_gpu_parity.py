@@ -228,6 +228,30 @@ def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
     assert np.isfinite(runs[0].view(np.float32)).all() and np.any(runs[0] != 0)
 
 
+def test_sgd_fp32_one_feature_not_evenly_spaced():
+    """Evenly spaced levels take the matrix-core loop; a single feature with other levels must
+    send every workgroup down the table path (workgroups on different loops would scale their
+    contributions to the exchange differently)."""
+    say("sgd fp32, 8-bit, one feature with uneven levels")
+    w = synth.dense8(n=4096, d=288, batch=256)
+    A, b = w.full()
+    L = _levels_for(w, A).copy()
+    rng = np.random.default_rng(3)
+    L[200] = np.sort(rng.uniform(-1, 1, 256)).astype(np.float32)
+    L[200, 0], L[200, -1] = -1.0, 1.0
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L)
+    p.quantize(2, 0)
+    c1, c2 = oracle.quantize(A, L, w.bits, 2, 0)
+    assert np.array_equal(p.codes(1), c1) and np.array_equal(p.codes(2), c2)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(2):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, 1e-3)
+        p.epoch(x, 1e-3)
+        assert rel_l2(x.cpu().numpy(), x_ref) <= TOL
+
+
 def test_sgd_fp32_with_non_uniform_levels():
     say("sgd fp32, optimal levels (table look-up path)")
     w = synth.e2e(n=2048, d=96, batch=64, n_candidates=128)
