@@ -100,6 +100,7 @@ struct SgdArgs {
                            // [2] max_j delta_j|x_j|, [3] max_j delta_j maxabs(L_j)
     int mfma;              // evenly spaced levels may take the matrix-core step loop
     const int *even;       // [kEvenBlocks] 1: the levels of that block of features are evenly spaced
+    int chunks;            // a minibatch is chunks * B samples (matrix-core loop only)
     uint32_t spin_limit;   // polls before a wait gives up (ZIPML_ETIMEOUT); the kernel still runs to its end
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     // debug outputs (may be null)
@@ -807,6 +808,11 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     }
 
     constexpr bool kMfmaBits = BITS == 2 || BITS == 4 || BITS == 8;
+    if (a.chunks > 1 && !(!INT && FAST && kMfmaBits && affine_all && a.mfma)) {
+        // a minibatch that is taken in chunks exists on the matrix-core loop only
+        if (w == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
+        return;
+    }
     if constexpr (!INT && FAST && kMfmaBits) {
         if (affine_all && a.mfma) {
             if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1>(a, L, L.mf);
@@ -1066,8 +1072,27 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     const Layout lay = make_layout(n, d, bits);
     const bool ident = model_bits > 0 && grid_max == (1 << bits) - 1;
     Plan p{};
-    if (int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, model_bits == 0, p))
-        return rc;
+    int64_t chunks = 1, micro = batch;
+    int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, model_bits == 0, p);
+    const bool stepwise = (flags & ZIPML_SGD_STEPWISE) != 0;
+    const bool debug = dbg_m || dbg_acc || dbg_r || dbg_g || dbg_gq;
+    if (rc == ZIPML_EUNSUPPORTED && model_bits == 0 && !stepwise && !debug && batch % 64 == 0) {
+        // A minibatch too large for one exchange is taken in equal chunks (matrix-core loop only:
+        // the kernel reports ZIPML_EUNSUPPORTED through the status word if the levels turn out
+        // not to be evenly spaced).
+        for (int64_t c = 2; c <= batch / 64; ++c) {
+            if (batch % c != 0 || (batch / c) % 64 != 0) continue;
+            Plan q{};
+            if (make_plan(lay.d32, bits, batch / c, false, true, q) == ZIPML_OK && q.mfma) {
+                p = q;
+                chunks = c;
+                micro = batch / c;
+                rc = ZIPML_OK;
+                break;
+            }
+        }
+    }
+    if (rc) return rc;
 
     unsigned char *ws = (unsigned char *)workspace_dev;
     SgdArgs a{};
@@ -1081,7 +1106,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.n32 = lay.n32;
     a.d = (int)d;
     a.d32 = (int)lay.d32;
-    a.B = (int)batch;
+    a.B = (int)micro;
+    a.chunks = (int)chunks;
     a.step0 = step0;
     a.nsteps = (int)nsteps;
     a.lr = lr;
@@ -1107,10 +1133,9 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.acc = (uint64_t *)(ws + Workspace::kAcc);
     a.bound = (const double *)(ws + Workspace::kBound);
     a.even = (const int *)(ws + Workspace::kEven);
-    a.acc_words = (int)Workspace::acc_words(batch);
+    a.acc_words = (int)Workspace::acc_words(micro);
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
-    const bool stepwise = (flags & ZIPML_SGD_STEPWISE) != 0;
     switch (bits) {
         case 1: return launch_sgd_mode<1>(s, a, p, stepwise);
         case 2: return launch_sgd_mode<2>(s, a, p, stepwise);

@@ -151,7 +151,10 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const bool owner = g_kh == 0 && lane < 16;          // this lane updates feature 16*g_ft + lane
     const int oc = 16 * g_ft + n16;                     // that feature, inside the workgroup
     float *const xs = L.xs;
-    const int64_t t_end = a.step0 + a.nsteps;
+    // A minibatch of C * B samples is taken as C chunks of B: every chunk has its own exchange,
+    // the model is updated after the last one.  u counts chunks through the epoch.
+    const int C = a.chunks;
+    const int64_t u_begin = a.step0 * C, u_end = (a.step0 + a.nsteps) * C;
 
     // ---- LDS of this path
     int8_t *const ydig = (int8_t *)mf;                              // [KB][4 digits][4 q][16]
@@ -171,11 +174,11 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 
     if (wave >= nw) {
         // nothing to look after: meet the others at their barriers, step by step
-        for (int64_t t = a.step0; t < t_end; ++t) {
+        for (int64_t u = u_begin; u < u_end; ++u) {
             lds_barrier();
             if (w == 0 && wave == kWaves - 1) {
                 // clear the exchange words of step t+2 (see zipml_sgd.hip for why now)
-                uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
+                uint64_t *nxt = a.acc + (size_t)((u + 2) & 3) * a.acc_words;
                 for (int i = lane; i < B + 2; i += kWave) store_dev(nxt + i, (uint64_t)0);
                 vm_wait_all();
             }
@@ -244,7 +247,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         for (int kb = 0; kb < KB; ++kb) {
             const int gq = 2 * kb + (q4 >> 1);
             p2ok[ti][kb] = tile < ntile && gq < ngroups;
-            const int64_t row = a.step0 * B + 16 * tile + n16;
+            const int64_t row = u_begin * B + 16 * tile + n16;
             const int64_t g = (int64_t)w * GQ + gq;
             p2ptr[ti][kb] = p2ok[ti][kb] ? a.p2 + (g * a.nb64 * 64 + row) * BITS + (q4 & 1) * HW : a.p2;
         }
@@ -255,7 +258,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         const int gq = g_ft >> 1, cin = 16 * (g_ft & 1) + n16;
         p1ok[m] = ks < NKS && gq < ngroups;
         const int64_t g = (int64_t)w * GQ + gq;
-        const int64_t rg = (a.step0 * B) / 32 + 2 * ks + (q4 >> 1);
+        const int64_t rg = (u_begin * B) / 32 + 2 * ks + (q4 >> 1);
         p1ptr[m] = p1ok[m] ? a.p1 + ((g * a.n32 + rg) * 32 + cin) * BITS + (q4 & 1) * HW : a.p1;
     }
     // loads of the step `ahead` steps after the one the pointers stand at
@@ -311,10 +314,10 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     for (int k = 0; k < kBpt; ++k) bnext[k] = bfut[k] = 0.0f;
     load_dot(0, c2cur);
     if constexpr (kDouble) {
-        if (a.step0 + 1 < t_end) load_dot(1, c2nxt);
+        if (u_begin + 1 < u_end) load_dot(1, c2nxt);
     }
     load_grad(0, c1);
-    load_labels(a.step0, bnext);
+    load_labels(u_begin, bnext);
 
     // where the digits of this thread's residuals go: sample i -> k-step i/64, q, byte
     int r_pos[kBpt];
@@ -332,10 +335,14 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     long long last_ = wall_clock64();
 #endif
 
-    for (int64_t t = a.step0; t < t_end; ++t) {
-        uint64_t *const acc = a.acc + (size_t)(t & 3) * a.acc_words;
-        const bool side_step = (t % kRefresh) == 0;            // bounds travel with this step's exchange
-        const bool side_next = ((t + 1) % kRefresh) == 0;
+    float rmax_step = 0.0f, gsum = 0.0f;
+    for (int64_t u = u_begin; u < u_end; ++u) {
+        const int64_t t = u / C;                                // minibatch step
+        const int chunk = (int)(u - t * C);
+        const bool first = chunk == 0, last = chunk == C - 1;
+        uint64_t *const acc = a.acc + (size_t)(u & 3) * a.acc_words;
+        const bool side_step = first && (t % kRefresh) == 0;   // bounds travel with this exchange
+        const bool side_next = last && ((t + 1) % kRefresh) == 0;
         ZIPML_TICK(7);
         lds_barrier();          // digits of y and the per-tile sums of the current model
         ZIPML_TICK(0);
@@ -387,7 +394,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         // for why that is the right moment and why no wait is needed here); with idle waves
         // around, one of them does it instead.
         if (nw == kWaves && w == 0 && wave == kWaves - 1) {
-            uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
+            uint64_t *nxt = a.acc + (size_t)((u + 2) & 3) * a.acc_words;
             for (int i = lane; i < B + 2; i += kWave) store_dev(nxt + i, (uint64_t)0);
             if (!(tid < B)) vm_wait_all();
         }
@@ -407,12 +414,12 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 p2ptr[ti][kb] += step_dwords;          // now stands at step t+1
             }
         if constexpr (kDouble) {
-            if (t + 2 < t_end) load_dot(1, c2nxt);
-            if (t + 1 < t_end) load_grad(1, c1nxt);
+            if (u + 2 < u_end) load_dot(1, c2nxt);
+            if (u + 1 < u_end) load_grad(1, c1nxt);
         } else {
-            if (t + 1 < t_end) load_dot(0, c2cur);
+            if (u + 1 < u_end) load_dot(0, c2cur);
         }
-        if (t + 1 < t_end) load_labels(t + 1, bfut);
+        if (u + 1 < u_end) load_labels(u + 1, bfut);
         ZIPML_TICK(1);
 
         // ============ residuals: poll the sums of this thread's samples
@@ -470,9 +477,14 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             beta_hat = side[0];
             ymax_hat = side[1] + ldexpf((float)W, -ky);     // |y_j| 2^ky <= |Y_j| + 1/2
         }
-        beta_hat += lr_abs * lambda * Rmax;
-        ymax_hat += lr_abs * mu * Rmax;
-        const int ky_next = scale_of();
+        rmax_step = fmaxf(rmax_step, Rmax);
+        int ky_next = ky;
+        if (last) {
+            beta_hat += lr_abs * lambda * rmax_step;
+            ymax_hat += lr_abs * mu * rmax_step;
+            ky_next = scale_of();
+            rmax_step = 0.0f;
+        }
         // residual digits
 #pragma unroll
         for (int q = 0; q < kBpt; ++q) {
@@ -503,7 +515,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 }
             }
             if constexpr (!kDouble) {
-                if (t + 1 < t_end) load_grad(0, c1);
+                if (u + 1 < u_end) load_grad(0, c1);
             }
             long long G = combine_digits(c);
             if (KSS > 1) {
@@ -515,16 +527,18 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             ZIPML_TICK(9);
             // owners: gradient, update, next step's digits
             if (g_kh == 0) {
-                float xnew = 0.0f;
-                if (owner) {
-                    const float S = fixed_to_float(G, kr);
-                    float g = o_mid * Rtot + o_dl * S;
-                    g = o_live ? __fdiv_rn(g, (float)B) : 0.0f;
-                    const float stp = a.lr * g;
-                    xnew = xs[oc] - stp;
-                    xs[oc] = xnew;
+                if (owner) gsum += o_mid * Rtot + o_dl * fixed_to_float(G, kr);   // chunks in order
+                if (last) {
+                    float xnew = 0.0f;
+                    if (owner) {
+                        const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)C) : 0.0f;
+                        const float stp = a.lr * g;
+                        xnew = xs[oc] - stp;
+                        xs[oc] = xnew;
+                    }
+                    gsum = 0.0f;
+                    refresh_y(xnew, ky_next, side_next);
                 }
-                refresh_y(xnew, ky_next, side_next);
             }
         }
         ky = ky_next;

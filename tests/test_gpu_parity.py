@@ -228,6 +228,40 @@ def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
     assert np.isfinite(runs[0].view(np.float32)).all() and np.any(runs[0] != 0)
 
 
+@pytest.mark.parametrize("name,factory,kw,batch,lr", [
+    ("dense8_b4096", synth.dense8, dict(n=8192, d=288), 4096, 0.05),       # two chunks of 2048
+    ("dense8_full_batch", synth.dense8, dict(n=8192, d=288), 8192, 0.05),  # gradient descent
+    ("lowbit_b8192", synth.lowbit, dict(n=16384, d=96), 8192, 0.2),        # 2-bit, per-column ranges
+])
+def test_large_minibatches_taken_in_chunks(name, factory, kw, batch, lr):
+    say("large batch", name)
+    w = factory(batch=batch, **kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, batch)
+    p.set_levels(L)
+    p.quantize(6, 0)
+    c1, c2 = oracle.quantize(A, L, w.bits, 6, 0)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(4):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, batch, lr)
+        p.epoch(x, lr)
+        err = rel_l2(x.cpu().numpy(), x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}")
+        assert err <= TOL
+    assert np.linalg.norm(x_ref) > 0
+    # with levels that are not evenly spaced such a batch is refused through the status word
+    L2 = L.copy()
+    L2[1] = np.sort(np.random.default_rng(0).uniform(L[1, 0], L[1, -1], L.shape[1])).astype(np.float32)
+    L2[1, 0], L2[1, -1] = L[1, 0], L[1, -1]
+    p.set_levels(L2)
+    x0 = x.clone()
+    zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, batch, lr, p.ws)
+    assert zipml.sgd_status(p.ws) == zipml.EUNSUPPORTED
+    assert torch.equal(x, x0)
+
+
 def test_sgd_fp32_one_feature_not_evenly_spaced():
     """Evenly spaced levels take the matrix-core loop; a single feature with other levels must
     send every workgroup down the table path (workgroups on different loops would scale their
