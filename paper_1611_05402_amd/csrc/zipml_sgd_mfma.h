@@ -232,7 +232,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             if (lane == 0) { bws[g_ft] = bw; ymx[g_ft] = amx; }
         }
     };
-    if (g_kh == 0) refresh_y(owner ? xs[oc] : 0.0f, ky, true);
+    float x_own = owner ? xs[oc] : 0.0f;               // the owner lane keeps its feature's weight
+    if (g_kh == 0) refresh_y(x_own, ky, true);
 
     // ---- packed data held in registers; the addresses advance by a fixed stride per step
     const int64_t step_dwords = (int64_t)B * BITS;      // both copies: B samples x BITS dwords per group
@@ -336,9 +337,9 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 #endif
 
     float rmax_step = 0.0f, gsum = 0.0f;
+    int64_t t = a.step0;                                        // minibatch step
+    int chunk = 0;
     for (int64_t u = u_begin; u < u_end; ++u) {
-        const int64_t t = u / C;                                // minibatch step
-        const int chunk = (int)(u - t * C);
         const bool first = chunk == 0, last = chunk == C - 1;
         uint64_t *const acc = a.acc + (size_t)(u & 3) * a.acc_words;
         const bool side_step = first && (t % kRefresh) == 0;   // bounds travel with this exchange
@@ -353,7 +354,9 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             const float4 c0 = *reinterpret_cast<const float4 *>(cqs);
             const float4 c1v = *reinterpret_cast<const float4 *>(cqs + 4);
             const float cq = ((c0.x + c0.y) + (c0.z + c0.w)) + ((c1v.x + c1v.y) + (c1v.z + c1v.w));
-            const long long kconst = __double2ll_rn(ldexp((double)cq, ky));
+            // cq * 2^ky as an integer (|.| < 2^43) without fp64: high part, then the exact rest
+            const float sc = ldexpf(cq, ky - 24), sc_hi = truncf(sc);
+            const long long kconst = ((long long)(int)sc_hi << 24) + (long long)__float2int_rn(ldexpf(sc - sc_hi, 24));
             // Four sample tiles share one accumulator: the digits of tile slot s sit in rows
             // 4s..4s+3 of its digit operand (zeros elsewhere), so its sums land in lanes
             // 16s..16s+15 and one combine / one atomic instruction serves all 64 lanes.
@@ -533,8 +536,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     if (owner) {
                         const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)C) : 0.0f;
                         const float stp = a.lr * g;
-                        xnew = xs[oc] - stp;
-                        xs[oc] = xnew;
+                        x_own = x_own - stp;
+                        xnew = x_own;
                     }
                     gsum = 0.0f;
                     refresh_y(xnew, ky_next, side_next);
@@ -542,8 +545,10 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             }
         }
         ky = ky_next;
+        if (last) { chunk = 0; ++t; } else { ++chunk; }
         ZIPML_TICK(6);
     }
+    if (owner) xs[oc] = x_own;
     lds_barrier();
 #ifdef ZIPML_PHASE_TIMING
     if (w == 0 && tid == 0)
