@@ -113,102 +113,135 @@ __device__ __forceinline__ void store_unit(uint32_t *__restrict__ p, const uint3
     for (int k = 0; k < BITS; ++k) q[k] = u[k];
 }
 
-constexpr int kTileCols = 128;   // 4 feature groups
-constexpr int kLdsRow = 33;      // dwords per LDS row of 128 code bytes (+1: conflict-free columns)
+constexpr int kTileCols = 64;    // 2 feature groups per workgroup
+constexpr int kLdsRow = 17;      // dwords per LDS row of 64 code bytes (+1: conflict-free columns)
 
+// Level tables of the workgroup's 64 features live in LDS ([64][K] floats, staged once); the
+// workgroup then walks down its share of the sample groups, 32 samples x 64 features per round,
+// with the fp32 values of the next round requested before the current one is worked on.
 template <int BITS>
 __global__ __launch_bounds__(256) void k_quantize_pack(
     const float *__restrict__ A, int64_t n_rows, int64_t d, int64_t lda, int64_t row0,
     int64_t nb64, int64_t n32, int64_t d32, const float *__restrict__ levels, uint64_t seed,
-    uint32_t epoch, uint32_t *__restrict__ p1, uint32_t *__restrict__ p2, int vec_ok)
+    uint32_t epoch, uint32_t *__restrict__ p1, uint32_t *__restrict__ p2, int vec_ok,
+    int64_t groups_per_block)
 {
+    extern __shared__ __align__(16) float tab[];          // [kTileCols][K]
     __shared__ uint32_t c1w[32 * kLdsRow];
     __shared__ uint32_t c2w[32 * kLdsRow];
     constexpr int K = 1 << BITS;
     const int tid = threadIdx.x;
-    const int64_t rg_local = blockIdx.x;              // sample group inside this chunk
     const int64_t col0 = (int64_t)blockIdx.y * kTileCols;
+    for (int e = tid; e < kTileCols * K; e += 256) {
+        const int64_t j = col0 + e / K;
+        tab[e] = j < d ? levels[j * K + e % K] : 0.0f;
+    }
+    __syncthreads();
 
-    // ---- phase 1: decide both codes of every element of the tile
-    const int cq = tid & 31;
+    const int cq = tid & 15;                  // which 4 features of the 64
     const int64_t col = col0 + 4 * cq;
     Column cols[4];
     bool live_col[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         live_col[e] = col + e < d;
-        cols[e] = make_column(levels + (live_col[e] ? col + e : 0) * K, K);
+        cols[e] = make_column(tab + (4 * cq + e) * K, K);
     }
+    const int64_t total_groups = (n_rows + 31) / 32;
+    const int64_t g_begin = (int64_t)blockIdx.x * groups_per_block;
+    const int64_t g_end = g_begin + groups_per_block < total_groups ? g_begin + groups_per_block : total_groups;
+    const bool vec = vec_ok && col + 3 < d;
+
+    auto fetch = [&](int64_t rg_local, float (&v)[2][4]) {
 #pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-        const int r = pass * 8 + (tid >> 5);
-        const int64_t i = rg_local * 32 + r;
-        uint32_t w1 = 0, w2 = 0;
-        if (i < n_rows && col < d) {
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            const float *src = A + i * lda + col;
-            if (vec_ok && col + 3 < d) {
-                const float4 q = *reinterpret_cast<const float4 *>(src);
-                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-            } else {
+        for (int pass = 0; pass < 2; ++pass) {
+            const int64_t i = rg_local * 32 + pass * 16 + (tid >> 4);
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (col + e < d) v[e] = src[e];
-            }
-            const uint64_t row = (uint64_t)(row0 + i);
-            const Philox4 r1 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 1u);
-            const Philox4 r2 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 2u);
-            int l[4];
-            float frac[4];
-            bracket4(cols, live_col, K, v, l, frac);
+            for (int e = 0; e < 4; ++e) v[pass][e] = 0.0f;
+            if (rg_local < g_end && i < n_rows && col < d) {
+                const float *src = A + i * lda + col;
+                if (vec) {
+                    const float4 q = *reinterpret_cast<const float4 *>(src);
+                    v[pass][0] = q.x; v[pass][1] = q.y; v[pass][2] = q.z; v[pass][3] = q.w;
+                } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (live_col[e]) {
-                    const uint32_t a = (uint32_t)l[e] + (u24(r1.w[e]) < frac[e] ? 1u : 0u);
-                    const uint32_t b = (uint32_t)l[e] + (u24(r2.w[e]) < frac[e] ? 1u : 0u);
-                    w1 |= a << (8 * e);
-                    w2 |= b << (8 * e);
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < d) v[pass][e] = src[e];
                 }
             }
         }
-        c1w[r * kLdsRow + cq] = w1;
-        c2w[r * kLdsRow + cq] = w2;
-    }
-    __syncthreads();
+    };
+    float vcur[2][4], vnxt[2][4];
+    fetch(g_begin, vcur);
+    for (int64_t rg_local = g_begin; rg_local < g_end; ++rg_local) {
+        fetch(rg_local + 1, vnxt);
+        // ---- phase 1: decide both codes of every element of the tile
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int r = pass * 16 + (tid >> 4);
+            const int64_t i = rg_local * 32 + r;
+            uint32_t w1 = 0, w2 = 0;
+            if (i < n_rows && col < d) {
+                const uint64_t row = (uint64_t)(row0 + i);
+                const Philox4 r1 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 1u);
+                const Philox4 r2 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 2u);
+                int l[4];
+                float frac[4];
+                bracket4(cols, live_col, K, vcur[pass], l, frac);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (live_col[e]) {
+                        const uint32_t a = (uint32_t)l[e] + (u24(r1.w[e]) < frac[e] ? 1u : 0u);
+                        const uint32_t b = (uint32_t)l[e] + (u24(r2.w[e]) < frac[e] ? 1u : 0u);
+                        w1 |= a << (8 * e);
+                        w2 |= b << (8 * e);
+                    }
+                }
+            }
+            c1w[r * kLdsRow + cq] = w1;
+            c2w[r * kLdsRow + cq] = w2;
+        }
+        __syncthreads();
 
-    // ---- phase 2: pack 32 codes per unit and store
-    const int64_t rg = row0 / 32 + rg_local;          // sample group in the whole matrix
-    if (tid < 128) {
-        // copy 2: one unit = sample r, feature group gq
-        const int r = tid & 31, gq = tid >> 5;
-        const int64_t g = col0 / 32 + gq;
-        if (g < d32) {
-            uint32_t unit[BITS];
+        // ---- phase 2: pack 32 codes per unit and store
+        const int64_t rg = row0 / 32 + rg_local;          // sample group in the whole matrix
+        if (tid < 64) {
+            // copy 2: one unit = sample r, feature group gq
+            const int r = tid & 31, gq = tid >> 5;
+            const int64_t g = col0 / 32 + gq;
+            if (g < d32) {
+                uint32_t unit[BITS];
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) unit[q] = 0;
+                for (int q = 0; q < BITS; ++q) unit[q] = 0;
 #pragma unroll
-            for (int k = 0; k < 32; ++k) {
-                const uint32_t w = c2w[r * kLdsRow + gq * 8 + (k >> 2)];
-                unit_set<BITS>(unit, k, (w >> (8 * (k & 3))) & 0xFFu);
+                for (int k = 0; k < 32; ++k) {
+                    const uint32_t w = c2w[r * kLdsRow + gq * 8 + (k >> 2)];
+                    unit_set<BITS>(unit, k, (w >> (8 * (k & 3))) & 0xFFu);
+                }
+                const int64_t i = rg * 32 + r;
+                store_unit<BITS>(p2 + (g * nb64 * 64 + i) * BITS, unit);
             }
-            const int64_t i = rg * 32 + r;
-            store_unit<BITS>(p2 + (g * nb64 * 64 + i) * BITS, unit);
-        }
-    } else {
-        // copy 1: one unit = feature c, the 32 samples of this group
-        const int c = tid - 128, gq = c >> 5, cin = c & 31;
-        const int64_t g = col0 / 32 + gq;
-        if (g < d32) {
-            uint32_t unit[BITS];
+        } else if (tid < 128) {
+            // copy 1: one unit = feature c, the 32 samples of this group
+            const int c = tid - 64, gq = c >> 5, cin = c & 31;
+            const int64_t g = col0 / 32 + gq;
+            if (g < d32) {
+                uint32_t unit[BITS];
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) unit[q] = 0;
+                for (int q = 0; q < BITS; ++q) unit[q] = 0;
 #pragma unroll
-            for (int k = 0; k < 32; ++k) {
-                const uint32_t w = c1w[k * kLdsRow + (c >> 2)];
-                unit_set<BITS>(unit, k, (w >> (8 * (c & 3))) & 0xFFu);
+                for (int k = 0; k < 32; ++k) {
+                    const uint32_t w = c1w[k * kLdsRow + (c >> 2)];
+                    unit_set<BITS>(unit, k, (w >> (8 * (c & 3))) & 0xFFu);
+                }
+                store_unit<BITS>(p1 + ((g * n32 + rg) * 32 + cin) * BITS, unit);
             }
-            store_unit<BITS>(p1 + ((g * n32 + rg) * 32 + cin) * BITS, unit);
         }
+        __syncthreads();
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vcur[pass][e] = vnxt[pass][e];
     }
 }
 
@@ -252,9 +285,21 @@ static int launch_quantize(hipStream_t s, const float *A, int64_t n_rows, int64_
                            uint32_t epoch, uint32_t *p1, uint32_t *p2)
 {
     const int vec_ok = (lda % 4 == 0) && aligned16(A);
-    dim3 grid((unsigned)((n_rows + 31) / 32), (unsigned)((lay.d32 + 3) / 4));
-    hipLaunchKernelGGL(k_quantize_pack<BITS>, grid, dim3(256), 0, s, A, n_rows, d, lda, row0,
-                       lay.nb64, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok);
+    const int64_t col_blocks = (lay.d + kTileCols - 1) / kTileCols;
+    const int64_t groups = (n_rows + 31) / 32;
+    // about 2048 workgroups in all, each with at least 4 sample groups to amortise its tables
+    int64_t row_blocks = (2048 + col_blocks - 1) / col_blocks;
+    if (row_blocks > (groups + 3) / 4) row_blocks = (groups + 3) / 4;
+    if (row_blocks < 1) row_blocks = 1;
+    if (col_blocks > 65535 || row_blocks > 0x7FFFFFFF) return ZIPML_EUNSUPPORTED;
+    const int64_t per_block = (groups + row_blocks - 1) / row_blocks;
+    const size_t shmem = (size_t)kTileCols * (1u << BITS) * sizeof(float);
+    if (HIP_FAILED(hipFuncSetAttribute((const void *)k_quantize_pack<BITS>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
+        return ZIPML_ELAUNCH;
+    dim3 grid((unsigned)row_blocks, (unsigned)col_blocks);
+    hipLaunchKernelGGL(k_quantize_pack<BITS>, grid, dim3(256), shmem, s, A, n_rows, d, lda, row0,
+                       lay.nb64, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok, per_block);
     return hip_check(hipGetLastError());
 }
 
