@@ -788,8 +788,8 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     // the matrix-core loop and on the vector loop scale their contributions differently, so that
     // choice has to be the same everywhere.
     int ok_all = 1;
-    if (!INT && tid < Workspace::kEvenBlocks) ok_all = a.even[tid];
-    const bool affine_all = __syncthreads_and(ok_all) && !INT;
+    if (a.mfma && tid < Workspace::kEvenBlocks) ok_all = a.even[tid];
+    const bool affine_all = __syncthreads_and(ok_all) && a.mfma != 0;
     for (int c = tid; c < CW; c += kThreads) {
         const bool live = j0 + c < a.d;
         const float lo = live ? Lg[(size_t)c * K] : 0.0f, hi = live ? Lg[(size_t)c * K + K - 1] : 0.0f;
@@ -849,18 +849,25 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
     for (int e = i; e < words; e += gridDim.x * blockDim.x) acc[e] = 0ull;
-    // blocks 0 .. kEvenBlocks-1: are the levels of this block's features evenly spaced (fp64
-    // formula, rounded once)?
-    if (blockIdx.x < Workspace::kEvenBlocks) {
-        const int per = (d + Workspace::kEvenBlocks - 1) / Workspace::kEvenBlocks;
-        const int jb = blockIdx.x * per;
+    // blocks 0 .. kEvenBlocks-1: is this block's share of the level tables evenly spaced (fp64
+    // formula, rounded once)?  Asked only where the answer matters (K a multiple of 4): four
+    // entries per load, the loads of a thread independent of each other.
+    if (even && blockIdx.x < Workspace::kEvenBlocks) {
+        const int spf = K / 4;                                   // 16-byte segments per feature
+        const int64_t total = (int64_t)d * spf;
+        const int64_t per = (total + Workspace::kEvenBlocks - 1) / Workspace::kEvenBlocks;
+        const int64_t s_end = (blockIdx.x + 1) * per < total ? (blockIdx.x + 1) * per : total;
         int ok = 1;
-        for (int e = threadIdx.x; e < per * K; e += 256) {
-            const int j = jb + e / K, c = e % K;
-            if (j < d) {
-                const double lo = (double)levels[(size_t)j * K], wdt = (double)levels[(size_t)j * K + K - 1] - lo;
-                ok &= (levels[(size_t)j * K + c] == (float)(lo + ((double)c * wdt) / (double)(K - 1)));
-            }
+        for (int64_t sg = blockIdx.x * per + threadIdx.x; sg < s_end; sg += 256) {
+            const int64_t j = sg / spf;
+            const int c0 = (int)(sg % spf) * 4;
+            const float *row = levels + j * K;
+            const double lo = (double)row[0], wdt = (double)row[K - 1] - lo;
+            const float4 v = *reinterpret_cast<const float4 *>(row + c0);
+            ok &= (v.x == (float)(lo + ((double)(c0 + 0) * wdt) / (double)(K - 1)));
+            ok &= (v.y == (float)(lo + ((double)(c0 + 1) * wdt) / (double)(K - 1)));
+            ok &= (v.z == (float)(lo + ((double)(c0 + 2) * wdt) / (double)(K - 1)));
+            ok &= (v.w == (float)(lo + ((double)(c0 + 3) * wdt) / (double)(K - 1)));
         }
         ok = __syncthreads_and(ok);
         if (threadIdx.x == 0) even[blockIdx.x] = ok;
@@ -991,7 +998,8 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     const int K = 1 << BITS;
     double *bound = const_cast<double *>(a.bound);
     hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, a.status, a.sync,
-                       a.acc, words, 1, a.levels, a.x, a.d, K, bound, const_cast<int *>(a.even));
+                       a.acc, words, 1, a.levels, a.x, a.d, K, bound,
+                       a.mfma ? const_cast<int *>(a.even) : nullptr);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (!stepwise) {
         a.persistent = 1;
@@ -1013,8 +1021,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         // bounds are taken from the model as it stands before this step
         uint64_t *acct = a.acc + (size_t)(t & 3) * a.acc_words;
         hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, a.status,
-                           a.sync, acct, a.acc_words, 0, a.levels, a.x, a.d, K, bound,
-                           const_cast<int *>(a.even));
+                           a.sync, acct, a.acc_words, 0, a.levels, a.x, a.d, K, bound, nullptr);
         for (int seg = 0; seg <= 3; ++seg) {
             if (seg == 0 && a.model_bits == 0) continue;
             if (seg == 3 && a.grad_bits == 0) continue;
@@ -1121,7 +1128,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.GQ = p.GQ;
     a.W = p.W;
     a.lds_levels = p.lds_levels;
-    a.mfma = p.mfma;
+    a.mfma = (p.mfma && !stepwise && !debug) ? 1 : 0;   // the matrix-core loop exists in the production launch only
     a.spin_limit = kSpinLimit;
     if (const char *env = getenv("ZIPML_SPIN_LIMIT")) {   // test hook: make every wait give up early
         const long v = atol(env);
