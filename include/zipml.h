@@ -124,6 +124,16 @@ int zipml_sgd_epoch(void *stream, const void *packed1_dev, const void *packed2_d
                     uint64_t seed, uint32_t epoch, int flags, void *workspace_dev,
                     size_t workspace_bytes);
 
+/* The same epoch for the least-squares SVM objective
+ *   1/(2n) sum_i (a_i^T x - b_i)^2 + (c/2) ||x||^2,  b_i in {-1, +1}
+ * ("Extension to Classification Models", Least Squares Support Vector Machines): the gradient of a
+ * step gets the additional term c * x, taken in full precision:  x <- x - lr * (g + l2 * x).
+ * Full-precision (fp32) model only; l2 >= 0; everything else as in zipml_sgd_epoch. */
+int zipml_sgd_epoch_l2(void *stream, const void *packed1_dev, const void *packed2_dev,
+                       const float *levels_dev, const float *b_dev, int64_t n, int64_t d, int bits,
+                       float *x_dev, int64_t batch, float lr, float l2, int flags,
+                       void *workspace_dev, size_t workspace_bytes);
+
 /* Waits for the stream and returns the status word the last zipml_sgd_epoch / zipml_debug_step
  * left in this workspace: ZIPML_OK or ZIPML_ETIMEOUT. */
 int zipml_sgd_status(void *stream, const void *workspace_dev, size_t workspace_bytes);

@@ -183,7 +183,7 @@ def grad_double(code1, code2, levels, bits, x, b):
     return g
 
 
-def sgd_epoch(codes1, codes2, levels, b, bits, x, batch, lr, symmetric=False):
+def sgd_epoch(codes1, codes2, levels, b, bits, x, batch, lr, symmetric=False, l2=0.0):
     """One epoch in full-precision-model mode; returns the new fp32 model."""
     codes1 = np.ascontiguousarray(codes1, np.uint8)
     codes2 = np.ascontiguousarray(codes2, np.uint8)
@@ -192,7 +192,7 @@ def sgd_epoch(codes1, codes2, levels, b, bits, x, batch, lr, symmetric=False):
     n, d = codes1.shape
     lib().zo_sgd_epoch(_p(codes1), _p(codes2), _p(levels), _p(b), C.c_int64(n), C.c_int64(d),
                        C.c_int(bits), _p(x), C.c_int64(batch), C.c_float(lr),
-                       C.c_int(int(symmetric)))
+                       C.c_int(int(symmetric)), C.c_float(l2))
     return x
 
 

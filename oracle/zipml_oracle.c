@@ -381,10 +381,12 @@ void zo_grad_double(const uint8_t *code1, const uint8_t *code2, const float *lev
 /*                                                                           */
 /* Full-precision-model mode (this function): every operation inside a step  */
 /* is fp64; the model is rounded to fp32 once per step, at the update.       */
+/* With l2 = c the objective has the extra term (c/2)||x||^2 of the least-   */
+/* squares SVM (labels +-1) and a step is  x <- x - lr (g + c x).            */
 /* ------------------------------------------------------------------------- */
 void zo_sgd_epoch(const uint8_t *codes1, const uint8_t *codes2, const float *levels,
                   const float *b, int64_t n, int64_t d, int bits, float *x, int64_t batch,
-                  float lr, int symmetric)
+                  float lr, int symmetric, float l2)
 {
     int K = 1 << bits;
     double *r2 = malloc(sizeof(double) * (size_t)batch); /* residuals from copy 2 */
@@ -413,7 +415,10 @@ void zo_sgd_epoch(const uint8_t *codes1, const uint8_t *codes2, const float *lev
             }
             g[j] = acc / (double)batch;
         }
-        for (int64_t j = 0; j < d; ++j) x[j] = (float)((double)x[j] - (double)lr * g[j]);
+        /* l2 = c > 0: least-squares SVM, the gradient gets the additional term c x
+         * ("Extension to Classification Models"). */
+        for (int64_t j = 0; j < d; ++j)
+            x[j] = (float)((double)x[j] - (double)lr * (g[j] + (double)l2 * (double)x[j]));
     }
     free(r2); free(r1); free(g);
 }

@@ -82,6 +82,7 @@ struct SgdArgs {
     int64_t step0;         // first step of this launch
     int nsteps;
     float lr, grid_lo, grid_step;
+    float l2;              // coefficient c of the extra gradient term c * x (least-squares SVM)
     int grad_bits, model_bits;
     int ident_grid;        // grid_idx[j][c] == c
     uint64_t seed;
@@ -610,7 +611,8 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 float Rabs = 0.0f;
 #pragma unroll
                 for (int q = 0; q < kWaves; ++q) Rabs += L.wsum[2 * kWaves + q];
-                bound_hat += fabs((double)a.lr) * lambda * ((double)Rabs / (double)B);
+                bound_hat += fabs((double)a.lr) * (lambda * ((double)Rabs / (double)B) +
+                                                   fabs((double)a.l2) * bound_hat);
             }
 
             ZIPML_TICK(8);
@@ -703,7 +705,8 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 }
             }
         } else if (tid < CW) {
-            const float stp = a.lr * gs[tid];
+            const float reg = a.l2 * xs[tid];
+            const float stp = a.lr * (gs[tid] + reg);
             xs[tid] = xs[tid] - stp;
         }
         if (MODE == kAffine) {
@@ -1046,7 +1049,7 @@ static int launch_sgd_mode(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwi
 static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_dev,
                    const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
                    float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d, int bits,
-                   float *x_dev, int64_t batch, float lr, int grad_bits, int model_bits,
+                   float *x_dev, int64_t batch, float lr, float l2, int grad_bits, int model_bits,
                    uint64_t seed, uint32_t epoch, int flags, int64_t step0, int64_t nsteps,
                    int32_t *dbg_m, int32_t *dbg_acc, float *dbg_r, float *dbg_g, int32_t *dbg_gq,
                    void *workspace_dev, size_t workspace_bytes)
@@ -1062,6 +1065,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     if (flags & ~(ZIPML_SGD_STEPWISE | ZIPML_SGD_AVERAGED)) return ZIPML_EINVAL;
     if (flags & ZIPML_SGD_AVERAGED) return ZIPML_EUNSUPPORTED;
     if (grad_bits > 0 && model_bits == 0) return ZIPML_EUNSUPPORTED;
+    if (!(l2 >= 0.0f)) return ZIPML_EINVAL;
+    if (l2 != 0.0f && model_bits > 0) return ZIPML_EUNSUPPORTED;   // the c*x term is not quantised here
     if (model_bits > 0) {
         if (!grid_idx_dev || grid_max < (1 << bits) - 1 || grid_max > 65535) return ZIPML_EINVAL;
         const int64_t s_m = ((int64_t)1 << (model_bits - 1)) - 1;
@@ -1118,6 +1123,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.step0 = step0;
     a.nsteps = (int)nsteps;
     a.lr = lr;
+    a.l2 = l2;
     a.grid_lo = grid_lo;
     a.grid_step = grid_step;
     a.grad_bits = grad_bits;
@@ -1170,9 +1176,20 @@ extern "C" int zipml_sgd_epoch(void *stream, const void *packed1_dev, const void
 {
     const int64_t steps = (batch > 0 && n > 0 && n % batch == 0) ? n / batch : 0;
     return run_sgd(stream, packed1_dev, packed2_dev, levels_dev, grid_idx_dev, grid_lo, grid_step,
-                   grid_max, b_dev, n, d, bits, x_dev, batch, lr, grad_bits, model_bits, seed, epoch,
-                   flags, 0, steps, nullptr, nullptr, nullptr, nullptr, nullptr, workspace_dev,
-                   workspace_bytes);
+                   grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits, model_bits, seed,
+                   epoch, flags, 0, steps, nullptr, nullptr, nullptr, nullptr, nullptr,
+                   workspace_dev, workspace_bytes);
+}
+
+extern "C" int zipml_sgd_epoch_l2(void *stream, const void *packed1_dev, const void *packed2_dev,
+                                  const float *levels_dev, const float *b_dev, int64_t n, int64_t d,
+                                  int bits, float *x_dev, int64_t batch, float lr, float l2,
+                                  int flags, void *workspace_dev, size_t workspace_bytes)
+{
+    const int64_t steps = (batch > 0 && n > 0 && n % batch == 0) ? n / batch : 0;
+    return run_sgd(stream, packed1_dev, packed2_dev, levels_dev, nullptr, 0.0f, 0.0f, 0, b_dev, n, d,
+                   bits, x_dev, batch, lr, l2, 0, 0, 0, 0, flags, 0, steps, nullptr, nullptr, nullptr,
+                   nullptr, nullptr, workspace_dev, workspace_bytes);
 }
 
 extern "C" int zipml_debug_step(void *stream, const void *packed1_dev, const void *packed2_dev,
@@ -1186,8 +1203,8 @@ extern "C" int zipml_debug_step(void *stream, const void *packed1_dev, const voi
                                 size_t workspace_bytes)
 {
     return run_sgd(stream, packed1_dev, packed2_dev, levels_dev, grid_idx_dev, grid_lo, grid_step,
-                   grid_max, b_dev, n, d, bits, x_dev, batch, lr, grad_bits, model_bits, seed, epoch,
-                   flags, step, 1, model_codes_dev, acc_dev, r_dev, g_dev, grad_codes_dev,
+                   grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits, model_bits, seed,
+                   epoch, flags, step, 1, model_codes_dev, acc_dev, r_dev, g_dev, grad_codes_dev,
                    workspace_dev, workspace_bytes);
 }
 

@@ -193,13 +193,13 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     // ---- bounds that fix the fixed-point scale of a step; every workgroup computes the same
     // numbers in the same order.  beta_hat >= sum_j maxabs(L_j)|x_j| bounds every partial and full
     // dot product; ymax_hat >= max_j |y_j| keeps the digits of y inside 32 bits.  Both are exact
-    // at launch, grow every step by a bound on the model's change (|dx_j| <= lr maxabs(L_j) max_i
-    // |r_i|), and are refreshed from exact per-workgroup values every kRefresh steps.
+    // at launch, grow every step by a bound on the model's change (|dx_j| <= lr (maxabs(L_j) max_i
+    // |r_i| + c |x_j|)), and are refreshed from exact per-workgroup values every kRefresh steps.
     float beta_hat = (float)a.bound[0] * 1.00001f;
     const float lambda = (float)a.bound[1] * 1.00001f;   // sum_j maxabs(L_j)^2
     float ymax_hat = (float)a.bound[2] * 1.00001f;
     const float mu = (float)a.bound[3] * 1.00001f;       // max_j delta_j maxabs(L_j)
-    const float lr_abs = fabsf(a.lr) * 1.00001f;
+    const float lr_abs = fabsf(a.lr) * 1.00001f, l2_abs = fabsf(a.l2) * 1.00001f;
     auto scale_of = [&]() {
         const int k1 = scale_exponent(beta_hat, 42), k2 = scale_exponent(ymax_hat, 29);
         return k1 < k2 ? k1 : k2;
@@ -483,8 +483,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         rmax_step = fmaxf(rmax_step, Rmax);
         int ky_next = ky;
         if (last) {
-            beta_hat += lr_abs * lambda * rmax_step;
-            ymax_hat += lr_abs * mu * rmax_step;
+            beta_hat += lr_abs * (lambda * rmax_step + l2_abs * beta_hat);
+            ymax_hat += lr_abs * (mu * rmax_step + l2_abs * ymax_hat);
             ky_next = scale_of();
             rmax_step = 0.0f;
         }
@@ -535,7 +535,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     float xnew = 0.0f;
                     if (owner) {
                         const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)C) : 0.0f;
-                        const float stp = a.lr * g;
+                        const float reg = a.l2 * x_own;
+                        const float stp = a.lr * (g + reg);
                         x_own = x_own - stp;
                         xnew = x_own;
                     }

@@ -40,6 +40,8 @@ class Workload:
     noise: float = 0.0
     seed: int = 0
     kind: str = "uniform"
+    sign_labels: bool = False        # two-class labels b = sign(a.x* + noise) in {-1, +1}
+    l2: float = 0.0                  # coefficient of the (c/2)||x||^2 term
     x_star: np.ndarray = field(default=None, repr=False)
     _col_scale: np.ndarray = field(default=None, repr=False)
     _col_min: np.ndarray = field(default=None, repr=False)
@@ -98,6 +100,8 @@ class Workload:
                 c0 = chunk * CHUNK
                 a, b = max(i0, c0), min(i1, c0 + rows)
                 out[a - i0:b - i0] += e[a - c0:b - c0]
+        if self.sign_labels:
+            out = np.where(out >= 0.0, 1.0, -1.0)
         return out.astype(np.float32)
 
     def full(self):
@@ -182,6 +186,13 @@ def dense8(n=65536, d=2048, seed=0, bits=8, batch=256) -> Workload:
                             seed=seed), 1.0 / np.sqrt(d))
 
 
+def lssvm(n=8192, d=288, seed=0, bits=8, batch=256, l2=0.05) -> Workload:
+    """Two-class least-squares SVM: clipped-normal features scaled to [-1,1], labels +-1 from a
+    random hyperplane with label noise, (c/2)||x||^2 regularisation."""
+    return _finish(Workload("lssvm", n, d, bits, batch, 0.05, 5, kind="gauss", noise=0.05,
+                            seed=seed, sign_labels=True, l2=l2), 1.0 / np.sqrt(d))
+
+
 def lowbit(n=1048576, d=512, seed=0, bits=2, batch=1024) -> Workload:
     """Workload 3: U[-1,1] with 20 % of the columns scaled by 0.05; per-column ranges."""
     return _finish(Workload("lowbit", n, d, bits, batch, 0.2, 5, kind="hetero", noise=0.1,
@@ -209,4 +220,4 @@ def ongrid(n=1024, d=32, seed=0, bits=3, batch=32, lo=-1.0, hi=1.0) -> Workload:
                             lo=lo, hi=hi, seed=seed), 1.0)
 
 
-WORKLOADS = {"tiny": tiny, "dense8": dense8, "lowbit": lowbit, "tomo": tomo, "e2e": e2e}
+WORKLOADS = {"lssvm": lssvm, "tiny": tiny, "dense8": dense8, "lowbit": lowbit, "tomo": tomo, "e2e": e2e}

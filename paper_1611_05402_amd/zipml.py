@@ -20,7 +20,7 @@ SGD_STEPWISE, SGD_AVERAGED = 1, 2
 OK, EINVAL, EALIGN, ERANGE, EWORKSPACE, ELAUNCH, EUNSUPPORTED, ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = ["zipml_strerror", "zipml_packed_bytes", "zipml_workspace_bytes", "zipml_levels",
-           "zipml_quantize", "zipml_sgd_epoch", "zipml_sgd_status", "zipml_loss",
+           "zipml_quantize", "zipml_sgd_epoch", "zipml_sgd_epoch_l2", "zipml_sgd_status", "zipml_loss",
            "zipml_unpack_codes", "zipml_debug_step"]
 
 
@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         sgd = [vp, vp, vp, vp, vp, f32, f32, i32, vp, i64, i64, i32, vp, i64, f32, i32, i32, u64, u32]
         L.zipml_sgd_epoch.restype = i32
         L.zipml_sgd_epoch.argtypes = sgd + [i32, vp, sz]
+        L.zipml_sgd_epoch_l2.restype = i32
+        L.zipml_sgd_epoch_l2.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, i64, f32, f32, i32, vp, sz]
         L.zipml_debug_step.restype = i32
         L.zipml_debug_step.argtypes = sgd + [i64, i32, vp, vp, vp, vp, vp, vp, sz]
         L.zipml_sgd_status.restype = i32
@@ -133,6 +135,14 @@ def sgd_epoch(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, workspace
                      bits, x, batch, lr, grad_bits, model_bits, seed, epoch, stream)
     _check(lib().zipml_sgd_epoch(*args, flags, _ptr(workspace),
                                  workspace.numel() * workspace.element_size()), "zipml_sgd_epoch")
+
+
+def sgd_epoch_l2(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, l2, workspace, *, flags=0,
+                 stream=None):
+    _check(lib().zipml_sgd_epoch_l2(_stream(stream), _ptr(packed1), _ptr(packed2), _ptr(levels_t),
+                                    _ptr(b), n, d, bits, _ptr(x), batch, lr, l2, flags,
+                                    _ptr(workspace), workspace.numel() * workspace.element_size()),
+           "zipml_sgd_epoch_l2")
 
 
 def debug_step(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, step, workspace, *,

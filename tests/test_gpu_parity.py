@@ -395,6 +395,42 @@ def test_end_to_end_optimal_levels_bit_exact():
     assert np.linalg.norm(x_ref) > 0
 
 
+# ------------------------------------------------------------------ least-squares SVM
+@pytest.mark.parametrize("name,kw", [
+    ("lssvm_8bit", dict()),                                   # matrix-core loop
+    ("lssvm_5bit_wide", dict(n=2048, d=1056, bits=5, batch=64)),   # vector loop, many workgroups
+    ("lssvm_small", dict(n=1024, d=96, bits=4, batch=32)),    # single workgroup
+])
+def test_least_squares_svm_epochs_match_oracle(name, kw):
+    say("ls-svm", name)
+    w = synth.lssvm(**kw)
+    A, b = w.full()
+    assert set(np.unique(b)) == {-1.0, 1.0}
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L)
+    p.quantize(12, 0)
+    c1, c2 = oracle.quantize(A, L, w.bits, 12, 0)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(3):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, w.lr, l2=w.l2)
+        zipml.sgd_epoch_l2(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, w.lr, w.l2, p.ws)
+        assert zipml.sgd_status(p.ws) == 0
+        err = rel_l2(x.cpu().numpy(), x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}")
+        assert err <= TOL
+    # the term matters, and the classifier it trains is better than chance
+    x_plain = oracle.sgd_epoch(c1, c2, L, b, w.bits, np.zeros(w.d, np.float32), w.batch, w.lr)
+    x_one = oracle.sgd_epoch(c1, c2, L, b, w.bits, np.zeros(w.d, np.float32), w.batch, w.lr, l2=w.l2)
+    assert rel_l2(x_one, x_plain) > 1e-4
+    acc = np.mean(np.sign(A @ x.cpu().numpy()) == b)
+    assert acc > 0.7
+    with pytest.raises(zipml.ZipmlError) as e:
+        zipml.sgd_epoch_l2(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, w.lr, -1.0, p.ws)
+    assert e.value.code == zipml.EINVAL
+
+
 # ------------------------------------------------------------------ failure handling
 @pytest.mark.parametrize("name,factory,kw", [
     ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256)),          # matrix-core loop

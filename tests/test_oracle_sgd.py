@@ -93,6 +93,41 @@ def test_epoch_uses_copy2_in_the_dot_and_copy1_outside():
     assert np.allclose(got, sym, atol=1e-7)
 
 
+# ------------------------------------------------------------------ least-squares SVM term
+def test_l2_term_reduces_to_textbook_ridge_sgd_and_its_closed_form():
+    """With on-grid data the quantisers are the identity, so an epoch with the extra c*x term
+    ("Extension to Classification Models", least-squares SVM) must equal textbook SGD on
+    1/(2n)||Ax-b||^2 + (c/2)||x||^2, and many epochs must reach (A^T A/n + cI)^-1 A^T b/n."""
+    bits, batch, c = 3, 32, 0.3
+    w = synth.ongrid(n=1024, d=12, bits=bits, batch=batch)
+    L = oracle.levels_uniform([w.lo] * w.d, [w.hi] * w.d, bits)
+    rng = np.random.default_rng(8)
+    codes = rng.integers(0, 1 << bits, (w.n, w.d))
+    A = np.take_along_axis(L.T, codes, axis=0).astype(np.float32)
+    b = np.where(A @ w.x_star >= 0, 1.0, -1.0).astype(np.float32)      # two-class labels
+    c1, c2 = oracle.quantize(A, L, bits, seed=5, epoch=0)
+    x0 = rng.standard_normal(w.d).astype(np.float32)
+    # one epoch against a plain NumPy loop
+    x = x0.astype(np.float64)
+    for t in range(w.n // batch):
+        Ab = A[t * batch:(t + 1) * batch].astype(np.float64)
+        g = Ab.T @ (Ab @ x - b[t * batch:(t + 1) * batch]) / batch
+        x = (x - 0.05 * (g + c * x)).astype(np.float32).astype(np.float64)
+    got = oracle.sgd_epoch(c1, c2, L, b, bits, x0, batch, 0.05, l2=c)
+    assert np.allclose(got, x, rtol=0, atol=1e-6)
+    assert not np.allclose(got, oracle.sgd_epoch(c1, c2, L, b, bits, x0, batch, 0.05), atol=1e-3)
+    # closed form of the regularised problem
+    A64 = A.astype(np.float64)
+    x_ridge = np.linalg.solve(A64.T @ A64 / w.n + c * np.eye(w.d), A64.T @ b / w.n)
+    xr = np.zeros(w.d, np.float32)
+    avg = np.zeros(w.d)
+    for ep in range(40):
+        xr = oracle.sgd_epoch(c1, c2, L, b, bits, xr, batch, 0.2 / (1 + ep), l2=c)
+        if ep >= 20:
+            avg += xr / 20
+    assert np.linalg.norm(avg - x_ridge) / np.linalg.norm(x_ridge) < 0.02
+
+
 # ------------------------------------------------------------------ epoch: convergence
 def test_converges_to_least_squares_solution_and_naive_does_not():
     """Double-sampled SGD with a diminishing step reaches (A^T A)^-1 A^T b (Sec. 5.1);
