@@ -98,6 +98,14 @@ int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, int64_t d, 
                    int64_t row0, int64_t n_total, const float *levels_dev, int bits, uint64_t seed,
                    uint32_t epoch, void *packed1_dev, void *packed2_dev);
 
+/* The same two copies in the other layout each, for the symmetrised estimator: packed1s_dev gets
+ * copy 2 in the layout of packed1, packed2s_dev copy 1 in the layout of packed2.  The draws are
+ * those of zipml_quantize with the same (seed, epoch): zipml_unpack_codes(packed1s, copy = 1)
+ * returns the codes of copy 2, and (packed2s, copy = 2) those of copy 1. */
+int zipml_quantize_swapped(void *stream, const float *A_dev, int64_t n_rows, int64_t d, int64_t lda,
+                           int64_t row0, int64_t n_total, const float *levels_dev, int bits,
+                           uint64_t seed, uint32_t epoch, void *packed1s_dev, void *packed2s_dev);
+
 /* One epoch of double-sampled minibatch SGD on F(x) = 1/(2n) sum_i (a_i^T x - b_i)^2
  * (Sec. 2 and eq. (5); the minibatch gradient is the mean over `batch` consecutive samples; the
  * n / batch steps run in storage order).  x_dev[d] is the fp32 master model, updated in place:
@@ -133,6 +141,19 @@ int zipml_sgd_epoch_l2(void *stream, const void *packed1_dev, const void *packed
                        const float *levels_dev, const float *b_dev, int64_t n, int64_t d, int bits,
                        float *x_dev, int64_t batch, float lr, float l2, int flags,
                        void *workspace_dev, size_t workspace_bytes);
+
+/* The same epoch with the symmetrised estimator (Supp. A.4: lower variance at no extra
+ * randomness; the form the authors report running):
+ *   g = 1/2 mean_i [ Q1(a_i) (Q2(a_i)^T x - b_i) + Q2(a_i) (Q1(a_i)^T x - b_i) ],
+ * which needs both copies in both layouts: packed1s_dev / packed2s_dev from
+ * zipml_quantize_swapped.  fp32 model; 2-, 4- or 8-bit evenly spaced levels; batch a multiple
+ * of 64; more than 256 features (otherwise ZIPML_EUNSUPPORTED, through the status word if it is
+ * the level tables that do not qualify).  l2 as in zipml_sgd_epoch_l2 (0 for plain least squares). */
+int zipml_sgd_epoch_avg(void *stream, const void *packed1_dev, const void *packed2_dev,
+                        const void *packed1s_dev, const void *packed2s_dev, const float *levels_dev,
+                        const float *b_dev, int64_t n, int64_t d, int bits, float *x_dev,
+                        int64_t batch, float lr, float l2, int flags, void *workspace_dev,
+                        size_t workspace_bytes);
 
 /* Waits for the stream and returns the status word the last zipml_sgd_epoch / zipml_debug_step
  * left in this workspace: ZIPML_OK or ZIPML_ETIMEOUT. */

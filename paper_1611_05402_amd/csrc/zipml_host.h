@@ -47,7 +47,8 @@ struct Workspace {
     static constexpr size_t kNorm = 8192;         // norm exchange: 2 x 3 x 512 doubles (24 KiB)
     static constexpr size_t kAcc = 8192 + 24576;  // 4 exchange buffers of acc_words 64-bit words
     static constexpr int kAccBuffers = 4;
-    static size_t acc_words(int64_t batch) { return (size_t)round_up(batch + 64, 64); }
+    // room for the sums of both code pairs of the symmetrised estimator and the side words
+    static size_t acc_words(int64_t batch) { return (size_t)round_up(2 * batch + 64, 64); }
     static size_t sgd_bytes(int64_t batch) { return kAcc + kAccBuffers * acc_words(batch) * 8; }
 };
 

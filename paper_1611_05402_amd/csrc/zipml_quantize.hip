@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
     const float *__restrict__ A, int64_t n_rows, int64_t d, int64_t lda, int64_t row0,
     int64_t nb64, int64_t n32, int64_t d32, const float *__restrict__ levels, uint64_t seed,
     uint32_t epoch, uint32_t *__restrict__ p1, uint32_t *__restrict__ p2, int vec_ok,
-    int64_t groups_per_block)
+    int64_t groups_per_block, int swapped)
 {
     extern __shared__ __align__(16) float tab[];          // [kTileCols][K]
     __shared__ uint32_t c1w[32 * kLdsRow];
@@ -183,8 +183,9 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
             uint32_t w1 = 0, w2 = 0;
             if (i < n_rows && col < d) {
                 const uint64_t row = (uint64_t)(row0 + i);
-                const Philox4 r1 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 1u);
-                const Philox4 r2 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), 2u);
+                // swapped: the feature-major array gets copy 2 (stream 2), the sample-major copy 1
+                const Philox4 r1 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), swapped ? 2u : 1u);
+                const Philox4 r2 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), swapped ? 1u : 2u);
                 int l[4];
                 float frac[4];
                 bracket4(cols, live_col, K, vcur[pass], l, frac);
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
 template <int BITS>
 static int launch_quantize(hipStream_t s, const float *A, int64_t n_rows, int64_t d, int64_t lda,
                            int64_t row0, const Layout &lay, const float *levels, uint64_t seed,
-                           uint32_t epoch, uint32_t *p1, uint32_t *p2)
+                           uint32_t epoch, uint32_t *p1, uint32_t *p2, int swapped)
 {
     const int vec_ok = (lda % 4 == 0) && aligned16(A);
     const int64_t col_blocks = (lay.d + kTileCols - 1) / kTileCols;
@@ -299,7 +300,8 @@ static int launch_quantize(hipStream_t s, const float *A, int64_t n_rows, int64_
         return ZIPML_ELAUNCH;
     dim3 grid((unsigned)row_blocks, (unsigned)col_blocks);
     hipLaunchKernelGGL(k_quantize_pack<BITS>, grid, dim3(256), shmem, s, A, n_rows, d, lda, row0,
-                       lay.nb64, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok, per_block);
+                       lay.nb64, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok, per_block,
+                       swapped);
     return hip_check(hipGetLastError());
 }
 
@@ -331,10 +333,10 @@ extern "C" size_t zipml_packed_bytes(int64_t n, int64_t d, int bits)
     return make_layout(n, d, bits).bytes();
 }
 
-extern "C" int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, int64_t d,
-                              int64_t lda, int64_t row0, int64_t n_total,
-                              const float *levels_dev, int bits, uint64_t seed, uint32_t epoch,
-                              void *packed1_dev, void *packed2_dev)
+static int quantize_entry(void *stream, const float *A_dev, int64_t n_rows, int64_t d, int64_t lda,
+                          int64_t row0, int64_t n_total, const float *levels_dev, int bits,
+                          uint64_t seed, uint32_t epoch, void *packed1_dev, void *packed2_dev,
+                          int swapped)
 {
     if (!A_dev || !levels_dev || !packed1_dev || !packed2_dev) return ZIPML_EINVAL;
     if (n_rows <= 0 || d <= 0 || lda < d || n_total <= 0 || !valid_bits(bits)) return ZIPML_EINVAL;
@@ -347,9 +349,27 @@ extern "C" int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, 
     const Layout lay = make_layout(n_total, d, bits);
     hipStream_t s = entry_stream(stream);
     uint32_t *p1 = (uint32_t *)packed1_dev, *p2 = (uint32_t *)packed2_dev;
-#define CALL(B) launch_quantize<B>(s, A_dev, n_rows, d, lda, row0, lay, levels_dev, seed, epoch, p1, p2)
+#define CALL(B) launch_quantize<B>(s, A_dev, n_rows, d, lda, row0, lay, levels_dev, seed, epoch, p1, p2, swapped)
     ZIPML_DISPATCH_BITS(bits, CALL)
 #undef CALL
+}
+
+extern "C" int zipml_quantize(void *stream, const float *A_dev, int64_t n_rows, int64_t d,
+                              int64_t lda, int64_t row0, int64_t n_total,
+                              const float *levels_dev, int bits, uint64_t seed, uint32_t epoch,
+                              void *packed1_dev, void *packed2_dev)
+{
+    return quantize_entry(stream, A_dev, n_rows, d, lda, row0, n_total, levels_dev, bits, seed, epoch,
+                          packed1_dev, packed2_dev, 0);
+}
+
+extern "C" int zipml_quantize_swapped(void *stream, const float *A_dev, int64_t n_rows, int64_t d,
+                                      int64_t lda, int64_t row0, int64_t n_total,
+                                      const float *levels_dev, int bits, uint64_t seed,
+                                      uint32_t epoch, void *packed1s_dev, void *packed2s_dev)
+{
+    return quantize_entry(stream, A_dev, n_rows, d, lda, row0, n_total, levels_dev, bits, seed, epoch,
+                          packed1s_dev, packed2s_dev, 1);
 }
 
 extern "C" int zipml_unpack_codes(void *stream, const void *packed_dev, int copy, int64_t n,

@@ -72,6 +72,8 @@ enum Mode { kAffine = 0, kTable = 1, kInt = 2 };
 
 struct SgdArgs {
     const uint32_t *p1, *p2;
+    const uint32_t *p1s, *p2s;   // symmetrised estimator: copy 2 feature-major, copy 1 sample-major
+    int avg;                     // 1: symmetrised estimator (matrix-core loop only)
     const float *levels;
     const uint16_t *grid;
     const float *b;
@@ -764,7 +766,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     L.red = (double *)carve(512 * 8);
     L.wsum = (float *)carve(3 * kWaves * 4);
     L.isum = (int *)carve(kWaves * 4);
-    L.mf = (unsigned char *)carve(a.mfma ? mfma_lds_bytes(a.GQ, B) : 0);
+    L.mf = (unsigned char *)carve(a.mfma ? mfma_lds_bytes(a.GQ, B, a.avg ? 2 : 1) : 0);
 
     // ---- one-time set-up: level slice, model slice
     const float *Lg = a.levels + (size_t)j0 * K;
@@ -811,15 +813,22 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     }
 
     constexpr bool kMfmaBits = BITS == 2 || BITS == 4 || BITS == 8;
-    if (a.chunks > 1 && !(!INT && FAST && kMfmaBits && affine_all && a.mfma)) {
-        // a minibatch that is taken in chunks exists on the matrix-core loop only
+    if ((a.chunks > 1 || a.avg) && !(!INT && FAST && kMfmaBits && affine_all && a.mfma)) {
+        // minibatches taken in chunks and the symmetrised estimator exist on the matrix-core loop only
         if (w == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
         return;
     }
     if constexpr (!INT && FAST && kMfmaBits) {
         if (affine_all && a.mfma) {
-            if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1>(a, L, L.mf);
-            else sgd_steps_mfma<BITS, UPT, 2>(a, L, L.mf);
+            if (a.avg) {
+                if constexpr (UPT <= 2) {      // the plan keeps the symmetrised estimator to these
+                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2>(a, L, L.mf);
+                    else sgd_steps_mfma<BITS, UPT, 2, 2>(a, L, L.mf);
+                }
+            } else {
+                if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1>(a, L, L.mf);
+                else sgd_steps_mfma<BITS, UPT, 2, 1>(a, L, L.mf);
+            }
         } else if (affine) {
             sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
         } else {
@@ -928,7 +937,7 @@ static size_t up16(size_t v) { return (v + 15) & ~(size_t)15; }
 
 // LDS needed for GQ feature groups per workgroup; 0 if it does not fit.
 static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool solo, bool mfma,
-                       int lds_limit, int &lds_levels)
+                       int pairs, int lds_limit, int &lds_levels)
 {
     const int K = 1 << bits, CW = 32 * GQ;
     const int nrg = batch >= 32 ? (int)(batch / 32) : 1;
@@ -940,7 +949,7 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool sol
                          (GQ > 1 ? up16((size_t)GQ * batch * 4) : 0) +
                          up16((size_t)kMaxUpt * kThreads * 4) + up16(512 * 8) +
                          up16(3 * kWaves * 4) + up16(kWaves * 4) +
-                         (mfma ? up16(mfma_lds_bytes(GQ, batch)) : 0);
+                         (mfma ? up16(mfma_lds_bytes(GQ, batch, pairs)) : 0);
     return total <= (size_t)lds_limit ? total : 0;
 }
 
@@ -948,7 +957,8 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool sol
 // latency grows with the number of workgroups, so small steps want few, fat workgroups; the
 // registers that hold a thread's units (at most kMaxUpt per pass) and the number of compute units
 // bound the choice from both sides.
-static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool fp32_model, Plan &p)
+static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool fp32_model, int pairs,
+                     Plan &p)
 {
     int cus = 0, lds = 0;
     if (int rc = device_limits(cus, lds)) return rc;
@@ -961,14 +971,15 @@ static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool 
     for (int GQ = 1; GQ <= 8; GQ <<= 1) {
         const int64_t W = (d32 + GQ - 1) / GQ;
         if (W > cus || W > 512) continue;
-        if (batch * GQ > (int64_t)kMaxUpt * kThreads) break;   // units per thread
+        // units per thread; two code pairs take twice the registers
+        if (batch * GQ > (int64_t)(pairs == 2 ? 2 : kMaxUpt) * kThreads) break;
         int ll = 0;
         // the matrix-core step loop: 2/4/8-bit codes, fp32 model, whole 64-sample blocks, more
         // than one workgroup, at most 8 feature tiles of 16 (whether the levels are evenly
         // spaced is found out by the kernel)
         const bool mfma = fp32_model && (bits == 2 || bits == 4 || bits == 8) && batch % 64 == 0 &&
                           W > 1 && GQ <= 4 && !getenv("ZIPML_NO_MFMA");
-        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, mfma, lds, ll);
+        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, mfma, pairs, lds, ll);
         if (!sh) break;
         best = GQ;
         p.GQ = GQ; p.W = (int)W; p.lds_levels = ll; p.shmem = sh; p.mfma = mfma ? 1 : 0;
@@ -1047,7 +1058,7 @@ static int launch_sgd_mode(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwi
 }
 
 static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_dev,
-                   const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
+                   const void *packed1s_dev, const void *packed2s_dev, const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
                    float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d, int bits,
                    float *x_dev, int64_t batch, float lr, float l2, int grad_bits, int model_bits,
                    uint64_t seed, uint32_t epoch, int flags, int64_t step0, int64_t nsteps,
@@ -1067,6 +1078,15 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     if (grad_bits > 0 && model_bits == 0) return ZIPML_EUNSUPPORTED;
     if (!(l2 >= 0.0f)) return ZIPML_EINVAL;
     if (l2 != 0.0f && model_bits > 0) return ZIPML_EUNSUPPORTED;   // the c*x term is not quantised here
+    const bool avg = packed1s_dev != nullptr || packed2s_dev != nullptr;
+    if (avg) {
+        // symmetrised estimator: both extra arrays, fp32 model, production launch, matrix-core loop
+        if (!packed1s_dev || !packed2s_dev) return ZIPML_EINVAL;
+        if (!aligned16(packed1s_dev) || !aligned16(packed2s_dev)) return ZIPML_EALIGN;
+        if (model_bits > 0 || (flags & ZIPML_SGD_STEPWISE) || dbg_m || dbg_acc || dbg_r || dbg_g || dbg_gq ||
+            !(bits == 2 || bits == 4 || bits == 8) || batch % 64 != 0)
+            return ZIPML_EUNSUPPORTED;
+    }
     if (model_bits > 0) {
         if (!grid_idx_dev || grid_max < (1 << bits) - 1 || grid_max > 65535) return ZIPML_EINVAL;
         const int64_t s_m = ((int64_t)1 << (model_bits - 1)) - 1;
@@ -1085,7 +1105,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     const bool ident = model_bits > 0 && grid_max == (1 << bits) - 1;
     Plan p{};
     int64_t chunks = 1, micro = batch;
-    int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, model_bits == 0, p);
+    const int pairs = avg ? 2 : 1;
+    int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, model_bits == 0, pairs, p);
     const bool stepwise = (flags & ZIPML_SGD_STEPWISE) != 0;
     const bool debug = dbg_m || dbg_acc || dbg_r || dbg_g || dbg_gq;
     if (rc == ZIPML_EUNSUPPORTED && model_bits == 0 && !stepwise && !debug && batch % 64 == 0) {
@@ -1095,7 +1116,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
         for (int64_t c = 2; c <= batch / 64; ++c) {
             if (batch % c != 0 || (batch / c) % 64 != 0) continue;
             Plan q{};
-            if (make_plan(lay.d32, bits, batch / c, false, true, q) == ZIPML_OK && q.mfma) {
+            if (make_plan(lay.d32, bits, batch / c, false, true, pairs, q) == ZIPML_OK && q.mfma) {
                 p = q;
                 chunks = c;
                 micro = batch / c;
@@ -1105,11 +1126,15 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
         }
     }
     if (rc) return rc;
+    if (avg && !p.mfma) return ZIPML_EUNSUPPORTED;   // e.g. a problem that fits one workgroup
 
     unsigned char *ws = (unsigned char *)workspace_dev;
     SgdArgs a{};
     a.p1 = (const uint32_t *)packed1_dev;
     a.p2 = (const uint32_t *)packed2_dev;
+    a.p1s = (const uint32_t *)packed1s_dev;
+    a.p2s = (const uint32_t *)packed2s_dev;
+    a.avg = avg ? 1 : 0;
     a.levels = levels_dev;
     a.grid = grid_idx_dev;
     a.b = b_dev;
@@ -1175,9 +1200,9 @@ extern "C" int zipml_sgd_epoch(void *stream, const void *packed1_dev, const void
                                size_t workspace_bytes)
 {
     const int64_t steps = (batch > 0 && n > 0 && n % batch == 0) ? n / batch : 0;
-    return run_sgd(stream, packed1_dev, packed2_dev, levels_dev, grid_idx_dev, grid_lo, grid_step,
-                   grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits, model_bits, seed,
-                   epoch, flags, 0, steps, nullptr, nullptr, nullptr, nullptr, nullptr,
+    return run_sgd(stream, packed1_dev, packed2_dev, nullptr, nullptr, levels_dev, grid_idx_dev,
+                   grid_lo, grid_step, grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits,
+                   model_bits, seed, epoch, flags, 0, steps, nullptr, nullptr, nullptr, nullptr, nullptr,
                    workspace_dev, workspace_bytes);
 }
 
@@ -1187,9 +1212,22 @@ extern "C" int zipml_sgd_epoch_l2(void *stream, const void *packed1_dev, const v
                                   int flags, void *workspace_dev, size_t workspace_bytes)
 {
     const int64_t steps = (batch > 0 && n > 0 && n % batch == 0) ? n / batch : 0;
-    return run_sgd(stream, packed1_dev, packed2_dev, levels_dev, nullptr, 0.0f, 0.0f, 0, b_dev, n, d,
-                   bits, x_dev, batch, lr, l2, 0, 0, 0, 0, flags, 0, steps, nullptr, nullptr, nullptr,
-                   nullptr, nullptr, workspace_dev, workspace_bytes);
+    return run_sgd(stream, packed1_dev, packed2_dev, nullptr, nullptr, levels_dev, nullptr, 0.0f, 0.0f,
+                   0, b_dev, n, d, bits, x_dev, batch, lr, l2, 0, 0, 0, 0, flags, 0, steps, nullptr,
+                   nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes);
+}
+
+extern "C" int zipml_sgd_epoch_avg(void *stream, const void *packed1_dev, const void *packed2_dev,
+                                   const void *packed1s_dev, const void *packed2s_dev,
+                                   const float *levels_dev, const float *b_dev, int64_t n, int64_t d,
+                                   int bits, float *x_dev, int64_t batch, float lr, float l2,
+                                   int flags, void *workspace_dev, size_t workspace_bytes)
+{
+    if (!packed1s_dev || !packed2s_dev) return ZIPML_EINVAL;
+    const int64_t steps = (batch > 0 && n > 0 && n % batch == 0) ? n / batch : 0;
+    return run_sgd(stream, packed1_dev, packed2_dev, packed1s_dev, packed2s_dev, levels_dev, nullptr,
+                   0.0f, 0.0f, 0, b_dev, n, d, bits, x_dev, batch, lr, l2, 0, 0, 0, 0, flags, 0, steps,
+                   nullptr, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes);
 }
 
 extern "C" int zipml_debug_step(void *stream, const void *packed1_dev, const void *packed2_dev,
@@ -1202,9 +1240,9 @@ extern "C" int zipml_debug_step(void *stream, const void *packed1_dev, const voi
                                 int32_t *grad_codes_dev, void *workspace_dev,
                                 size_t workspace_bytes)
 {
-    return run_sgd(stream, packed1_dev, packed2_dev, levels_dev, grid_idx_dev, grid_lo, grid_step,
-                   grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits, model_bits, seed,
-                   epoch, flags, step, 1, model_codes_dev, acc_dev, r_dev, g_dev, grad_codes_dev,
+    return run_sgd(stream, packed1_dev, packed2_dev, nullptr, nullptr, levels_dev, grid_idx_dev,
+                   grid_lo, grid_step, grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits,
+                   model_bits, seed, epoch, flags, step, 1, model_codes_dev, acc_dev, r_dev, g_dev, grad_codes_dev,
                    workspace_dev, workspace_bytes);
 }
 

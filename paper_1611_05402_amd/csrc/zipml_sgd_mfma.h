@@ -114,16 +114,20 @@ __device__ __forceinline__ int scale_exponent(float v, int bits)
 }
 
 // LDS bytes of the matrix-core path for a plan.
-__host__ __device__ inline size_t mfma_lds_bytes(int GQ, int64_t batch)
+__host__ __device__ inline size_t mfma_lds_bytes(int GQ, int64_t batch, int pairs)
 {
     const size_t KB = (size_t)(GQ + 1) / 2;
-    return KB * 256 + (size_t)(batch / 64) * 256 + (size_t)4 * 32 * GQ * 8 + 512;
+    return KB * 256 + (size_t)pairs * (size_t)(batch / 64) * 256 + (size_t)4 * 32 * GQ * 8 + 512;
 }
 
 constexpr int kRefresh = 16;   // steps between exact refreshes of the magnitude bounds
 
 // KB: 64-feature blocks per workgroup (1: GQ <= 2, 2: GQ == 4).
-template <int BITS, int UPT, int KB>
+// NC: 1 = the estimator of eq. (5), g = mean_i Q1(a_i) (Q2(a_i)^T x - b_i);
+//     2 = its symmetrised form (Supp. A.4), 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)]: a
+//     second pair of packed arrays holds copy 1 sample-major and copy 2 feature-major, both
+//     pairs go through the same two passes at the same model, with one exchange for both.
+template <int BITS, int UPT, int KB, int NC>
 __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, unsigned char *mf)
 {
     constexpr int HW = BITS / 2;                       // packed dwords per lane operand
@@ -132,7 +136,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     constexpr int kNG = UPT == 1 ? 4 : 2 * UPT;        // gradient instructions per wave, at most
     // Small steps hold two steps of packed data in registers (the loads need more than a step to
     // arrive); large steps are long enough for loads issued one step ahead, and need the registers.
-    constexpr bool kDouble = UPT <= 2;
+    constexpr bool kDouble = UPT <= 2 && NC == 1;
     constexpr int kT2 = kDouble ? kTiles : 1, kG2 = kDouble ? kNG : 1;
     constexpr int kBpt = UPT;                          // samples per thread in the residual phase
     constexpr float kOff = BITS == 8 ? 128.0f : 0.0f;
@@ -155,11 +159,13 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     // the model is updated after the last one.  u counts chunks through the epoch.
     const int C = a.chunks;
     const int64_t u_begin = a.step0 * C, u_end = (a.step0 + a.nsteps) * C;
+    const int nwords = NC * B + 2;                      // exchange words of a chunk: sums, 2 side words
+    const uint32_t *const p2base[2] = {a.p2, a.p2s}, *const p1base[2] = {a.p1, a.p1s};
 
     // ---- LDS of this path
     int8_t *const ydig = (int8_t *)mf;                              // [KB][4 digits][4 q][16]
-    int8_t *const rdig = ydig + KB * 256;                           // [NKS][4 digits][4 q][16]
-    long long *const gpart = (long long *)(rdig + (size_t)NKS * 256);   // [4][CW]
+    int8_t *const rdig = ydig + KB * 256;                           // [NC][NKS][4 digits][4 q][16]
+    long long *const gpart = (long long *)(rdig + (size_t)NC * NKS * 256);   // [4][CW]
     unsigned char *misc = (unsigned char *)(gpart + 4 * CW);
     float *const cqs = (float *)misc;                               // [8] per tile: sum_j mid_j x_j
     float *const bws = (float *)(misc + 32);                        // [8] sum_j maxabs(L_j)|x_j|
@@ -168,7 +174,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     float *const wsum = (float *)(misc + 128);                      // [8] per wave sum_i r_i
     float *const side = (float *)(misc + 160);                      // [2] decoded side words
 
-    for (int e = tid; e < KB * 256 + NKS * 256; e += kThreads) ydig[e] = 0;
+    for (int e = tid; e < KB * 256 + NC * NKS * 256; e += kThreads) ydig[e] = 0;
     if (tid < 8) { cqs[tid] = 0.0f; bws[tid] = 0.0f; ymx[tid] = 0; wmax[tid] = 0.0f; wsum[tid] = 0.0f; }
     lds_barrier();
 
@@ -179,7 +185,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             if (w == 0 && wave == kWaves - 1) {
                 // clear the exchange words of step t+2 (see zipml_sgd.hip for why now)
                 uint64_t *nxt = a.acc + (size_t)((u + 2) & 3) * a.acc_words;
-                for (int i = lane; i < B + 2; i += kWave) store_dev(nxt + i, (uint64_t)0);
+                for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
                 vm_wait_all();
             }
             lds_barrier();
@@ -237,8 +243,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 
     // ---- packed data held in registers; the addresses advance by a fixed stride per step
     const int64_t step_dwords = (int64_t)B * BITS;      // both copies: B samples x BITS dwords per group
-    uint32_t c2cur[kTiles][KB][HW], c2nxt[kT2][KB][HW], c1[kNG][HW], c1nxt[kG2][HW];
-    const uint32_t *p2ptr[kTiles][KB], *p1ptr[kNG];
+    uint32_t c2cur[NC][kTiles][KB][HW], c2nxt[kT2][KB][HW], c1[NC][kNG][HW], c1nxt[kG2][HW];
+    const uint32_t *p2ptr[NC][kTiles][KB], *p1ptr[NC][kNG];
     bool p2ok[kTiles][KB], p1ok[kNG];
     float bnext[kBpt], bfut[kBpt];
 #pragma unroll
@@ -250,7 +256,10 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             p2ok[ti][kb] = tile < ntile && gq < ngroups;
             const int64_t row = u_begin * B + 16 * tile + n16;
             const int64_t g = (int64_t)w * GQ + gq;
-            p2ptr[ti][kb] = p2ok[ti][kb] ? a.p2 + (g * a.nb64 * 64 + row) * BITS + (q4 & 1) * HW : a.p2;
+#pragma unroll
+            for (int cc = 0; cc < NC; ++cc)
+                p2ptr[cc][ti][kb] = p2ok[ti][kb] ? p2base[cc] + (g * a.nb64 * 64 + row) * BITS + (q4 & 1) * HW
+                                                 : p2base[cc];
         }
     }
 #pragma unroll
@@ -260,27 +269,30 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         p1ok[m] = ks < NKS && gq < ngroups;
         const int64_t g = (int64_t)w * GQ + gq;
         const int64_t rg = (u_begin * B) / 32 + 2 * ks + (q4 >> 1);
-        p1ptr[m] = p1ok[m] ? a.p1 + ((g * a.n32 + rg) * 32 + cin) * BITS + (q4 & 1) * HW : a.p1;
+#pragma unroll
+        for (int cc = 0; cc < NC; ++cc)
+            p1ptr[cc][m] = p1ok[m] ? p1base[cc] + ((g * a.n32 + rg) * 32 + cin) * BITS + (q4 & 1) * HW
+                                   : p1base[cc];
     }
     // loads of the step `ahead` steps after the one the pointers stand at
-    auto load_dot = [&](int ahead, auto &dst) {
+    auto load_dot = [&](int cc, int ahead, auto &dst) {
 #pragma unroll
         for (int ti = 0; ti < kTiles; ++ti)
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
                 const uint32_t *q = static_cast<const uint32_t *>(
-                    __builtin_assume_aligned(p2ptr[ti][kb] + ahead * step_dwords, 4 * HW));
+                    __builtin_assume_aligned(p2ptr[cc][ti][kb] + ahead * step_dwords, 4 * HW));
                 if (p2ok[ti][kb]) {
 #pragma unroll
                     for (int k = 0; k < HW; ++k) dst[ti][kb][k] = q[k];
                 }
             }
     };
-    auto load_grad = [&](int ahead, auto &dst) {
+    auto load_grad = [&](int cc, int ahead, auto &dst) {
 #pragma unroll
         for (int m = 0; m < kNG; ++m) {
             const uint32_t *q = static_cast<const uint32_t *>(
-                __builtin_assume_aligned(p1ptr[m] + ahead * step_dwords, 4 * HW));
+                __builtin_assume_aligned(p1ptr[cc][m] + ahead * step_dwords, 4 * HW));
             if (p1ok[m]) {
 #pragma unroll
                 for (int k = 0; k < HW; ++k) dst[m][k] = q[k];
@@ -301,23 +313,28 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int k = 0; k < HW; ++k) {
-                c2cur[ti][kb][k] = 0u;
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) c2cur[cc][ti][kb][k] = 0u;
                 if constexpr (kDouble) c2nxt[ti][kb][k] = 0u;
             }
 #pragma unroll
     for (int m = 0; m < kNG; ++m)
 #pragma unroll
         for (int k = 0; k < HW; ++k) {
-            c1[m][k] = 0u;
+#pragma unroll
+            for (int cc = 0; cc < NC; ++cc) c1[cc][m][k] = 0u;
             if constexpr (kDouble) c1nxt[m][k] = 0u;
         }
 #pragma unroll
     for (int k = 0; k < kBpt; ++k) bnext[k] = bfut[k] = 0.0f;
-    load_dot(0, c2cur);
-    if constexpr (kDouble) {
-        if (u_begin + 1 < u_end) load_dot(1, c2nxt);
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) {
+        load_dot(cc, 0, c2cur[cc]);
+        load_grad(cc, 0, c1[cc]);
     }
-    load_grad(0, c1);
+    if constexpr (kDouble) {
+        if (u_begin + 1 < u_end) load_dot(0, 1, c2nxt);
+    }
     load_labels(u_begin, bnext);
 
     // where the digits of this thread's residuals go: sample i -> k-step i/64, q, byte
@@ -366,19 +383,24 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             for (int kb = 0; kb < KB; ++kb)
                 afull[kb] = *reinterpret_cast<const v4i *>(ydig + (kb * 4 + (n16 & 3)) * 64 + q4 * 16);
 #pragma unroll
-            for (int gi = 0; gi < kSlots; ++gi) {
-                if (wave + nw * 4 * gi < ntile) {
-                    v4i c = {0, 0, 0, 0};
+            for (int cc = 0; cc < NC; ++cc) {
 #pragma unroll
-                    for (int sl = 0; sl < 4; ++sl) {
+                for (int gi = 0; gi < kSlots; ++gi) {
+                    if (wave + nw * 4 * gi < ntile) {
+                        v4i c = {0, 0, 0, 0};
 #pragma unroll
-                        for (int kb = 0; kb < KB; ++kb) {
-                            const v4i as = (n16 >> 2) == sl ? afull[kb] : zero;
-                            c = __builtin_amdgcn_mfma_i32_16x16x64_i8(as, expand_codes<BITS>(c2cur[4 * gi + sl][kb]), c, 0, 0, 0);
+                        for (int sl = 0; sl < 4; ++sl) {
+#pragma unroll
+                            for (int kb = 0; kb < KB; ++kb) {
+                                const v4i as = (n16 >> 2) == sl ? afull[kb] : zero;
+                                c = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                    as, expand_codes<BITS>(c2cur[cc][4 * gi + sl][kb]), c, 0, 0, 0);
+                            }
                         }
+                        const int tile = wave + nw * (4 * gi + q4);
+                        if (tile < ntile)
+                            add_dev(acc + cc * B + 16 * tile + n16, pack_int(combine_digits(c) + kconst));
                     }
-                    const int tile = wave + nw * (4 * gi + q4);
-                    if (tile < ntile) add_dev(acc + 16 * tile + n16, pack_int(combine_digits(c) + kconst));
                 }
             }
             if (side_step && wave == 0 && lane < 2) {
@@ -390,7 +412,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     mx = ymx[f] > mx ? ymx[f] : mx;
                 }
                 const long long v = lane == 0 ? __double2ll_ru(ldexp((double)bw, ky)) + 1 : (long long)mx;
-                add_dev(acc + B + lane, pack_int(v));
+                add_dev(acc + NC * B + lane, pack_int(v));
             }
         }
         // The last wave of workgroup 0 clears the exchange words of step t+2 (see zipml_sgd.hip
@@ -398,7 +420,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         // around, one of them does it instead.
         if (nw == kWaves && w == 0 && wave == kWaves - 1) {
             uint64_t *nxt = a.acc + (size_t)((u + 2) & 3) * a.acc_words;
-            for (int i = lane; i < B + 2; i += kWave) store_dev(nxt + i, (uint64_t)0);
+            for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
             if (!(tid < B)) vm_wait_all();
         }
         // Rotate copy 2 and request what later steps need, now: the loads travel while the
@@ -412,38 +434,46 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             for (int kb = 0; kb < KB; ++kb) {
                 if constexpr (kDouble) {
 #pragma unroll
-                    for (int k = 0; k < HW; ++k) c2cur[ti][kb][k] = c2nxt[ti][kb][k];
+                    for (int k = 0; k < HW; ++k) c2cur[0][ti][kb][k] = c2nxt[ti][kb][k];
                 }
-                p2ptr[ti][kb] += step_dwords;          // now stands at step t+1
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) p2ptr[cc][ti][kb] += step_dwords;   // now at step t+1
             }
         if constexpr (kDouble) {
-            if (u + 2 < u_end) load_dot(1, c2nxt);
-            if (u + 1 < u_end) load_grad(1, c1nxt);
+            if (u + 2 < u_end) load_dot(0, 1, c2nxt);
+            if (u + 1 < u_end) load_grad(0, 1, c1nxt);
         } else {
-            if (u + 1 < u_end) load_dot(0, c2cur);
+            if (u + 1 < u_end) {
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) load_dot(cc, 0, c2cur[cc]);
+            }
         }
         if (u + 1 < u_end) load_labels(u + 1, bfut);
         ZIPML_TICK(1);
 
         // ============ residuals: poll the sums of this thread's samples
-        float r[kBpt];
+        float r[NC][kBpt];
         float rmax = 0.0f, rsum = 0.0f;
         {
-            uint64_t raw[kBpt], rawx = 0;
+            uint64_t raw[NC][kBpt], rawx = 0;
             const bool want_side = side_step && wave == 0;     // wave 0 also fetches the side words
             uint32_t spins = 0;
             if (tid < B || want_side) {
 #pragma unroll 1
                 for (;;) {
 #pragma unroll
-                    for (int q = 0; q < kBpt; ++q) {
-                        const int i = tid + q * nthr;
-                        raw[q] = load_dev(acc + (i < B ? i : B - 1));
-                    }
-                    if (want_side) rawx = load_dev(acc + B + (lane & 1));
+                    for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+                        for (int q = 0; q < kBpt; ++q) {
+                            const int i = tid + q * nthr;
+                            raw[cc][q] = load_dev(acc + cc * B + (i < B ? i : B - 1));
+                        }
+                    if (want_side) rawx = load_dev(acc + NC * B + (lane & 1));
                     bool all = !want_side || (int)(rawx >> kCountShift) == W;
 #pragma unroll
-                    for (int q = 0; q < kBpt; ++q) all = all && (int)(raw[q] >> kCountShift) == W;
+                    for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+                        for (int q = 0; q < kBpt; ++q) all = all && (int)(raw[cc][q] >> kCountShift) == W;
                     if (all || dead) break;
                     if (++spins > a.spin_limit) {
                         store_dev(a.status, (int)ZIPML_ETIMEOUT);
@@ -455,11 +485,14 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 #pragma unroll
             for (int q = 0; q < kBpt; ++q) {
                 const int i = tid + q * nthr;
-                r[q] = 0.0f;
-                if (i < B) {
-                    r[q] = fixed_to_float(unpack_sum(raw[q], W), ky) - bnext[q];
-                    rmax = fmaxf(rmax, fabsf(r[q]));
-                    rsum += r[q];
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) {
+                    r[cc][q] = 0.0f;
+                    if (i < B) {
+                        r[cc][q] = fixed_to_float(unpack_sum(raw[cc][q], W), ky) - bnext[q];
+                        rmax = fmaxf(rmax, fabsf(r[cc][q]));
+                        rsum += r[cc][q];
+                    }
                 }
                 bnext[q] = bfut[q];
             }
@@ -490,10 +523,14 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         }
         // residual digits
 #pragma unroll
-        for (int q = 0; q < kBpt; ++q) {
-            const int i = tid + q * nthr;
-            if (i < B) store_digits(rdig + r_pos[q], signed_digits(__float2int_rn(ldexpf(r[q], kr))));
-        }
+        for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+            for (int q = 0; q < kBpt; ++q) {
+                const int i = tid + q * nthr;
+                if (i < B)
+                    store_digits(rdig + cc * NKS * 256 + r_pos[q],
+                                 signed_digits(__float2int_rn(ldexpf(r[cc][q], kr))));
+            }
         lds_barrier();
         ZIPML_TICK(8);
 
@@ -501,24 +538,31 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         {
             v4i c = {0, 0, 0, 0};
 #pragma unroll
-            for (int m = 0; m < kNG; ++m) {
-                const int ks = g_kh + KSS * m;
-                if (ks < NKS) {
-                    v4i ad = {0, 0, 0, 0};
-                    if (n16 < 4) ad = *reinterpret_cast<const v4i *>(rdig + (ks * 4 + n16) * 64 + q4 * 16);
-                    c = __builtin_amdgcn_mfma_i32_16x16x64_i8(ad, expand_codes<BITS>(c1[m]), c, 0, 0, 0);
+            for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+                for (int m = 0; m < kNG; ++m) {
+                    const int ks = g_kh + KSS * m;
+                    if (ks < NKS) {
+                        v4i ad = {0, 0, 0, 0};
+                        if (n16 < 4)
+                            ad = *reinterpret_cast<const v4i *>(rdig + ((cc * NKS + ks) * 4 + n16) * 64 + q4 * 16);
+                        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(ad, expand_codes<BITS>(c1[cc][m]), c, 0, 0, 0);
+                    }
                 }
-            }
 #pragma unroll
             for (int m = 0; m < kNG; ++m) {
-                p1ptr[m] += step_dwords;
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) p1ptr[cc][m] += step_dwords;
                 if constexpr (kDouble) {
 #pragma unroll
-                    for (int k = 0; k < HW; ++k) c1[m][k] = c1nxt[m][k];
+                    for (int k = 0; k < HW; ++k) c1[0][m][k] = c1nxt[m][k];
                 }
             }
             if constexpr (!kDouble) {
-                if (u + 1 < u_end) load_grad(0, c1);
+                if (u + 1 < u_end) {
+#pragma unroll
+                    for (int cc = 0; cc < NC; ++cc) load_grad(cc, 0, c1[cc]);
+                }
             }
             long long G = combine_digits(c);
             if (KSS > 1) {
@@ -534,7 +578,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 if (last) {
                     float xnew = 0.0f;
                     if (owner) {
-                        const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)C) : 0.0f;
+                        const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)(C * NC)) : 0.0f;
                         const float reg = a.l2 * x_own;
                         const float stp = a.lr * (g + reg);
                         x_own = x_own - stp;

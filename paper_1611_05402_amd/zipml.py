@@ -20,7 +20,8 @@ SGD_STEPWISE, SGD_AVERAGED = 1, 2
 OK, EINVAL, EALIGN, ERANGE, EWORKSPACE, ELAUNCH, EUNSUPPORTED, ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = ["zipml_strerror", "zipml_packed_bytes", "zipml_workspace_bytes", "zipml_levels",
-           "zipml_quantize", "zipml_sgd_epoch", "zipml_sgd_epoch_l2", "zipml_sgd_status", "zipml_loss",
+           "zipml_quantize", "zipml_quantize_swapped", "zipml_sgd_epoch", "zipml_sgd_epoch_l2",
+           "zipml_sgd_epoch_avg", "zipml_sgd_status", "zipml_loss",
            "zipml_unpack_codes", "zipml_debug_step"]
 
 
@@ -58,6 +59,10 @@ def lib() -> C.CDLL:
                                    C.POINTER(C.c_double), vp, sz]
         L.zipml_quantize.restype = i32
         L.zipml_quantize.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, i32, u64, u32, vp, vp]
+        L.zipml_quantize_swapped.restype = i32
+        L.zipml_quantize_swapped.argtypes = L.zipml_quantize.argtypes
+        L.zipml_sgd_epoch_avg.restype = i32
+        L.zipml_sgd_epoch_avg.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, vp, i64, f32, f32, i32, vp, sz]
         sgd = [vp, vp, vp, vp, vp, f32, f32, i32, vp, i64, i64, i32, vp, i64, f32, i32, i32, u64, u32]
         L.zipml_sgd_epoch.restype = i32
         L.zipml_sgd_epoch.argtypes = sgd + [i32, vp, sz]
@@ -121,6 +126,13 @@ def quantize(A, n_rows, d, lda, row0, n_total, levels_t, bits, seed, epoch, pack
            "zipml_quantize")
 
 
+def quantize_swapped(A, n_rows, d, lda, row0, n_total, levels_t, bits, seed, epoch, packed1s,
+                     packed2s, stream=None):
+    _check(lib().zipml_quantize_swapped(_stream(stream), _ptr(A), n_rows, d, lda, row0, n_total,
+                                        _ptr(levels_t), bits, seed, epoch, _ptr(packed1s),
+                                        _ptr(packed2s)), "zipml_quantize_swapped")
+
+
 def _sgd_args(packed1, packed2, levels_t, grid_idx, grid_lo, grid_step, grid_max, b, n, d, bits, x,
               batch, lr, grad_bits, model_bits, seed, epoch, stream):
     return [_stream(stream), _ptr(packed1), _ptr(packed2), _ptr(levels_t), _ptr(grid_idx),
@@ -143,6 +155,15 @@ def sgd_epoch_l2(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, l2, wo
                                     _ptr(b), n, d, bits, _ptr(x), batch, lr, l2, flags,
                                     _ptr(workspace), workspace.numel() * workspace.element_size()),
            "zipml_sgd_epoch_l2")
+
+
+def sgd_epoch_avg(packed1, packed2, packed1s, packed2s, levels_t, b, n, d, bits, x, batch, lr,
+                  workspace, *, l2=0.0, flags=0, stream=None):
+    _check(lib().zipml_sgd_epoch_avg(_stream(stream), _ptr(packed1), _ptr(packed2), _ptr(packed1s),
+                                     _ptr(packed2s), _ptr(levels_t), _ptr(b), n, d, bits, _ptr(x),
+                                     batch, lr, l2, flags, _ptr(workspace),
+                                     workspace.numel() * workspace.element_size()),
+           "zipml_sgd_epoch_avg")
 
 
 def debug_step(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, step, workspace, *,

@@ -395,6 +395,64 @@ def test_end_to_end_optimal_levels_bit_exact():
     assert np.linalg.norm(x_ref) > 0
 
 
+# ------------------------------------------------------------------ symmetrised estimator
+@pytest.mark.parametrize("name,factory,kw,lr,l2", [
+    ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256), 1e-3, 0.0),
+    ("dense8_wide_b512", synth.dense8, dict(n=4096, d=1100, batch=512), 1e-3, 0.0),
+    ("lowbit_small", synth.lowbit, dict(n=8192, d=640, batch=1024), 0.05, 0.0),
+    ("lssvm_4bit", synth.lssvm, dict(n=4096, d=288, bits=4, batch=128), 0.05, 0.05),
+    ("dense8_b4096_chunks", synth.dense8, dict(n=8192, d=288, batch=4096), 0.05, 0.0),
+])
+def test_symmetrised_estimator_matches_oracle(name, factory, kw, lr, l2):
+    """g = 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)] (Supp. A.4)."""
+    say("averaged", name)
+    w = factory(**kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L)
+    p.quantize(21, 0)
+    p1s, p2s = torch.zeros_like(p.p1), torch.zeros_like(p.p2)
+    zipml.quantize_swapped(p.A, w.n, w.d, w.d, 0, w.n, p.levels, w.bits, 21, 0, p1s, p2s)
+    c1, c2 = oracle.quantize(A, L, w.bits, 21, 0)
+    # the swapped arrays hold the other copy in the same layout
+    out = torch.zeros(w.n, w.d, dtype=torch.uint8, device=DEV)
+    zipml.unpack_codes(p1s, 1, w.n, w.d, w.bits, out)
+    assert np.array_equal(out.cpu().numpy(), c2)
+    zipml.unpack_codes(p2s, 2, w.n, w.d, w.bits, out)
+    assert np.array_equal(out.cpu().numpy(), c1)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(3):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, lr, symmetric=True, l2=l2)
+        zipml.sgd_epoch_avg(p.p1, p.p2, p1s, p2s, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, lr,
+                            p.ws, l2=l2)
+        assert zipml.sgd_status(p.ws) == 0
+        err = rel_l2(x.cpu().numpy(), x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}")
+        assert err <= TOL
+    # it is a different estimator from eq. (5)
+    x_plain = oracle.sgd_epoch(c1, c2, L, b, w.bits, np.zeros(w.d, np.float32), w.batch, lr, l2=l2)
+    x_sym = oracle.sgd_epoch(c1, c2, L, b, w.bits, np.zeros(w.d, np.float32), w.batch, lr, symmetric=True, l2=l2)
+    assert rel_l2(x_sym, x_plain) > 1e-5
+
+
+def test_symmetrised_estimator_refusals():
+    w = synth.tiny(n=1024, d=64, batch=64, bits=4)             # fits one workgroup: not on the matrix cores
+    A, b = w.full()
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(_levels_for(w, A))
+    p.quantize(1, 0)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    with pytest.raises(zipml.ZipmlError) as e:
+        zipml.sgd_epoch_avg(p.p1, p.p2, p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 0.01, p.ws)
+    assert e.value.code == zipml.EUNSUPPORTED
+    with pytest.raises(zipml.ZipmlError) as e:      # the flag of the plain entry point has no arrays to work on
+        zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 0.01, p.ws,
+                        flags=zipml.SGD_AVERAGED)
+    assert e.value.code == zipml.EUNSUPPORTED
+
+
 # ------------------------------------------------------------------ least-squares SVM
 @pytest.mark.parametrize("name,kw", [
     ("lssvm_8bit", dict()),                                   # matrix-core loop
