@@ -7,6 +7,8 @@
 #include "zipml_device.h"
 #include "zipml_host.h"
 
+#include <stdlib.h>
+
 #include <algorithm>
 #include <atomic>
 #include <limits>
@@ -120,6 +122,92 @@ __global__ __launch_bounds__(256) void k_hist(const float *__restrict__ A, int64
 // Host dynamic program for one feature: s intervals over the M+1 bin edges m/M.
 // Returns the total variance; idx[0..s] are the chosen edges.  Ties: smallest j.
 // ---------------------------------------------------------------------------------------------
+// The dynamic program of Sec. 3 on the device: one workgroup per feature, everything in LDS.
+//   T(1, m) = V(0, m),  T(k, m) = min_{k-1 <= j <= m-1} T(k-1, j) + V(j, m),
+//   V(j, m) = sum over the points in [d_j, d_m) of (d_m - t)(t - d_j), from prefix moments.
+// The arithmetic is that of the host version below, operation by operation (prefix sums in index
+// order, the same expression for V, the smallest j on ties), so both give the same levels.
+// Thread tid takes the end points m = tid, tid + 256, ...; in step i of the inner loop all threads
+// read the same j, which LDS serves as a broadcast.
+// LDS: 6 arrays of M+1 doubles and the argmin table (s+1) x (M+1) uint16.
+__host__ __device__ inline size_t dp_lds_bytes(int M, int s)
+{
+    const size_t W = (size_t)M + 1;
+    return 6 * W * sizeof(double) + (((size_t)s + 1) * W * sizeof(uint16_t) + 15) / 16 * 16 + 64;
+}
+__global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hist,
+                                                   const float *__restrict__ lo,
+                                                   const float *__restrict__ hi, int64_t d, int M,
+                                                   int s, float *__restrict__ levels,
+                                                   uint16_t *__restrict__ grid,
+                                                   double *__restrict__ objective)
+{
+    extern __shared__ __align__(16) unsigned char dp_smem[];
+    const int W = M + 1, K = s + 1, tid = threadIdx.x;
+    double *C = (double *)dp_smem, *S1 = C + W, *S2 = S1 + W, *edge = S2 + W, *prev = edge + W,
+           *cur = prev + W;
+    uint16_t *arg = (uint16_t *)(cur + W);                       // [s+1][W]
+    const double INF = __longlong_as_double(0x7FF0000000000000ll);
+    for (int64_t j = blockIdx.x; j < d; j += gridDim.x) {
+        const double *mom = hist + (size_t)j * M * 3;
+        __syncthreads();
+        // prefix moments, in index order (three chains, one thread each)
+        if (tid < 3) {
+            double *dst = tid == 0 ? C : tid == 1 ? S1 : S2;
+            double acc = 0.0;
+            dst[0] = 0.0;
+            for (int m = 0; m < M; ++m) {
+                acc = acc + mom[m * 3 + tid];
+                dst[m + 1] = acc;
+            }
+        }
+        for (int m = tid; m < W; m += 256) {
+            edge[m] = (double)m / (double)M;
+            prev[m] = INF;
+        }
+        __syncthreads();
+        auto V = [&](int jj, int m) {
+            const double dj = edge[jj], dm = edge[m];
+            return -(S2[m] - S2[jj]) + (dj + dm) * (S1[m] - S1[jj]) - dj * dm * (C[m] - C[jj]);
+        };
+        for (int m = 1 + tid; m <= M; m += 256) {
+            prev[m] = V(0, m);
+            arg[1 * W + m] = 0;
+        }
+        __syncthreads();
+        for (int k = 2; k <= s; ++k) {
+            for (int m = tid; m < W; m += 256) {
+                double best = INF;
+                int bj = k - 1;
+                if (m >= k) {
+                    for (int jj = k - 1; jj <= m - 1; ++jj) {
+                        const double v = prev[jj] + V(jj, m);
+                        if (v < best) { best = v; bj = jj; }
+                    }
+                    arg[(size_t)k * W + m] = (uint16_t)bj;
+                }
+                cur[m] = best;
+            }
+            __syncthreads();
+            double *t = prev; prev = cur; cur = t;
+        }
+        if (tid == 0) {
+            const double total = prev[M];
+            double cnt = C[M];
+            objective[j] = cnt > 0.0 ? total / cnt : 0.0;
+            const double l = (double)lo[j], w = (double)hi[j] - l;
+            int m = M;
+            for (int k = s; k >= 1; --k) {
+                if (grid) grid[(size_t)j * K + k] = (uint16_t)m;
+                levels[(size_t)j * K + k] = (float)(l + (w * (double)m) / (double)M);
+                m = arg[(size_t)k * W + m];
+            }
+            if (grid) grid[(size_t)j * K] = 0;
+            levels[(size_t)j * K] = (float)(l + (w * 0.0) / (double)M);
+        }
+    }
+}
+
 static double dp_one_feature(const double *mom, int M, int s, std::vector<double> &C,
                              std::vector<double> &S1, std::vector<double> &S2,
                              std::vector<double> &prev, std::vector<double> &cur,
@@ -165,7 +253,8 @@ static size_t levels_workspace_bytes(int64_t d, int n_candidates)
 {
     size_t keys = (size_t)round_up(d * 8, 256);
     size_t hist = (size_t)d * (size_t)n_candidates * 3 * sizeof(double);
-    return keys + hist;
+    size_t objective = (size_t)d * sizeof(double);     // per-feature value of the dynamic program
+    return keys + hist + objective;
 }
 
 }  // namespace zipml
@@ -234,6 +323,36 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
     hipLaunchKernelGGL(k_hist, dim3(cb, (unsigned)slabs), dim3(256), 0, s, A_dev, n, d, lda,
                        rows_per_slab, lo_dev, hi_dev, M, hist_dev);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+
+    // The dynamic program runs on the device when its tables fit in LDS (up to 5 bits at 1024
+    // candidates), else on the host cores.
+    int lds_limit = 0, dev = 0;
+    if (HIP_FAILED(hipGetDevice(&dev)) ||
+        HIP_FAILED(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev)))
+        return ZIPML_ELAUNCH;
+    const size_t dp_lds = dp_lds_bytes(M, sI);
+    if (dp_lds <= (size_t)lds_limit && !getenv("ZIPML_HOST_DP")) {
+        double *objective_dev = hist_dev + hcount;
+        uint16_t *grid_dev = grid_idx_dev;       // may be null
+        if (HIP_FAILED(hipFuncSetAttribute((const void *)k_dp_levels,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)dp_lds)))
+            return ZIPML_ELAUNCH;
+        const unsigned blocks = (unsigned)(d < 2048 ? d : 2048);
+        hipLaunchKernelGGL(k_dp_levels, dim3(blocks), dim3(256), dp_lds, s, hist_dev, lo_dev, hi_dev, d,
+                           M, sI, levels_dev, grid_dev, objective_dev);
+        if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+        if (mean_variance_host) {
+            std::vector<double> per_feature((size_t)d);
+            if (hipMemcpyAsync(per_feature.data(), objective_dev, sizeof(double) * (size_t)d,
+                               hipMemcpyDeviceToHost, s) != hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess)
+                return ZIPML_ELAUNCH;
+            double mv = 0.0;
+            for (int64_t j = 0; j < d; ++j) mv += per_feature[(size_t)j];
+            *mean_variance_host = mv / (double)d;
+        }
+        return ZIPML_OK;
+    }
     std::vector<double> hist((size_t)hcount);
     std::vector<float> lo((size_t)d), hi((size_t)d);
     if (hipMemcpyAsync(hist.data(), hist_dev, sizeof(double) * (size_t)hcount, hipMemcpyDeviceToHost,

@@ -75,6 +75,31 @@ def test_optimal_levels_match_oracle_dp():
     assert np.mean([np.array_equal(Gg[j], G[j]) for j in range(40)]) > 0.9
 
 
+def test_device_and_host_level_search_agree(monkeypatch):
+    """The dynamic program runs on the device when its tables fit in LDS and on the host cores
+    otherwise; both must give the same levels, index by index."""
+    say("levels optimal: device vs host dynamic program")
+    w = synth.e2e(n=4096, d=70, n_candidates=512)
+    A, b = w.full()
+    for bits in (2, 3, 5):
+        res = []
+        for host in (False, True):
+            if host:
+                monkeypatch.setenv("ZIPML_HOST_DP", "1")
+            else:
+                monkeypatch.delenv("ZIPML_HOST_DP", raising=False)
+            p = GpuProblem(A, b, bits, 32, n_candidates=512)
+            mv = p.make_levels(zipml.OPTIMAL, 0, n_candidates=512, want_mv=True)
+            res.append((p.grid.cpu().numpy().copy(), p.levels.cpu().numpy().copy(), mv))
+        monkeypatch.delenv("ZIPML_HOST_DP", raising=False)
+        assert np.array_equal(res[0][0], res[1][0])
+        assert np.array_equal(res[0][1], res[1][1])
+        # (the bin moments are accumulated with atomics, so two runs may differ in the last bits)
+        assert np.isclose(res[0][2], res[1][2], rtol=1e-12, atol=0)
+        G = res[0][0].view(np.uint16)
+        assert np.all(G[:, 0] == 0) and np.all(G[:, -1] == 512) and np.all(np.diff(G.astype(np.int32), axis=1) > 0)
+
+
 # ------------------------------------------------------------------ quantise
 QCASES = [
     # name, n, d, bits, level spec
