@@ -45,11 +45,22 @@ struct Workspace {
     static constexpr size_t kEven = 4096 + 1024;  // kEvenBlocks ints: levels evenly spaced, per block of features
     static constexpr int kEvenBlocks = 64;
     static constexpr size_t kNorm = 8192;         // norm exchange: 2 x 3 x 512 doubles (24 KiB)
-    static constexpr size_t kAcc = 8192 + 24576;  // 4 exchange buffers of acc_words 64-bit words
+    static constexpr size_t kAcc = 8192 + 24576;  // exchange buffers, 64-bit words (see below)
     static constexpr int kAccBuffers = 4;
-    // room for the sums of both code pairs of the symmetrised estimator and the side words
+    // One set of exchange buffers: kAccBuffers x acc_words(batch of one exchange), with room for
+    // the sums of both code pairs of the symmetrised estimator and the side words.
     static size_t acc_words(int64_t batch) { return (size_t)round_up(2 * batch + 64, 64); }
-    static size_t sgd_bytes(int64_t batch) { return kAcc + kAccBuffers * acc_words(batch) * 8; }
+    // A large minibatch is split over up to kMaxReplicas sets of workgroups; every replica has its
+    // own set of exchange buffers for its share of the minibatch (R * acc_words(batch / R) <=
+    // 2 * batch + 64 * R words per buffer), and the replicas exchange gradients through two
+    // buffers of kGradWords tagged words (at most 256 workgroups x 128 features), which follow
+    // the exchange buffers in use.
+    static constexpr int kMaxReplicas = 256;
+    static constexpr size_t kGradWords = 256 * 128;
+    static size_t sgd_bytes(int64_t batch)
+    {
+        return kAcc + (kAccBuffers * (2 * (size_t)round_up(batch, 64) + 64 * kMaxReplicas) + 2 * kGradWords) * 8;
+    }
 };
 
 // Called on entry of every API function: hipGetLastError() is sticky per host thread, so an

@@ -34,6 +34,7 @@
 #include "zipml_host.h"
 
 #include <math.h>
+#include <algorithm>
 #include <stdlib.h>
 
 namespace zipml {
@@ -104,6 +105,8 @@ struct SgdArgs {
     int mfma;              // evenly spaced levels may take the matrix-core step loop
     const int *even;       // [kEvenBlocks] 1: the levels of that block of features are evenly spaced
     int chunks;            // a minibatch is chunks * B samples (matrix-core loop only)
+    int R;                 // replicas of the W workgroups that share the chunks of a minibatch (divides chunks)
+    uint64_t *gx;          // [2][R][W * 32 GQ] tagged words: gradient exchange between replicas
     uint32_t spin_limit;   // polls before a wait gives up (ZIPML_ETIMEOUT); the kernel still runs to its end
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     // debug outputs (may be null)
@@ -741,7 +744,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
-    const int w = blockIdx.x;
+    const int w = blockIdx.x % a.W;                // feature block; blockIdx.x / a.W: replica (matrix-core loop)
     const int CW = 32 * a.GQ;
     const int B = a.B;
     const int nrg = B >= 32 ? B / 32 : 1;
@@ -815,7 +818,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     constexpr bool kMfmaBits = BITS == 2 || BITS == 4 || BITS == 8;
     if ((a.chunks > 1 || a.avg) && !(!INT && FAST && kMfmaBits && affine_all && a.mfma)) {
         // minibatches taken in chunks and the symmetrised estimator exist on the matrix-core loop only
-        if (w == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
+        if (blockIdx.x == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
         return;
     }
     if constexpr (!INT && FAST && kMfmaBits) {
@@ -840,8 +843,8 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         else sgd_steps<BITS, kTable, FAST, UPT>(a, L);
     }
 
-    // ---- write the model slice back
-    if (FAST || a.seg_last >= 3)
+    // ---- write the model slice back (the replicas hold identical copies: the first one does it)
+    if ((FAST || a.seg_last >= 3) && blockIdx.x < a.W)
         for (int c = tid; c < CW; c += kThreads)
             if (j0 + c < a.d) a.x[j0 + c] = L.xs[c];
 }
@@ -957,16 +960,21 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool sol
 // latency grows with the number of workgroups, so small steps want few, fat workgroups; the
 // registers that hold a thread's units (at most kMaxUpt per pass) and the number of compute units
 // bound the choice from both sides.
+static int target_workgroups()
+{
+    if (const char *env = getenv("ZIPML_TARGET_W")) {   // tuning override: preferred workgroup count
+        const int v = atoi(env);
+        if (v >= 1 && v <= 512) return v;
+    }
+    return 32;
+}
+
 static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool fp32_model, int pairs,
                      Plan &p)
 {
     int cus = 0, lds = 0;
     if (int rc = device_limits(cus, lds)) return rc;
-    int kTargetW = 32;
-    if (const char *env = getenv("ZIPML_TARGET_W")) {   // tuning override: preferred workgroup count
-        const int v = atoi(env);
-        if (v >= 1 && v <= 512) kTargetW = v;
-    }
+    const int kTargetW = target_workgroups();
     int best = 0;
     for (int GQ = 1; GQ <= 8; GQ <<= 1) {
         const int64_t W = (d32 + GQ - 1) / GQ;
@@ -1008,7 +1016,8 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)p.shmem)))
         return ZIPML_ELAUNCH;
-    const int words = Workspace::kAccBuffers * a.acc_words;
+    // exchange buffers of every replica, and the gradient exchange words behind them
+    const int words = a.R * Workspace::kAccBuffers * a.acc_words + (a.R > 1 ? 2 * (int)Workspace::kGradWords : 0);
     const int K = 1 << BITS;
     double *bound = const_cast<double *>(a.bound);
     hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, a.status, a.sync,
@@ -1020,7 +1029,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         a.seg_first = 0;
         a.seg_last = 3;
         void *params[] = {&a};
-        if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(a.W), dim3(kThreads), params,
+        if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(a.W * a.R), dim3(kThreads), params,
                                                   (unsigned)p.shmem, s)))
             return ZIPML_ELAUNCH;
         return ZIPML_OK;
@@ -1109,20 +1118,44 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     int rc = make_plan(lay.d32, bits, batch, model_bits > 0 && !ident, model_bits == 0, pairs, p);
     const bool stepwise = (flags & ZIPML_SGD_STEPWISE) != 0;
     const bool debug = dbg_m || dbg_acc || dbg_r || dbg_g || dbg_gq;
-    if (rc == ZIPML_EUNSUPPORTED && model_bits == 0 && !stepwise && !debug && batch % 64 == 0) {
+    int replicas = 1;
+    int64_t forced = 0;
+    if (const char *env = getenv("ZIPML_MICRO_BATCH")) forced = atol(env);   // tuning override: chunk size
+    const bool split_ok = model_bits == 0 && !stepwise && !debug && batch % 64 == 0 &&
+                          (bits == 2 || bits == 4 || bits == 8);
+    if (split_ok && (rc == ZIPML_EUNSUPPORTED || (rc == ZIPML_OK && p.mfma && forced > 0 && forced < batch))) {
         // A minibatch too large for one exchange is taken in equal chunks (matrix-core loop only:
         // the kernel reports ZIPML_EUNSUPPORTED through the status word if the levels turn out
-        // not to be evenly spaced).
+        // not to be evenly spaced).  The largest chunk whose plan reaches the preferred number of
+        // workgroups is taken (fewer, fatter workgroups leave more compute units for replicas),
+        // else the largest that fits at all.
+        int cus = 0, lds = 0;
+        if (int lrc = device_limits(cus, lds)) return lrc;
+        const int64_t w_goal = std::max<int64_t>(target_workgroups(), (lay.d32 + 3) / 4);
+        bool have = false;
         for (int64_t c = 2; c <= batch / 64; ++c) {
             if (batch % c != 0 || (batch / c) % 64 != 0) continue;
+            if (forced > 0 && batch / c != forced) continue;
             Plan q{};
-            if (make_plan(lay.d32, bits, batch / c, false, true, pairs, q) == ZIPML_OK && q.mfma) {
+            if (make_plan(lay.d32, bits, batch / c, false, true, pairs, q) != ZIPML_OK || !q.mfma) continue;
+            if (!have || q.W <= w_goal) {
                 p = q;
                 chunks = c;
                 micro = batch / c;
                 rc = ZIPML_OK;
-                break;
+                have = true;
             }
+            if (q.W <= w_goal) break;
+        }
+        if (have) {
+            // The chunks of a minibatch are independent: R replicas of the W workgroups take every
+            // R-th chunk each (R a power of two that divides the number of chunks).
+            int64_t cap = std::min<int64_t>(cus / p.W, Workspace::kMaxReplicas);
+            if (const char *env = getenv("ZIPML_REPLICAS")) {   // tuning override: at most this many
+                const long v = atol(env);
+                if (v >= 1) cap = std::min<int64_t>(cap, v);
+            }
+            while (replicas * 2 <= cap && chunks % (replicas * 2) == 0) replicas *= 2;
         }
     }
     if (rc) return rc;
@@ -1145,6 +1178,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.d32 = (int)lay.d32;
     a.B = (int)micro;
     a.chunks = (int)chunks;
+    a.R = replicas;
     a.step0 = step0;
     a.nsteps = (int)nsteps;
     a.lr = lr;
@@ -1172,6 +1206,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.bound = (const double *)(ws + Workspace::kBound);
     a.even = (const int *)(ws + Workspace::kEven);
     a.acc_words = (int)Workspace::acc_words(micro);
+    a.gx = a.acc + (size_t)replicas * Workspace::kAccBuffers * a.acc_words;
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
     switch (bits) {

@@ -143,7 +143,9 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
     const int n16 = lane & 15, q4 = lane >> 4;
-    const int w = blockIdx.x, W = a.W, GQ = a.GQ, CW = 32 * GQ, B = a.B;
+    const int W = a.W, GQ = a.GQ, CW = 32 * GQ, B = a.B;
+    const int w = blockIdx.x % W;                       // feature block of this workgroup
+    const int R = a.R, rep = blockIdx.x / W;            // replicas (see below), and which one this is
     const int j0 = w * CW;
     const int ngroups = (a.d32 - w * GQ) < GQ ? (a.d32 - w * GQ) : GQ;
     const int ntile = B / 16, NKS = B / 64;
@@ -155,11 +157,19 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const bool owner = g_kh == 0 && lane < 16;          // this lane updates feature 16*g_ft + lane
     const int oc = 16 * g_ft + n16;                     // that feature, inside the workgroup
     float *const xs = L.xs;
-    // A minibatch of C * B samples is taken as C chunks of B: every chunk has its own exchange,
-    // the model is updated after the last one.  u counts chunks through the epoch.
-    const int C = a.chunks;
+    // A minibatch of a.chunks * B samples is taken in chunks of B: every chunk has its own
+    // exchange, the model is updated after the last one.  The chunks of a minibatch do not depend
+    // on each other, so R replicas of the W workgroups (each with its own exchange buffers and its
+    // own, identical copy of the model) take every R-th chunk each: replica `rep` takes the chunks
+    // rep, rep + R, ... of every minibatch, C = a.chunks / R of them, which are R chunks apart
+    // through the whole epoch.  After its last chunk of a minibatch a workgroup hands its share of
+    // the gradient to the R - 1 workgroups that own the same features (exchange_gradient below);
+    // all add the R shares in the same order, so the copies of the model stay identical.
+    // u counts this replica's chunks through the epoch; chunk u is chunk u * R + rep of the data.
+    const int C = a.chunks / R;
     const int64_t u_begin = a.step0 * C, u_end = (a.step0 + a.nsteps) * C;
     const int nwords = NC * B + 2;                      // exchange words of a chunk: sums, 2 side words
+    uint64_t *const acc_base = a.acc + (size_t)rep * Workspace::kAccBuffers * a.acc_words;
     const uint32_t *const p2base[2] = {a.p2, a.p2s}, *const p1base[2] = {a.p1, a.p1s};
 
     // ---- LDS of this path
@@ -172,7 +182,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     int *const ymx = (int *)(misc + 64);                            // [8] max_j |Y_j|
     float *const wmax = (float *)(misc + 96);                       // [8] per wave max_i |r_i|
     float *const wsum = (float *)(misc + 128);                      // [8] per wave sum_i r_i
-    float *const side = (float *)(misc + 160);                      // [2] decoded side words
+    float *const side = (float *)(misc + 160);                      // [2] decoded side words, [1] largest |residual| of all replicas
 
     for (int e = tid; e < KB * 256 + NC * NKS * 256; e += kThreads) ydig[e] = 0;
     if (tid < 8) { cqs[tid] = 0.0f; bws[tid] = 0.0f; ymx[tid] = 0; wmax[tid] = 0.0f; wsum[tid] = 0.0f; }
@@ -184,7 +194,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             lds_barrier();
             if (w == 0 && wave == kWaves - 1) {
                 // clear the exchange words of step t+2 (see zipml_sgd.hip for why now)
-                uint64_t *nxt = a.acc + (size_t)((u + 2) & 3) * a.acc_words;
+                uint64_t *nxt = acc_base + (size_t)((u + 2) & 3) * a.acc_words;
                 for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
                 vm_wait_all();
             }
@@ -242,7 +252,9 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     if (g_kh == 0) refresh_y(x_own, ky, true);
 
     // ---- packed data held in registers; the addresses advance by a fixed stride per step
-    const int64_t step_dwords = (int64_t)B * BITS;      // both copies: B samples x BITS dwords per group
+    const int64_t step_dwords = (int64_t)R * B * BITS;  // both copies: B samples x BITS dwords per group,
+                                                        // R chunks from one chunk of this replica to its next
+    const int64_t row_begin = (u_begin * R + rep) * B;  // first sample of this replica's first chunk
     uint32_t c2cur[NC][kTiles][KB][HW], c2nxt[kT2][KB][HW], c1[NC][kNG][HW], c1nxt[kG2][HW];
     const uint32_t *p2ptr[NC][kTiles][KB], *p1ptr[NC][kNG];
     bool p2ok[kTiles][KB], p1ok[kNG];
@@ -254,7 +266,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         for (int kb = 0; kb < KB; ++kb) {
             const int gq = 2 * kb + (q4 >> 1);
             p2ok[ti][kb] = tile < ntile && gq < ngroups;
-            const int64_t row = u_begin * B + 16 * tile + n16;
+            const int64_t row = row_begin + 16 * tile + n16;
             const int64_t g = (int64_t)w * GQ + gq;
 #pragma unroll
             for (int cc = 0; cc < NC; ++cc)
@@ -268,7 +280,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         const int gq = g_ft >> 1, cin = 16 * (g_ft & 1) + n16;
         p1ok[m] = ks < NKS && gq < ngroups;
         const int64_t g = (int64_t)w * GQ + gq;
-        const int64_t rg = (u_begin * B) / 32 + 2 * ks + (q4 >> 1);
+        const int64_t rg = row_begin / 32 + 2 * ks + (q4 >> 1);
 #pragma unroll
         for (int cc = 0; cc < NC; ++cc)
             p1ptr[cc][m] = p1ok[m] ? p1base[cc] + ((g * a.n32 + rg) * 32 + cin) * BITS + (q4 & 1) * HW
@@ -299,11 +311,11 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             }
         }
     };
-    auto load_labels = [&](int64_t t, float (&dst)[kBpt]) {
+    auto load_labels = [&](int64_t uu, float (&dst)[kBpt]) {
 #pragma unroll
         for (int k = 0; k < kBpt; ++k) {
             const int i = tid + k * nthr;
-            if (i < B) dst[k] = a.b[t * B + i];
+            if (i < B) dst[k] = a.b[(uu * R + rep) * B + i];
         }
     };
     // operands that are never loaded multiply digit rows that are zero; give them a value anyway
@@ -358,12 +370,21 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     int chunk = 0;
     for (int64_t u = u_begin; u < u_end; ++u) {
         const bool first = chunk == 0, last = chunk == C - 1;
-        uint64_t *const acc = a.acc + (size_t)(u & 3) * a.acc_words;
+        uint64_t *const acc = acc_base + (size_t)(u & 3) * a.acc_words;
         const bool side_step = first && (t % kRefresh) == 0;   // bounds travel with this exchange
         const bool side_next = last && ((t + 1) % kRefresh) == 0;
         ZIPML_TICK(7);
         lds_barrier();          // digits of y and the per-tile sums of the current model
         ZIPML_TICK(0);
+        if (R > 1 && first && u > u_begin) {
+            // the model has just moved by the gradient of all replicas: grow the bounds by the
+            // largest residual any of them saw (left in LDS by the owner waves)
+            const float rall = side[2];
+            beta_hat += lr_abs * (lambda * rall + l2_abs * beta_hat);
+            ymax_hat += lr_abs * (mu * rall + l2_abs * ymax_hat);
+            ky = scale_of();
+            rmax_step = 0.0f;
+        }
 
         // ============ dot pass: one instruction per (16 samples, 64 features)
         {
@@ -419,7 +440,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         // for why that is the right moment and why no wait is needed here); with idle waves
         // around, one of them does it instead.
         if (nw == kWaves && w == 0 && wave == kWaves - 1) {
-            uint64_t *nxt = a.acc + (size_t)((u + 2) & 3) * a.acc_words;
+            uint64_t *nxt = acc_base + (size_t)((u + 2) & 3) * a.acc_words;
             for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
             if (!(tid < B)) vm_wait_all();
         }
@@ -515,7 +536,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         }
         rmax_step = fmaxf(rmax_step, Rmax);
         int ky_next = ky;
-        if (last) {
+        if (last && R == 1) {
             beta_hat += lr_abs * (lambda * rmax_step + l2_abs * beta_hat);
             ymax_hat += lr_abs * (mu * rmax_step + l2_abs * ymax_hat);
             ky_next = scale_of();
@@ -576,16 +597,68 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             if (g_kh == 0) {
                 if (owner) gsum += o_mid * Rtot + o_dl * fixed_to_float(G, kr);   // chunks in order
                 if (last) {
+                    int ky_own = ky_next;
+                    if (R > 1) {
+                        // ---- gradient exchange between the replicas of this feature block.  A
+                        // 64-bit word carries, above the fp32 gradient share, a 16-bit tag of the
+                        // step and an upper bound (8 significant bits) of the largest |residual|
+                        // the replica saw, so one store delivers everything and its arrival.  Two
+                        // buffers alternate (a workgroup cannot finish step t+1 before every
+                        // replica has read step t: it needs their words of step t+1 first).
+                        const size_t nfeat = (size_t)W * CW;
+                        uint64_t *const gxb = a.gx + (size_t)(t & 1) * ((size_t)R * nfeat);
+                        const uint32_t tag = ((uint32_t)(t + 1) & 0x7FFFu) | 0x8000u;
+                        // bf16-like: truncate to 16 bits, one step up (rmax_step >= 0, finite or inf)
+                        const uint32_t rbits = __float_as_uint(rmax_step);
+                        const uint32_t r16 = rbits >= 0x7F800000u ? 0x7F80u : (rbits >> 16) + 1u;
+                        if (owner)
+                            store_dev(gxb + (size_t)rep * nfeat + j0 + oc,
+                                      ((uint64_t)((tag << 16) | r16) << 32) | (uint64_t)__float_as_uint(gsum));
+                        float gtot = 0.0f, rall = 0.0f;
+                        if (owner) {
+                            uint32_t spins = 0;
+                            for (int q0 = 0; q0 < R; q0 += 8) {      // eight replicas per round of loads
+                                uint64_t vg[8];
+#pragma unroll 1
+                                for (;;) {
+                                    bool all = true;
+#pragma unroll
+                                    for (int q = 0; q < 8; ++q)
+                                        if (q0 + q < R) {
+                                            vg[q] = load_dev(gxb + (size_t)(q0 + q) * nfeat + j0 + oc);
+                                            all = all && (uint32_t)(vg[q] >> 48) == tag;
+                                        }
+                                    if (all || dead) break;
+                                    if (++spins > a.spin_limit) {
+                                        store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                                        dead = true;
+                                    }
+                                }
+#pragma unroll
+                                for (int q = 0; q < 8; ++q)
+                                    if (q0 + q < R) {                 // shares are added in replica order
+                                        gtot += __uint_as_float((uint32_t)vg[q]);
+                                        rall = fmaxf(rall, __uint_as_float(((uint32_t)(vg[q] >> 32) & 0xFFFFu) << 16));
+                                    }
+                            }
+                        }
+                        gsum = gtot;
+                        if (g_ft == 0 && lane == 0) side[2] = rall;   // for everybody, after the next barrier
+                        const float bh = beta_hat + lr_abs * (lambda * rall + l2_abs * beta_hat);
+                        const float yh = ymax_hat + lr_abs * (mu * rall + l2_abs * ymax_hat);
+                        const int k1 = scale_exponent(bh, 42), k2 = scale_exponent(yh, 29);
+                        ky_own = k1 < k2 ? k1 : k2;                   // what scale_of() will give then
+                    }
                     float xnew = 0.0f;
                     if (owner) {
-                        const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)(C * NC)) : 0.0f;
+                        const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)(a.chunks * NC)) : 0.0f;
                         const float reg = a.l2 * x_own;
                         const float stp = a.lr * (g + reg);
                         x_own = x_own - stp;
                         xnew = x_own;
                     }
                     gsum = 0.0f;
-                    refresh_y(xnew, ky_next, side_next);
+                    refresh_y(xnew, ky_own, side_next);
                 }
             }
         }

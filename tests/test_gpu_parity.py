@@ -234,6 +234,7 @@ def test_sgd_epochs_match_oracle(name, factory, kw, epochs, lr, flags):
     ("dense8_small", synth.dense8, dict(n=8192, d=288, batch=256), 1e-3),     # matrix-core loop
     ("lowbit_small", synth.lowbit, dict(n=8192, d=96, batch=1024), 0.05),     # 2-bit, per-column ranges
     ("b5", synth.tiny, dict(n=2048, d=160, batch=64, bits=5), 0.01),          # vector loop
+    ("dense8_replicas", synth.dense8, dict(n=16384, d=288, batch=8192), 0.05),  # chunks on four replicas
 ])
 def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
     """Sums across workgroups are integer sums: the order of arrival must not show in the result."""
@@ -257,8 +258,13 @@ def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
     ("dense8_b4096", synth.dense8, dict(n=8192, d=288), 4096, 0.05),       # two chunks of 2048
     ("dense8_full_batch", synth.dense8, dict(n=8192, d=288), 8192, 0.05),  # gradient descent
     ("lowbit_b8192", synth.lowbit, dict(n=16384, d=96), 8192, 0.2),        # 2-bit, per-column ranges
+    ("dense8_b6144", synth.dense8, dict(n=12288, d=288), 6144, 0.05),      # three chunks: one replica
+    ("dense8_wide_b8192", synth.dense8, dict(n=16384, d=1100), 8192, 0.02),  # 8 chunks on 4 replicas of 35
+    ("tomo4_b4096", synth.tomo, dict(n=8192, d=256), 4096, 0.5),           # 4-bit, sparse rows
 ])
 def test_large_minibatches_taken_in_chunks(name, factory, kw, batch, lr):
+    """A minibatch that does not fit one exchange is taken in chunks, and the chunks are shared
+    out over replicas of the workgroups that exchange their gradient shares once per step."""
     say("large batch", name)
     w = factory(batch=batch, **kw)
     A, b = w.full()
@@ -518,6 +524,7 @@ def test_least_squares_svm_epochs_match_oracle(name, kw):
 @pytest.mark.parametrize("name,factory,kw", [
     ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256)),          # matrix-core loop
     ("b5_wide", synth.tiny, dict(n=2048, d=1056, batch=64, bits=5)),         # vector loop, 33 groups
+    ("dense8_replicas", synth.dense8, dict(n=8192, d=288, batch=4096)),      # chunks on two replicas
 ])
 def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, monkeypatch):
     """Every device-wide wait is bounded.  With the bound forced to zero polls from the host, each
