@@ -61,6 +61,16 @@ struct Workspace {
     {
         return kAcc + (kAccBuffers * (2 * (size_t)round_up(batch, 64) + 64 * kMaxReplicas) + 2 * kGradWords) * 8;
     }
+    // Very large minibatches (kRowsMinBatch samples or more, a multiple of 64) may take the
+    // sample-owner kernel: per-feature constants (2 arrays), one gradient per workgroup (at most
+    // kMaxRowsWgs) and one sum of residuals per workgroup, all fp32, behind everything else.
+    static constexpr int64_t kRowsMinBatch = 16384;
+    static constexpr int kMaxRowsWgs = 256;
+    static size_t rows_bytes(int64_t d, int64_t batch)
+    {
+        if (batch < kRowsMinBatch || batch % 64 != 0) return 0;
+        return ((size_t)(kMaxRowsWgs + 2) * (size_t)round_up(d, 64) + kMaxRowsWgs + 64) * 4;
+    }
 };
 
 // Called on entry of every API function: hipGetLastError() is sticky per host thread, so an

@@ -188,6 +188,7 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ p, uint32
 
 }  // namespace zipml
 #include "zipml_sgd_mfma.h"
+#include "zipml_sgd_rows.h"
 namespace zipml {
 
 // ---- inner loops over the 32 codes of a unit (v: 32 wave-uniform fp32/int32 values in LDS) ----
@@ -1066,6 +1067,44 @@ static int launch_sgd_mode(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwi
                             : launch_sgd<BITS, false>(s, a, p, stepwise);
 }
 
+// Sample-owner kernel for very large minibatches (zipml_sgd_rows.h).
+template <int BITS>
+static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs, double *bound,
+                       int *even, uint64_t *acc)
+{
+    const int K = 1 << BITS;
+    const int nfeat = r.NKB * 64;
+    const size_t shmem = rows_lds_bytes(r.NKB);
+    // blocks per wave and item: as many as the registers hold, fewer for narrow problems
+    int kpi = 16 / BITS;
+    if (const char *env = getenv("ZIPML_ROWS_KPI")) {   // tuning override: at most this many
+        const int v = atoi(env);
+        if (v >= 1 && v < kpi) kpi = v;
+    }
+    while (kpi > 1 && (r.NKB < kWaves * kpi || (kpi & (kpi - 1)))) --kpi;
+    const void *kern = nullptr;
+    if constexpr (BITS == 8) kern = kpi == 2 ? (const void *)k_sgd_rows<8, 2> : (const void *)k_sgd_rows<8, 1>;
+    if constexpr (BITS == 4)
+        kern = kpi == 4 ? (const void *)k_sgd_rows<4, 4> : kpi == 2 ? (const void *)k_sgd_rows<4, 2>
+                                                                   : (const void *)k_sgd_rows<4, 1>;
+    if constexpr (BITS == 2)
+        kern = kpi == 8 ? (const void *)k_sgd_rows<2, 8> : kpi == 4 ? (const void *)k_sgd_rows<2, 4>
+             : kpi == 2 ? (const void *)k_sgd_rows<2, 2> : (const void *)k_sgd_rows<2, 1>;
+    if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
+        return ZIPML_ELAUNCH;
+    // status word, barrier counter, evenly-spaced check (no exchange words to clear)
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, r.status, r.sync,
+                       acc, 0, 1, levels, r.x, r.d, K, bound, even);
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+    hipLaunchKernelGGL(k_rows_prepare, dim3((nfeat + 255) / 256), dim3(256), 0, s, levels, r.d, K, nfeat,
+                       BITS == 8 ? 128.0f : 0.0f, const_cast<float *>(r.dl), const_cast<float *>(r.mid));
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+    void *params[] = {&r};
+    if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(wgs), dim3(kThreads), params, (unsigned)shmem, s)))
+        return ZIPML_ELAUNCH;
+    return ZIPML_OK;
+}
+
 static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_dev,
                    const void *packed1s_dev, const void *packed2s_dev, const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
                    float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d, int bits,
@@ -1156,6 +1195,67 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
                 if (v >= 1) cap = std::min<int64_t>(cap, v);
             }
             while (replicas * 2 <= cap && chunks % (replicas * 2) == 0) replicas *= 2;
+        }
+    }
+    // Very large minibatches: workgroups that own samples instead of features need no exchange
+    // per sample (evenly spaced levels only: the kernel reports ZIPML_EUNSUPPORTED through the
+    // status word otherwise, as for chunked minibatches).
+    {
+        // It pays from about two tiles of 64 samples per compute unit on (a step costs two
+        // device-wide barriers and a reduction over all workgroups), earlier for wide problems.
+        int64_t rows_min = lay.d_pad >= 8192 ? Workspace::kRowsMinBatch : 2 * Workspace::kRowsMinBatch;
+        if (const char *env = getenv("ZIPML_ROWS_MIN_BATCH")) {   // tuning override (not below the workspace's rule)
+            const long v = atol(env);
+            if (v >= Workspace::kRowsMinBatch) rows_min = v;
+        }
+        int cus = 0, lds = 0;
+        if (int lrc = device_limits(cus, lds)) return lrc;
+        const int NKB = (int)((lay.d32 + 1) / 2);
+        // (the kernel's per-lane byte offsets are 32 bits wide: one feature group of copy 2 must fit)
+        if (split_ok && !avg && batch >= rows_min && batch / 64 >= cus &&
+            rows_lds_bytes(NKB) <= (size_t)lds && lay.n_pad * bits * 4 < ((int64_t)1 << 32) &&
+            !getenv("ZIPML_NO_MFMA")) {
+            unsigned char *wsb = (unsigned char *)workspace_dev;
+            float *rows = (float *)(wsb + Workspace::sgd_bytes(batch) + (size_t)round_up(d, 64) * 4);
+            int wgs = std::min(cus, Workspace::kMaxRowsWgs);
+            if (const char *env = getenv("ZIPML_ROWS_WGS")) {   // tuning override
+                const int v = atoi(env);
+                if (v >= 1 && v <= Workspace::kMaxRowsWgs) wgs = v;
+            }
+            RowsArgs r{};
+            r.p1 = (const uint32_t *)packed1_dev;
+            r.p2 = (const uint32_t *)packed2_dev;
+            r.b = b_dev;
+            r.x = x_dev;
+            r.dl = rows;
+            r.mid = rows + (size_t)NKB * 64;
+            r.part = rows + (size_t)2 * NKB * 64;
+            r.n_pad = lay.n_pad;
+            r.n32 = lay.n32;
+            r.d = (int)d;
+            r.d32 = (int)lay.d32;
+            r.NKB = NKB;
+            r.B = batch;
+            r.step0 = step0;
+            r.nsteps = (int)nsteps;
+            r.lr = lr;
+            r.l2 = l2;
+            r.status = (int *)(wsb + Workspace::kStatus);
+            r.sync = (uint32_t *)(wsb + Workspace::kSync);
+            r.even = (const int *)(wsb + Workspace::kEven);
+            r.spin_limit = kSpinLimit;
+            if (const char *env = getenv("ZIPML_SPIN_LIMIT")) {   // test hook: make every wait give up early
+                const long v = atol(env);
+                if (v >= 0 && v <= (long)kSpinLimit) r.spin_limit = (uint32_t)v;
+            }
+            double *bound = (double *)(wsb + Workspace::kBound);
+            int *even = (int *)(wsb + Workspace::kEven);
+            uint64_t *acc = (uint64_t *)(wsb + Workspace::kAcc);
+            switch (bits) {
+                case 2: return launch_rows<2>(s, r, levels_dev, wgs, bound, even, acc);
+                case 4: return launch_rows<4>(s, r, levels_dev, wgs, bound, even, acc);
+                case 8: return launch_rows<8>(s, r, levels_dev, wgs, bound, even, acc);
+            }
         }
     }
     if (rc) return rc;

@@ -254,6 +254,53 @@ def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
     assert np.isfinite(runs[0].view(np.float32)).all() and np.any(runs[0] != 0)
 
 
+@pytest.mark.parametrize("name,factory,kw,batch,lr,l2", [
+    ("dense8_b16384", synth.dense8, dict(n=32768, d=288), 16384, 0.05, 0.0),     # odd number of feature groups
+    ("dense8_wide_full_batch", synth.dense8, dict(n=16384, d=1100), 16384, 0.02, 0.0),
+    ("lowbit_full_batch", synth.lowbit, dict(n=32768, d=96), 32768, 0.2, 0.0),   # 2-bit, per-column ranges
+    ("tomo4_b16384", synth.tomo, dict(n=32768, d=256), 16384, 0.5, 0.0),         # 4-bit, sparse rows
+    ("lssvm_b16384", synth.lssvm, dict(n=16384, d=288, bits=8), 16384, 0.05, 0.05),
+])
+def test_very_large_minibatches_on_sample_owners(name, factory, kw, batch, lr, l2, monkeypatch):
+    """Very large minibatches (by default from two tiles of 64 samples per compute unit on; here
+    from 16,384 samples, the smallest the workspace provides for) go to workgroups that own samples
+    instead of features: same estimator, same oracle."""
+    say("sample owners", name)
+    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")
+    w = factory(batch=batch, **kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, batch)
+    p.set_levels(L)
+    p.quantize(8, 0)
+    c1, c2 = oracle.quantize(A, L, w.bits, 8, 0)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    runs = []
+    for ep in range(4):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, batch, lr, l2=l2)
+        zipml.sgd_epoch_l2(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, batch, lr, l2, p.ws)
+        assert zipml.sgd_status(p.ws) == 0
+        err = rel_l2(x.cpu().numpy(), x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}")
+        assert err <= TOL
+    assert np.linalg.norm(x_ref) > 0
+    # the sums are taken in a fixed order: a second run gives the same bits
+    y = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(4):
+        zipml.sgd_epoch_l2(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, y, batch, lr, l2, p.ws)
+    assert torch.equal(x, y)
+    # levels that are not evenly spaced are refused through the status word
+    L2 = L.copy()
+    L2[1] = np.sort(np.random.default_rng(0).uniform(L[1, 0], L[1, -1], L.shape[1])).astype(np.float32)
+    L2[1, 0], L2[1, -1] = L[1, 0], L[1, -1]
+    p.set_levels(L2)
+    x0 = x.clone()
+    zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, batch, lr, p.ws)
+    assert zipml.sgd_status(p.ws) == zipml.EUNSUPPORTED
+    assert torch.equal(x, x0)
+
+
 @pytest.mark.parametrize("name,factory,kw,batch,lr", [
     ("dense8_b4096", synth.dense8, dict(n=8192, d=288), 4096, 0.05),       # two chunks of 2048
     ("dense8_full_batch", synth.dense8, dict(n=8192, d=288), 8192, 0.05),  # gradient descent
@@ -525,11 +572,13 @@ def test_least_squares_svm_epochs_match_oracle(name, kw):
     ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256)),          # matrix-core loop
     ("b5_wide", synth.tiny, dict(n=2048, d=1056, batch=64, bits=5)),         # vector loop, 33 groups
     ("dense8_replicas", synth.dense8, dict(n=8192, d=288, batch=4096)),      # chunks on two replicas
+    ("dense8_sample_owners", synth.dense8, dict(n=16384, d=288, batch=16384)),
 ])
 def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, monkeypatch):
     """Every device-wide wait is bounded.  With the bound forced to zero polls from the host, each
     wait gives up at once: the kernel must still run to its end and leave ZIPML_ETIMEOUT."""
     say("timeout path", name)
+    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")    # (for the sample-owner case)
     w = factory(**kw)
     A, b = w.full()
     p = GpuProblem(A, b, w.bits, w.batch)
@@ -571,11 +620,26 @@ def test_degenerate_inputs():
     with pytest.raises(zipml.ZipmlError) as e:
         zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, 32, 5, 2, x, 24, 0.1, p.ws)
     assert e.value.code == zipml.EINVAL
-    # a batch too large for the persistent kernel is refused, not mis-executed
+    # one feature group and a minibatch of 32,768: no feature owners to share the work, the
+    # sample-owner kernel takes it
     big = synth.tiny(n=1 << 15, d=32, batch=1 << 15, bits=8)
     Ab, bb = big.full()
+    Lb = uniform_levels_np(32, 8, -1.0, 1.0)
     pb = GpuProblem(Ab, bb, 8, 1 << 15)
+    pb.set_levels(Lb)
+    pb.quantize(4, 0)
+    cb1, cb2 = oracle.quantize(Ab, Lb, 8, 4, 0)
     xb = torch.zeros(32, dtype=torch.float32, device=DEV)
+    pb.epoch(xb, 0.1)
+    assert rel_l2(xb.cpu().numpy(), oracle.sgd_epoch(cb1, cb2, Lb, bb, 8, np.zeros(32), 1 << 15, 0.1)) <= TOL
+    # a batch too large for one exchange at a code width the matrix cores do not take is refused,
+    # not mis-executed
+    odd = synth.tiny(n=1 << 13, d=32, batch=1 << 13, bits=5)
+    Ao, bo = odd.full()
+    po = GpuProblem(Ao, bo, 5, 1 << 13)
+    po.set_levels(uniform_levels_np(32, 5, -1.0, 1.0))
+    po.quantize(4, 0)
+    xo = torch.zeros(32, dtype=torch.float32, device=DEV)
     with pytest.raises(zipml.ZipmlError) as e:
-        zipml.sgd_epoch(pb.p1, pb.p2, pb.levels, pb.b, 1 << 15, 32, 8, xb, 1 << 15, 0.1, pb.ws)
+        zipml.sgd_epoch(po.p1, po.p2, po.levels, po.b, 1 << 13, 32, 5, xo, 1 << 13, 0.1, po.ws)
     assert e.value.code == zipml.EUNSUPPORTED
