@@ -170,6 +170,30 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    # ---- the same epoch at larger minibatches (same resident data; not part of `value`):
+    # 4x, 16x and the whole data set per step, and the whole-data-set step on 8x the samples
+    # (random codes: only the rate matters there)
+    sweep = []
+
+    def sweep_point(nn, p1s, p2s, bs, batch, reps=5):
+        xs = torch.zeros(d, dtype=torch.float32, device=dev)
+        wss = torch.zeros(zipml.workspace_bytes(nn, d, bits, batch), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: zipml.sgd_epoch(p1s, p2s, lev, bs, nn, d, bits, xs, batch, w.lr, wss), reps)
+        assert zipml.sgd_status(wss) == 0
+        nbytes = nn * (2 * d * bits / 8 + 4)
+        sweep.append({"n": nn, "batch": batch, "ms_per_epoch": ms, "us_per_step": ms * 1e3 / (nn // batch),
+                      "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
+
+    if not args.batch:
+        for mult in (4, 16):
+            sweep_point(n, p1, p2, bd, B * mult)
+        sweep_point(n, p1, p2, bd, n)
+        n8 = 8 * n
+        q1 = torch.randint(0, 256, (zipml.packed_bytes(n8, d, bits),), dtype=torch.uint8, device=dev)
+        q2 = torch.randint(0, 256, (zipml.packed_bytes(n8, d, bits),), dtype=torch.uint8, device=dev)
+        sweep_point(n8, q1, q2, torch.randn(n8, device=dev), n8)
+        del q1, q2
+
     loss_ms = timed(lambda: zipml.loss(bd, x, n, d, ws, A=Ad_full, lda=d))
     final_loss = zipml.loss(bd, x, n, d, ws, A=Ad_full, lda=d)
     loss_p_ms = timed(lambda: zipml.loss(bd, x, n, d, ws, packed=p2, copy=2, levels_t=lev, bits=bits))
@@ -200,6 +224,7 @@ def main():
                      "kernel_ms": kern_ms, "us_per_minibatch_step": kern_ms * 1e3 / (n // B)},
         "other_ms": {"levels": levels_ms, "quantize": quant_ms, "loss_fp32": loss_ms,
                      "loss_packed": loss_p_ms, "generate_and_upload_s": gen_s},
+        "batch_sweep": sweep,
         "final_loss": final_loss,
         "paper_context": "paper reports ratios only: up to 6.5x over a 32-bit FPGA implementation "
                          "or 10-core Hogwild! (other hardware; not a target)",

@@ -123,7 +123,13 @@ int zipml_quantize_swapped(void *stream, const float *A_dev, int64_t n_rows, int
  *     the update (Supp. D, E).
  * grid_max is the largest grid index (2^bits - 1 for UNIFORM levels, n_candidates for OPTIMAL);
  * ZIPML_ERANGE if grid_max * s * d could exceed int32.
- * batch must divide n and be 4, 8, 16 or a multiple of 32.
+ * batch must divide n and be 4, 8, 16 or a multiple of 32.  A minibatch of up to 2048 / GQ samples
+ * (GQ = 1, 2 or 4 groups of 32 features per workgroup; 1024 samples at d = 2048) is one exchange
+ * between the workgroups; larger ones -- up to the whole data set, i.e. gradient descent with
+ * double sampling -- are supported for the fp32 model with evenly spaced 2-, 4- or 8-bit levels
+ * and batch a multiple of 64 (taken in chunks by replicas of the workgroups, or by workgroups that
+ * own samples instead of features); otherwise ZIPML_EUNSUPPORTED, which for level tables that
+ * turn out not to be evenly spaced arrives through zipml_sgd_status with x_dev left untouched.
  * The call is asynchronous; a failed grid-wide wait is reported by zipml_sgd_status. */
 int zipml_sgd_epoch(void *stream, const void *packed1_dev, const void *packed2_dev,
                     const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,

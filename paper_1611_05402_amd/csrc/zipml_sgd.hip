@@ -20,16 +20,19 @@
 //     the partial sums that every workgroup tracks identically (see sgd_steps);
 //   - the packed data does not depend on the model.  Every thread owns the same units (sample x
 //     feature group for the dot pass, feature x sample group for the gradient pass) in every
-//     step and fetches them into registers ahead of time: right after the sums of step t have
-//     been read it requests copy 1 of step t+1 and copy 2 of step t+2.  That is the one point of
-//     a step from which no latency-critical memory operation follows for about a microsecond
-//     (loads of a wave, and of a compute unit's memory pipeline, return in order, so a long load
-//     in flight would hold back the atomics' acknowledgement, the barrier poll and the sums);
+//     step and fetches them into registers ahead of time: directly behind the atomics of step t
+//     it requests copy 1 of step t+1 and copy 2 of step t+2.  The loads then travel while the
+//     exchange is under way (loads of a wave, and of a compute unit's memory pipeline, return in
+//     order: requested before the atomics they would hold back the exchange by their own latency;
+//     behind them, the poll that is queued after them returns when both are done);
 //   - exchanged data moves only through device-scope atomics / loads, so no cache write-back or
 //     invalidation is ever needed;
 //   - workgroup barriers inside a step order LDS traffic only (lds_barrier).
 // End-to-end mode adds two small exchanges per step (the l2 norms of model and gradient), each
 // closed by a grid barrier (one monotonically increasing arrival counter).
+// Minibatches too large for one exchange are taken in chunks, shared out over replicas of the
+// workgroups (zipml_sgd_mfma.h), and very large ones by workgroups that own samples instead of
+// features (zipml_sgd_rows.h); run_sgd below chooses.
 #include "zipml_device.h"
 #include "zipml_host.h"
 
@@ -738,7 +741,9 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 // ---------------------------------------------------------------------------------------------
 // The epoch kernel: LDS carve, one-time set-up, then the step loop of the right mode.
 // ---------------------------------------------------------------------------------------------
-template <int BITS, bool INT, bool FAST, int UPT>
+// REP: the launch has replicas of the workgroups (a.R > 1; matrix-core loop only).  A kernel of
+// its own, so that the code of the replicas costs the ordinary launch no registers.
+template <int BITS, bool INT, bool FAST, int UPT, bool REP = false>
 __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
 {
     constexpr int K = 1 << BITS;
@@ -822,16 +827,30 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         if (blockIdx.x == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
         return;
     }
-    if constexpr (!INT && FAST && kMfmaBits) {
+    if constexpr (REP) {
+        if constexpr (!INT && FAST && kMfmaBits) {
+            if (affine_all && a.mfma) {     // (anything else has been refused above: replicas imply chunks)
+                if (a.avg) {
+                    if constexpr (UPT <= 2) {
+                        if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2, true>(a, L, L.mf);
+                        else sgd_steps_mfma<BITS, UPT, 2, 2, true>(a, L, L.mf);
+                    }
+                } else {
+                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, true>(a, L, L.mf);
+                    else sgd_steps_mfma<BITS, UPT, 2, 1, true>(a, L, L.mf);
+                }
+            }
+        }
+    } else if constexpr (!INT && FAST && kMfmaBits) {
         if (affine_all && a.mfma) {
             if (a.avg) {
                 if constexpr (UPT <= 2) {      // the plan keeps the symmetrised estimator to these
-                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2>(a, L, L.mf);
-                    else sgd_steps_mfma<BITS, UPT, 2, 2>(a, L, L.mf);
+                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2, false>(a, L, L.mf);
+                    else sgd_steps_mfma<BITS, UPT, 2, 2, false>(a, L, L.mf);
                 }
             } else {
-                if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1>(a, L, L.mf);
-                else sgd_steps_mfma<BITS, UPT, 2, 1>(a, L, L.mf);
+                if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, false>(a, L, L.mf);
+                else sgd_steps_mfma<BITS, UPT, 2, 1, false>(a, L, L.mf);
             }
         } else if (affine) {
             sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
@@ -1013,7 +1032,14 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         kern = p.upt == 1 ? (const void *)k_sgd<BITS, INT, true, 1>
              : p.upt == 2 ? (const void *)k_sgd<BITS, INT, true, 2>
                           : (const void *)k_sgd<BITS, INT, true, 4>;
+        if constexpr (!INT && (BITS == 2 || BITS == 4 || BITS == 8)) {
+            if (a.R > 1)
+                kern = p.upt == 1 ? (const void *)k_sgd<BITS, false, true, 1, true>
+                     : p.upt == 2 ? (const void *)k_sgd<BITS, false, true, 2, true>
+                                  : (const void *)k_sgd<BITS, false, true, 4, true>;
+        }
     }
+    if (a.R > 1 && !(fast && !INT && (BITS == 2 || BITS == 4 || BITS == 8))) return ZIPML_EUNSUPPORTED;
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)p.shmem)))
         return ZIPML_ELAUNCH;

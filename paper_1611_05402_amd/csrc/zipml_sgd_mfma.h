@@ -127,7 +127,8 @@ constexpr int kRefresh = 16;   // steps between exact refreshes of the magnitude
 //     2 = its symmetrised form (Supp. A.4), 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)]: a
 //     second pair of packed arrays holds copy 1 sample-major and copy 2 feature-major, both
 //     pairs go through the same two passes at the same model, with one exchange for both.
-template <int BITS, int UPT, int KB, int NC>
+// REP: the chunks of a minibatch are shared out over replicas of the workgroups (a.R > 1).
+template <int BITS, int UPT, int KB, int NC, bool REP>
 __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, unsigned char *mf)
 {
     constexpr int HW = BITS / 2;                       // packed dwords per lane operand
@@ -145,7 +146,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const int n16 = lane & 15, q4 = lane >> 4;
     const int W = a.W, GQ = a.GQ, CW = 32 * GQ, B = a.B;
     const int w = blockIdx.x % W;                       // feature block of this workgroup
-    const int R = a.R, rep = blockIdx.x / W;            // replicas (see below), and which one this is
+    const int R = REP ? a.R : 1, rep = REP ? blockIdx.x / W : 0;   // replicas (see below), and which one this is
     const int j0 = w * CW;
     const int ngroups = (a.d32 - w * GQ) < GQ ? (a.d32 - w * GQ) : GQ;
     const int ntile = B / 16, NKS = B / 64;
@@ -376,7 +377,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         ZIPML_TICK(7);
         lds_barrier();          // digits of y and the per-tile sums of the current model
         ZIPML_TICK(0);
-        if (R > 1 && first && u > u_begin) {
+        if (REP && first && u > u_begin) {
             // the model has just moved by the gradient of all replicas: grow the bounds by the
             // largest residual any of them saw (left in LDS by the owner waves)
             const float rall = side[2];
@@ -536,7 +537,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         }
         rmax_step = fmaxf(rmax_step, Rmax);
         int ky_next = ky;
-        if (last && R == 1) {
+        if (last && !REP) {
             beta_hat += lr_abs * (lambda * rmax_step + l2_abs * beta_hat);
             ymax_hat += lr_abs * (mu * rmax_step + l2_abs * ymax_hat);
             ky_next = scale_of();
@@ -598,7 +599,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 if (owner) gsum += o_mid * Rtot + o_dl * fixed_to_float(G, kr);   // chunks in order
                 if (last) {
                     int ky_own = ky_next;
-                    if (R > 1) {
+                    if constexpr (REP) {
                         // ---- gradient exchange between the replicas of this feature block.  A
                         // 64-bit word carries, above the fp32 gradient share, a 16-bit tag of the
                         // step and an upper bound (8 significant bits) of the largest |residual|
