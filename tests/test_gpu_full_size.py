@@ -51,6 +51,21 @@ def test_dense8_full_size_codes_epoch_and_loss():
         l2_ref = oracle.loss_codes(c2, L, w.bits, b, x_ref)
         assert abs(p.loss(x, packed_copy=2) - l2_ref) <= TOL * l2_ref
     assert l_ref < 0.95 * oracle.loss(A, b, np.zeros(w.d, np.float32))   # the loss goes down
+    # the larger minibatches that bench.py's batch_sweep times on the same data: one exchange with
+    # four units per thread, chunks on replicas, and one step per epoch on the sample owners
+    for batch, lr in ((1024, 4e-3), (4096, 1.6e-2), (w.n, 0.25)):
+        say(f"full-size dense8: batch {batch}")
+        ws = torch.zeros(zipml.workspace_bytes(w.n, w.d, w.bits, batch), dtype=torch.uint8, device=DEV)
+        x_ref = np.zeros(w.d, np.float32)
+        x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        for ep in range(2):
+            x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, batch, lr)
+            zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, batch, lr, ws)
+            assert zipml.sgd_status(ws) == 0
+            err = rel_l2(x.cpu().numpy(), x_ref)
+            say(f"  epoch {ep}: rel L2 {err:.2e}")
+            assert err <= TOL
+        assert np.linalg.norm(x_ref) > 0
 
 
 # Sampled minibatch steps of the wide / long shapes: the oracle quantises and steps through the
