@@ -183,7 +183,18 @@ def grad_double(code1, code2, levels, bits, x, b):
     return g
 
 
-def sgd_epoch(codes1, codes2, levels, b, bits, x, batch, lr, symmetric=False, l2=0.0):
+PROX_NONE, PROX_L1, PROX_L2SQ, PROX_BOX = 0, 1, 2, 3
+
+
+def prox(v, kind, gamma, coef):
+    """Proximal operator of gamma * R at the scalar v (Sec. 2)."""
+    f = lib().zo_prox
+    f.restype = C.c_double
+    return float(f(C.c_double(v), C.c_int(kind), C.c_double(gamma), C.c_double(coef)))
+
+
+def sgd_epoch(codes1, codes2, levels, b, bits, x, batch, lr, symmetric=False, l2=0.0,
+              prox_kind=PROX_NONE, prox_coef=0.0):
     """One epoch in full-precision-model mode; returns the new fp32 model."""
     codes1 = np.ascontiguousarray(codes1, np.uint8)
     codes2 = np.ascontiguousarray(codes2, np.uint8)
@@ -192,7 +203,8 @@ def sgd_epoch(codes1, codes2, levels, b, bits, x, batch, lr, symmetric=False, l2
     n, d = codes1.shape
     lib().zo_sgd_epoch(_p(codes1), _p(codes2), _p(levels), _p(b), C.c_int64(n), C.c_int64(d),
                        C.c_int(bits), _p(x), C.c_int64(batch), C.c_float(lr),
-                       C.c_int(int(symmetric)), C.c_float(l2))
+                       C.c_int(int(symmetric)), C.c_float(l2), C.c_int(prox_kind),
+                       C.c_float(prox_coef))
     return x
 
 

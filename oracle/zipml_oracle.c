@@ -24,7 +24,10 @@
  * expectation and variance (b-x)(x-a); the paper's 0.7 -> {0,1} example;
  * naive-estimator bias = diag(err) x and double-sampled bias = 0 by full
  * enumeration; on-grid data == textbook minibatch SGD; convergence to the
- * normal-equations solution; DP == brute force over all level subsets.
+ * normal-equations solution; DP == brute force over all level subsets; the
+ * l2 term == textbook ridge SGD and its closed form; the proximal step ==
+ * brute-force minimisation of its definition and the lasso / ridge / box
+ * closed forms of an orthogonal design.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -384,9 +387,26 @@ void zo_grad_double(const uint8_t *code1, const uint8_t *code2, const float *lev
 /* With l2 = c the objective has the extra term (c/2)||x||^2 of the least-   */
 /* squares SVM (labels +-1) and a step is  x <- x - lr (g + c x).            */
 /* ------------------------------------------------------------------------- */
+/* Proximal operator of gamma * R at v (Sec. 2, the update x <- prox_{gamma R}(x - gamma g)):
+ * argmin_u 1/2 (u - v)^2 + gamma R(u), coordinate by coordinate, for the separable regularisers
+ *   kind 1: R(x) = coef * ||x||_1            -> soft threshold at gamma * coef
+ *   kind 2: R(x) = coef / 2 * ||x||_2^2      -> v / (1 + gamma * coef)
+ *   kind 3: R = indicator of ||x||_inf <= coef (a constraint) -> clamp to [-coef, coef]
+ *   kind 0: R = 0. */
+double zo_prox(double v, int kind, double gamma, double coef)
+{
+    if (kind == 1) {
+        double t = gamma * coef;
+        return v > t ? v - t : v < -t ? v + t : 0.0;
+    }
+    if (kind == 2) return v / (1.0 + gamma * coef);
+    if (kind == 3) return v > coef ? coef : v < -coef ? -coef : v;
+    return v;
+}
+
 void zo_sgd_epoch(const uint8_t *codes1, const uint8_t *codes2, const float *levels,
                   const float *b, int64_t n, int64_t d, int bits, float *x, int64_t batch,
-                  float lr, int symmetric, float l2)
+                  float lr, int symmetric, float l2, int prox, float prox_coef)
 {
     int K = 1 << bits;
     double *r2 = malloc(sizeof(double) * (size_t)batch); /* residuals from copy 2 */
@@ -417,8 +437,10 @@ void zo_sgd_epoch(const uint8_t *codes1, const uint8_t *codes2, const float *lev
         }
         /* l2 = c > 0: least-squares SVM, the gradient gets the additional term c x
          * ("Extension to Classification Models"). */
-        for (int64_t j = 0; j < d; ++j)
-            x[j] = (float)((double)x[j] - (double)lr * (g[j] + (double)l2 * (double)x[j]));
+        for (int64_t j = 0; j < d; ++j) {
+            double v = (double)x[j] - (double)lr * (g[j] + (double)l2 * (double)x[j]);
+            x[j] = (float)zo_prox(v, prox, (double)lr, (double)prox_coef);
+        }
     }
     free(r2); free(r1); free(g);
 }

@@ -128,6 +128,67 @@ def test_l2_term_reduces_to_textbook_ridge_sgd_and_its_closed_form():
     assert np.linalg.norm(avg - x_ridge) / np.linalg.norm(x_ridge) < 0.02
 
 
+# ------------------------------------------------------------------ proximal step
+def test_prox_is_the_minimiser_of_its_definition():
+    """prox_{gamma R}(v) = argmin_u 1/2 (u - v)^2 + gamma R(u) (Sec. 2): each kind against a
+    brute-force minimisation of that objective on a fine grid."""
+    rng = np.random.default_rng(12)
+    u = np.linspace(-4.0, 4.0, 800001)            # grid step 1e-5
+    for kind, R in ((oracle.PROX_L1, lambda u, c: c * np.abs(u)),
+                    (oracle.PROX_L2SQ, lambda u, c: 0.5 * c * u * u),
+                    (oracle.PROX_BOX, lambda u, c: np.where(np.abs(u) <= c, 0.0, np.inf))):
+        for _ in range(12):
+            v, gamma, c = rng.uniform(-3, 3), rng.uniform(0.05, 1.5), rng.uniform(0.1, 1.2)
+            best = u[np.argmin(0.5 * (u - v) ** 2 + gamma * R(u, c))]
+            assert abs(oracle.prox(v, kind, gamma, c) - best) <= 1.1e-5, (kind, v, gamma, c)
+    assert oracle.prox(1.25, oracle.PROX_NONE, 0.3, 0.7) == 1.25
+    # inside the threshold the l1 prox is exactly zero, and it is odd
+    assert oracle.prox(0.2, oracle.PROX_L1, 0.5, 0.5) == 0.0
+    assert oracle.prox(-0.7, oracle.PROX_L1, 0.5, 0.5) == -oracle.prox(0.7, oracle.PROX_L1, 0.5, 0.5)
+
+
+def test_prox_epoch_reaches_the_lasso_and_constrained_closed_forms():
+    """Orthogonal on-grid design (A^T A = n I, entries +-1 sit on the levels, so both quantisers
+    are the identity): with step 1 and one minibatch per epoch a single proximal step from any
+    start lands on the closed-form solution of
+      1/(2n)||Ax-b||^2 + lam ||x||_1       -> soft(A^T b / n, lam)
+      1/(2n)||Ax-b||^2 + lam/2 ||x||^2     -> (A^T b / n) / (1 + lam)
+      1/(2n)||Ax-b||^2  s.t. ||x||_inf <= lam -> clip(A^T b / n, -lam, lam)."""
+    n, d, bits = 64, 8, 1
+    H = np.array([[1.0]])
+    while H.shape[0] < n:
+        H = np.block([[H, H], [H, -H]])
+    A = H[:, 1:d + 1].astype(np.float32)                       # orthogonal +-1 columns
+    assert np.array_equal(A.T @ A, n * np.eye(d, dtype=np.float32))
+    rng = np.random.default_rng(5)
+    xs = np.array([2.0, -1.5, 0.3, -0.2, 0.0, 0.9, -0.05, 0.6])
+    b = (A @ xs + 0.3 * rng.standard_normal(n)).astype(np.float32)
+    L = oracle.levels_uniform([-1] * d, [1] * d, bits)
+    c1, c2 = oracle.quantize(A, L, bits, seed=3, epoch=0)
+    assert np.array_equal(np.take_along_axis(L.T, c1.astype(np.int64), axis=0), A)   # identity quantiser
+    z = A.astype(np.float64).T @ b / n
+    lam = 0.4
+    x0 = rng.standard_normal(d).astype(np.float32)
+    expect = {oracle.PROX_L1: np.sign(z) * np.maximum(np.abs(z) - lam, 0.0),
+              oracle.PROX_L2SQ: z / (1.0 + lam),
+              oracle.PROX_BOX: np.clip(z, -lam, lam),
+              oracle.PROX_NONE: z}
+    for kind, want in expect.items():
+        got = oracle.sgd_epoch(c1, c2, L, b, bits, x0, n, 1.0, prox_kind=kind, prox_coef=lam)
+        assert np.allclose(got, want, rtol=0, atol=2e-6), kind
+    assert np.count_nonzero(expect[oracle.PROX_L1] == 0) >= 2      # the l1 solution is sparse here
+    # minibatches: textbook proximal SGD in NumPy, step by step
+    batch, lr = 16, 0.1
+    x = x0.astype(np.float64)
+    for t in range(n // batch):
+        Ab = A[t * batch:(t + 1) * batch].astype(np.float64)
+        g = Ab.T @ (Ab @ x - b[t * batch:(t + 1) * batch]) / batch
+        v = x - lr * g
+        x = (np.sign(v) * np.maximum(np.abs(v) - lr * lam, 0.0)).astype(np.float32).astype(np.float64)
+    got = oracle.sgd_epoch(c1, c2, L, b, bits, x0, batch, lr, prox_kind=oracle.PROX_L1, prox_coef=lam)
+    assert np.allclose(got, x, rtol=0, atol=1e-6)
+
+
 # ------------------------------------------------------------------ epoch: convergence
 def test_converges_to_least_squares_solution_and_naive_does_not():
     """Double-sampled SGD with a diminishing step reaches (A^T A)^-1 A^T b (Sec. 5.1);
