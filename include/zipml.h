@@ -148,6 +148,25 @@ int zipml_sgd_epoch_l2(void *stream, const void *packed1_dev, const void *packed
                        float *x_dev, int64_t batch, float lr, float l2, int flags,
                        void *workspace_dev, size_t workspace_bytes);
 
+/* The same epoch with the proximal step of the general update of Sec. 2,
+ *   x <- prox_{lr R}( x - lr * (g + l2 * x) ),  prox_{lr R}(v) = argmin_u 1/2 ||u - v||^2 + lr R(u),
+ * for the regularisers that act coordinate by coordinate:
+ *   ZIPML_PROX_L1    R(x) = prox_coef * ||x||_1          (soft threshold at lr * prox_coef)
+ *   ZIPML_PROX_L2SQ  R(x) = prox_coef / 2 * ||x||_2^2    (v / (1 + lr * prox_coef))
+ *   ZIPML_PROX_BOX   the constraint ||x||_inf <= prox_coef (clamp)
+ *   ZIPML_PROX_NONE  R = 0 (then the call is zipml_sgd_epoch_l2).
+ * Full-precision (fp32) model only; prox_coef >= 0; everything else as in zipml_sgd_epoch_l2.
+ * (Regularisers that need a norm of the whole model -- the unsquared l2 norm, an l2 ball -- are
+ * not provided.) */
+#define ZIPML_PROX_NONE 0
+#define ZIPML_PROX_L1   1
+#define ZIPML_PROX_L2SQ 2
+#define ZIPML_PROX_BOX  3
+int zipml_sgd_epoch_prox(void *stream, const void *packed1_dev, const void *packed2_dev,
+                         const float *levels_dev, const float *b_dev, int64_t n, int64_t d, int bits,
+                         float *x_dev, int64_t batch, float lr, float l2, int prox, float prox_coef,
+                         int flags, void *workspace_dev, size_t workspace_bytes);
+
 /* The same epoch with the symmetrised estimator (Supp. A.4: lower variance at no extra
  * randomness; the form the authors report running):
  *   g = 1/2 mean_i [ Q1(a_i) (Q2(a_i)^T x - b_i) + Q2(a_i) (Q1(a_i)^T x - b_i) ],

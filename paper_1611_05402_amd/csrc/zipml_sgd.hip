@@ -89,6 +89,8 @@ struct SgdArgs {
     int nsteps;
     float lr, grid_lo, grid_step;
     float l2;              // coefficient c of the extra gradient term c * x (least-squares SVM)
+    int prox;              // proximal step after the update (ZIPML_PROX_*), fp32 model only
+    float prox_coef;
     int grad_bits, model_bits;
     int ident_grid;        // grid_idx[j][c] == c
     uint64_t seed;
@@ -116,6 +118,21 @@ struct SgdArgs {
     int32_t *dbg_m, *dbg_acc, *dbg_gq;
     float *dbg_r, *dbg_g;
 };
+
+// Proximal operator of lr * R at v, coordinate-wise (Sec. 2, x <- prox_{gamma R}(x - gamma g)):
+// l1 norm -> soft threshold at lr * coef; coef/2 ||x||^2 -> v / (1 + lr * coef); the constraint
+// ||x||_inf <= coef -> clamp.  None of them increases |v|, so the magnitude bounds that the step
+// loops track for the model stay valid.
+__device__ __forceinline__ float apply_prox(float v, int kind, float lr, float coef)
+{
+    if (kind == ZIPML_PROX_L1) {
+        const float t = lr * coef;
+        return v > t ? v - t : v < -t ? v + t : 0.0f;
+    }
+    if (kind == ZIPML_PROX_L2SQ) return __fdiv_rn(v, 1.0f + lr * coef);
+    if (kind == ZIPML_PROX_BOX) return fminf(fmaxf(v, -coef), coef);
+    return v;
+}
 
 // LDS arrays of one workgroup.
 struct Lds {
@@ -716,7 +733,8 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
         } else if (tid < CW) {
             const float reg = a.l2 * xs[tid];
             const float stp = a.lr * (gs[tid] + reg);
-            xs[tid] = xs[tid] - stp;
+            const float v = xs[tid] - stp;
+            xs[tid] = a.prox ? apply_prox(v, a.prox, a.lr, a.prox_coef) : v;
         }
         if (MODE == kAffine) {
             // the owner threads refresh y = delta * x and the per-wave parts of sum_j lo_j x_j
@@ -1137,9 +1155,14 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
                    float *x_dev, int64_t batch, float lr, float l2, int grad_bits, int model_bits,
                    uint64_t seed, uint32_t epoch, int flags, int64_t step0, int64_t nsteps,
                    int32_t *dbg_m, int32_t *dbg_acc, float *dbg_r, float *dbg_g, int32_t *dbg_gq,
-                   void *workspace_dev, size_t workspace_bytes)
+                   void *workspace_dev, size_t workspace_bytes, int prox = ZIPML_PROX_NONE,
+                   float prox_coef = 0.0f)
 {
     if (!packed1_dev || !packed2_dev || !levels_dev || !b_dev || !x_dev) return ZIPML_EINVAL;
+    if (prox != ZIPML_PROX_NONE && prox != ZIPML_PROX_L1 && prox != ZIPML_PROX_L2SQ && prox != ZIPML_PROX_BOX)
+        return ZIPML_EINVAL;
+    if (prox != ZIPML_PROX_NONE && !(prox_coef >= 0.0f)) return ZIPML_EINVAL;
+    if (prox != ZIPML_PROX_NONE && model_bits > 0) return ZIPML_EUNSUPPORTED;   // fp32 model only
     if (n <= 0 || d <= 0 || !valid_bits(bits) || batch <= 0 || n % batch != 0) return ZIPML_EINVAL;
     if (!(batch == 4 || batch == 8 || batch == 16 || batch % 32 == 0)) return ZIPML_EINVAL;
     if (n > (int64_t)1 << 40 || d > (1 << 24)) return ZIPML_EINVAL;
@@ -1266,6 +1289,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
             r.nsteps = (int)nsteps;
             r.lr = lr;
             r.l2 = l2;
+            r.prox = prox;
+            r.prox_coef = prox_coef;
             r.status = (int *)(wsb + Workspace::kStatus);
             r.sync = (uint32_t *)(wsb + Workspace::kSync);
             r.even = (const int *)(wsb + Workspace::kEven);
@@ -1309,6 +1334,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.nsteps = (int)nsteps;
     a.lr = lr;
     a.l2 = l2;
+    a.prox = prox;
+    a.prox_coef = prox_coef;
     a.grid_lo = grid_lo;
     a.grid_step = grid_step;
     a.grad_bits = grad_bits;
@@ -1376,6 +1403,18 @@ extern "C" int zipml_sgd_epoch_l2(void *stream, const void *packed1_dev, const v
     return run_sgd(stream, packed1_dev, packed2_dev, nullptr, nullptr, levels_dev, nullptr, 0.0f, 0.0f,
                    0, b_dev, n, d, bits, x_dev, batch, lr, l2, 0, 0, 0, 0, flags, 0, steps, nullptr,
                    nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes);
+}
+
+extern "C" int zipml_sgd_epoch_prox(void *stream, const void *packed1_dev, const void *packed2_dev,
+                                    const float *levels_dev, const float *b_dev, int64_t n, int64_t d,
+                                    int bits, float *x_dev, int64_t batch, float lr, float l2,
+                                    int prox, float prox_coef, int flags, void *workspace_dev,
+                                    size_t workspace_bytes)
+{
+    const int64_t steps = (batch > 0 && n > 0 && n % batch == 0) ? n / batch : 0;
+    return run_sgd(stream, packed1_dev, packed2_dev, nullptr, nullptr, levels_dev, nullptr, 0.0f, 0.0f,
+                   0, b_dev, n, d, bits, x_dev, batch, lr, l2, 0, 0, 0, 0, flags, 0, steps, nullptr,
+                   nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes, prox, prox_coef);
 }
 
 extern "C" int zipml_sgd_epoch_avg(void *stream, const void *packed1_dev, const void *packed2_dev,

@@ -656,6 +656,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                         const float reg = a.l2 * x_own;
                         const float stp = a.lr * (g + reg);
                         x_own = x_own - stp;
+                        if (a.prox) x_own = apply_prox(x_own, a.prox, a.lr, a.prox_coef);
                         xnew = x_own;
                     }
                     gsum = 0.0f;

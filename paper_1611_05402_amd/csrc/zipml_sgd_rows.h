@@ -34,6 +34,8 @@ struct RowsArgs {
     int64_t step0;
     int nsteps;
     float lr, l2;
+    int prox;                // proximal step after the update (ZIPML_PROX_*)
+    float prox_coef;
     int *status;
     uint32_t *sync;
     const int *even;         // [kEvenBlocks] from k_sgd_prepare
@@ -330,7 +332,8 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
                     const float g = __fdiv_rn(a.mid[j] * Rtot + a.dl[j] * G, (float)a.B);
                     const float reg = a.l2 * xj;
                     const float stp = a.lr * (g + reg);
-                    store_dev(a.x + j, xj - stp);
+                    const float v = xj - stp;
+                    store_dev(a.x + j, a.prox ? apply_prox(v, a.prox, a.lr, a.prox_coef) : v);
                 }
             }
         }

@@ -16,12 +16,13 @@ LIB_PATH = os.path.join(HERE, "libzipml.so")
 UNIFORM, OPTIMAL = 0, 1
 RANGE_GIVEN, SYMMETRIC = 1, 2
 SGD_STEPWISE, SGD_AVERAGED = 1, 2
+PROX_NONE, PROX_L1, PROX_L2SQ, PROX_BOX = 0, 1, 2, 3
 
 OK, EINVAL, EALIGN, ERANGE, EWORKSPACE, ELAUNCH, EUNSUPPORTED, ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = ["zipml_strerror", "zipml_packed_bytes", "zipml_workspace_bytes", "zipml_levels",
            "zipml_quantize", "zipml_quantize_swapped", "zipml_sgd_epoch", "zipml_sgd_epoch_l2",
-           "zipml_sgd_epoch_avg", "zipml_sgd_status", "zipml_loss",
+           "zipml_sgd_epoch_prox", "zipml_sgd_epoch_avg", "zipml_sgd_status", "zipml_loss",
            "zipml_unpack_codes", "zipml_debug_step"]
 
 
@@ -68,6 +69,9 @@ def lib() -> C.CDLL:
         L.zipml_sgd_epoch.argtypes = sgd + [i32, vp, sz]
         L.zipml_sgd_epoch_l2.restype = i32
         L.zipml_sgd_epoch_l2.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, i64, f32, f32, i32, vp, sz]
+        L.zipml_sgd_epoch_prox.restype = i32
+        L.zipml_sgd_epoch_prox.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, i64, f32, f32, i32, f32,
+                                           i32, vp, sz]
         L.zipml_debug_step.restype = i32
         L.zipml_debug_step.argtypes = sgd + [i64, i32, vp, vp, vp, vp, vp, vp, sz]
         L.zipml_sgd_status.restype = i32
@@ -155,6 +159,15 @@ def sgd_epoch_l2(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, l2, wo
                                     _ptr(b), n, d, bits, _ptr(x), batch, lr, l2, flags,
                                     _ptr(workspace), workspace.numel() * workspace.element_size()),
            "zipml_sgd_epoch_l2")
+
+
+def sgd_epoch_prox(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, prox, prox_coef,
+                   workspace, *, l2=0.0, flags=0, stream=None):
+    _check(lib().zipml_sgd_epoch_prox(_stream(stream), _ptr(packed1), _ptr(packed2), _ptr(levels_t),
+                                      _ptr(b), n, d, bits, _ptr(x), batch, lr, l2, prox, prox_coef,
+                                      flags, _ptr(workspace),
+                                      workspace.numel() * workspace.element_size()),
+           "zipml_sgd_epoch_prox")
 
 
 def sgd_epoch_avg(packed1, packed2, packed1s, packed2s, levels_t, b, n, d, bits, x, batch, lr,

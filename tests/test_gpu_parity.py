@@ -567,6 +567,71 @@ def test_least_squares_svm_epochs_match_oracle(name, kw):
     assert e.value.code == zipml.EINVAL
 
 
+# ------------------------------------------------------------------ proximal step
+@pytest.mark.parametrize("name,factory,kw,lr", [
+    ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256), 0.02),          # matrix-core loop
+    ("b5_wide", synth.tiny, dict(n=2048, d=1056, batch=64, bits=5), 0.01),          # vector loop
+    ("tiny_one_workgroup", synth.tiny, dict(n=2048, d=64, batch=16, bits=4), 0.01),  # no exchange
+    ("dense8_replicas", synth.dense8, dict(n=8192, d=288, batch=4096), 0.1),        # chunks on replicas
+    ("dense8_sample_owners", synth.dense8, dict(n=16384, d=288, batch=16384), 0.2),
+])
+@pytest.mark.parametrize("kind,coef", [(zipml.PROX_L1, 0.05), (zipml.PROX_L2SQ, 0.5), (zipml.PROX_BOX, 0.04)])
+def test_proximal_step_matches_oracle(name, factory, kw, lr, kind, coef, monkeypatch):
+    """x <- prox_{lr R}(x - lr g) (Sec. 2) on every step loop, for the three regularisers."""
+    say("prox", name, kind)
+    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")
+    w = factory(**kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L)
+    p.quantize(13, 0)
+    c1, c2 = oracle.quantize(A, L, w.bits, 13, 0)
+    plain = np.zeros(w.d, np.float32)
+    for ep in range(3):
+        plain = oracle.sgd_epoch(c1, c2, L, b, w.bits, plain, w.batch, lr)
+    if kind == zipml.PROX_BOX:
+        coef = float(np.float32(0.5 * np.abs(plain).max()))     # a box that the run does hit
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(3):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, lr, prox_kind=kind, prox_coef=coef)
+        zipml.sgd_epoch_prox(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, lr, kind, coef, p.ws)
+        assert zipml.sgd_status(p.ws) == 0
+        err = rel_l2(x.cpu().numpy(), x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}")
+        assert err <= TOL
+    xg = x.cpu().numpy()
+    assert rel_l2(x_ref, plain) > 1e-4      # the step matters
+    if kind == zipml.PROX_L1:
+        # the soft threshold leaves exact zeros, the same ones on both sides up to coordinates
+        # that sit at the threshold
+        z_ref, z_gpu = x_ref == 0, xg == 0
+        assert np.mean(z_ref != z_gpu) <= 0.01
+        if name.startswith("dense8"):            # small true weights: many are thresholded away
+            assert z_ref.sum() > 0
+    if kind == zipml.PROX_BOX:
+        assert np.abs(xg).max() <= np.float32(coef) and (np.abs(xg) == np.float32(coef)).sum() > 0
+
+
+def test_proximal_step_refusals():
+    w = synth.tiny(n=1024, d=64, batch=16, bits=4)
+    A, b = w.full()
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(_levels_for(w, A))
+    p.quantize(1, 0)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for kind, coef in ((7, 0.1), (zipml.PROX_L1, -0.1)):
+        with pytest.raises(zipml.ZipmlError) as e:
+            zipml.sgd_epoch_prox(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 0.01, kind, coef, p.ws)
+        assert e.value.code == zipml.EINVAL
+    # no regulariser: the same bits as the plain entry point
+    y = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    zipml.sgd_epoch_prox(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 0.01, zipml.PROX_NONE, 0.0, p.ws)
+    p.epoch(y, 0.01)
+    assert torch.equal(x, y)
+
+
 # ------------------------------------------------------------------ failure handling
 @pytest.mark.parametrize("name,factory,kw", [
     ("dense8_small", synth.dense8, dict(n=4096, d=288, batch=256)),          # matrix-core loop
