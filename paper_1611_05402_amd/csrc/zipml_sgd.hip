@@ -925,7 +925,7 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
         ok = __syncthreads_and(ok);
         if (threadIdx.x == 0) even[blockIdx.x] = ok;
     }
-    if (blockIdx.x != 0) return;
+    if (blockIdx.x != 0 || !bound) return;     // (the sample-owner kernel takes its scales from the data)
     double pb = 0.0, pl = 0.0, py = 0.0, pm = 0.0;
     for (int j = threadIdx.x; j < d; j += 256) {
         const double lo = (double)levels[(size_t)j * K], hi = (double)levels[(size_t)j * K + K - 1];
@@ -1113,32 +1113,32 @@ static int launch_sgd_mode(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwi
 
 // Sample-owner kernel for very large minibatches (zipml_sgd_rows.h).
 template <int BITS>
-static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs, double *bound,
-                       int *even, uint64_t *acc)
+static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs, int *even, uint64_t *acc)
 {
     const int K = 1 << BITS;
     const int nfeat = r.NKB * 64;
     const size_t shmem = rows_lds_bytes(r.NKB);
     // blocks per wave and item: as many as the registers hold, fewer for narrow problems
-    int kpi = 16 / BITS;
-    if (const char *env = getenv("ZIPML_ROWS_KPI")) {   // tuning override: at most this many
+    // (measured: short items are best at 4 and 8 bits, 5.8-5.9 TB/s; 2-bit codes want two blocks)
+    int kpi = BITS == 2 ? 2 : 1;
+    if (const char *env = getenv("ZIPML_ROWS_KPI")) {   // tuning override (at most 32 / BITS)
         const int v = atoi(env);
-        if (v >= 1 && v < kpi) kpi = v;
+        if (v >= 1 && v <= 32 / BITS) kpi = v;
     }
     while (kpi > 1 && (r.NKB < kWaves * kpi || (kpi & (kpi - 1)))) --kpi;
     const void *kern = nullptr;
-    if constexpr (BITS == 8) kern = kpi == 2 ? (const void *)k_sgd_rows<8, 2> : (const void *)k_sgd_rows<8, 1>;
+    if constexpr (BITS == 8) kern = kpi >= 2 ? (const void *)k_sgd_rows<8, 2> : (const void *)k_sgd_rows<8, 1>;
     if constexpr (BITS == 4)
-        kern = kpi == 4 ? (const void *)k_sgd_rows<4, 4> : kpi == 2 ? (const void *)k_sgd_rows<4, 2>
+        kern = kpi >= 4 ? (const void *)k_sgd_rows<4, 4> : kpi == 2 ? (const void *)k_sgd_rows<4, 2>
                                                                    : (const void *)k_sgd_rows<4, 1>;
     if constexpr (BITS == 2)
-        kern = kpi == 8 ? (const void *)k_sgd_rows<2, 8> : kpi == 4 ? (const void *)k_sgd_rows<2, 4>
-             : kpi == 2 ? (const void *)k_sgd_rows<2, 2> : (const void *)k_sgd_rows<2, 1>;
+        kern = kpi >= 4 ? (const void *)k_sgd_rows<2, 4> : kpi == 2 ? (const void *)k_sgd_rows<2, 2>
+                                                                   : (const void *)k_sgd_rows<2, 1>;
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
         return ZIPML_ELAUNCH;
     // status word, barrier counter, evenly-spaced check (no exchange words to clear)
     hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, r.status, r.sync,
-                       acc, 0, 1, levels, r.x, r.d, K, bound, even);
+                       acc, 0, 1, levels, r.x, r.d, K, (double *)nullptr, even);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     hipLaunchKernelGGL(k_rows_prepare, dim3((nfeat + 255) / 256), dim3(256), 0, s, levels, r.d, K, nfeat,
                        BITS == 8 ? 128.0f : 0.0f, const_cast<float *>(r.dl), const_cast<float *>(r.mid));
@@ -1299,13 +1299,12 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
                 const long v = atol(env);
                 if (v >= 0 && v <= (long)kSpinLimit) r.spin_limit = (uint32_t)v;
             }
-            double *bound = (double *)(wsb + Workspace::kBound);
             int *even = (int *)(wsb + Workspace::kEven);
             uint64_t *acc = (uint64_t *)(wsb + Workspace::kAcc);
             switch (bits) {
-                case 2: return launch_rows<2>(s, r, levels_dev, wgs, bound, even, acc);
-                case 4: return launch_rows<4>(s, r, levels_dev, wgs, bound, even, acc);
-                case 8: return launch_rows<8>(s, r, levels_dev, wgs, bound, even, acc);
+                case 2: return launch_rows<2>(s, r, levels_dev, wgs, even, acc);
+                case 4: return launch_rows<4>(s, r, levels_dev, wgs, even, acc);
+                case 8: return launch_rows<8>(s, r, levels_dev, wgs, even, acc);
             }
         }
     }
