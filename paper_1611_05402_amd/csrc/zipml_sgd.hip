@@ -774,6 +774,13 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     const int nrg = B >= 32 ? B / 32 : 1;
     const int Rlen = nrg * 32;                     // residual slots (zero outside the batch)
     const int j0 = w * CW;
+#ifdef ZIPML_PHASE_TIMING
+    // where this workgroup runs: XCC id (HW_REG_XCC_ID) and the HW_ID register (SE / CU / SIMD fields)
+    if (tid == 0) {
+        ((long long *)(a.nrm + 2048))[16 + 2 * blockIdx.x] = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);
+        ((long long *)(a.nrm + 2048))[17 + 2 * blockIdx.x] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);
+    }
+#endif
 
     size_t off = 0;
     auto carve = [&](size_t bytes) { void *p = smem + off; off += (bytes + 15) & ~(size_t)15; return p; };
@@ -888,7 +895,8 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
 }
 
 // Launch preparation: clears the barrier counter, the status word and exchange words, checks
-// block by block whether the levels are evenly spaced; block 0 also takes the two magnitude bounds of the dot exchange from the levels and the current model,
+// block by block (kEvenBlocks of them) whether the levels are evenly spaced; one more block takes
+// the magnitude bounds of the dot exchange from the levels and the current model,
 //   bound[0] = sum_j maxabs(L_j) |x_j|,   bound[1] = sum_j maxabs(L_j)^2,
 //   bound[2] = max_j delta_j |x_j|,       bound[3] = max_j delta_j maxabs(L_j),
 // (delta_j: spacing of evenly spaced levels) in fp64 with a fixed order.
@@ -925,7 +933,8 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
         ok = __syncthreads_and(ok);
         if (threadIdx.x == 0) even[blockIdx.x] = ok;
     }
-    if (blockIdx.x != 0 || !bound) return;     // (the sample-owner kernel takes its scales from the data)
+    // one more block takes the magnitude bounds (the sample-owner kernel takes its scales from the data)
+    if (blockIdx.x != Workspace::kEvenBlocks || !bound) return;
     double pb = 0.0, pl = 0.0, py = 0.0, pm = 0.0;
     for (int j = threadIdx.x; j < d; j += 256) {
         const double lo = (double)levels[(size_t)j * K], hi = (double)levels[(size_t)j * K + K - 1];
@@ -1065,7 +1074,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     const int words = a.R * Workspace::kAccBuffers * a.acc_words + (a.R > 1 ? 2 * (int)Workspace::kGradWords : 0);
     const int K = 1 << BITS;
     double *bound = const_cast<double *>(a.bound);
-    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, a.status, a.sync,
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, a.status, a.sync,
                        a.acc, words, 1, a.levels, a.x, a.d, K, bound,
                        a.mfma ? const_cast<int *>(a.even) : nullptr);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
@@ -1088,7 +1097,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         // the exchange buffer that step t uses was last used by step t-4: clear it; the magnitude
         // bounds are taken from the model as it stands before this step
         uint64_t *acct = a.acc + (size_t)(t & 3) * a.acc_words;
-        hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, a.status,
+        hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, a.status,
                            a.sync, acct, a.acc_words, 0, a.levels, a.x, a.d, K, bound, nullptr);
         for (int seg = 0; seg <= 3; ++seg) {
             if (seg == 0 && a.model_bits == 0) continue;
@@ -1137,7 +1146,7 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
         return ZIPML_ELAUNCH;
     // status word, barrier counter, evenly-spaced check (no exchange words to clear)
-    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks), dim3(256), 0, s, r.status, r.sync,
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, r.status, r.sync,
                        acc, 0, 1, levels, r.x, r.d, K, (double *)nullptr, even);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     hipLaunchKernelGGL(k_rows_prepare, dim3((nfeat + 255) / 256), dim3(256), 0, s, levels, r.d, K, nfeat,
