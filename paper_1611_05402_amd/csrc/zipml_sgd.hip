@@ -1368,6 +1368,15 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.even = (const int *)(ws + Workspace::kEven);
     a.acc_words = (int)Workspace::acc_words(micro);
     a.gx = a.acc + (size_t)replicas * Workspace::kAccBuffers * a.acc_words;
+    // the exchange buffers of all replicas and the gradient exchange words must fit what
+    // zipml_workspace_bytes provides for this batch (they do by construction: checked anyway)
+    {
+        const size_t used = ((size_t)replicas * Workspace::kAccBuffers * a.acc_words +
+                             (replicas > 1 ? 2 * Workspace::kGradWords : 0)) * 8;
+        if (Workspace::kAcc + used > Workspace::sgd_bytes(batch) ||
+            (replicas > 1 && (size_t)replicas * p.W * 32 * p.GQ > Workspace::kGradWords))
+            return ZIPML_EWORKSPACE;
+    }
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
     switch (bits) {

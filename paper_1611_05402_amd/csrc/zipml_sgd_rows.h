@@ -182,7 +182,15 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
     // The packed data do not depend on the model: the first item of a step is requested before the
     // previous step's gradients are added up (here: before the first step's model is read).
     if (p < NT) issue(a.step0 * a.B + 64 * (int64_t)p, 0, buf0);
+#ifdef ZIPML_PHASE_TIMING
+    long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long last_ = wall_clock64();
+#define ZIPML_RTICK(k) do { if (p == 0 && tid == 0) { const long long now_ = wall_clock64(); prof_[k] += now_ - last_; last_ = now_; } } while (0)
+#else
+#define ZIPML_RTICK(k) do { } while (0)
+#endif
     for (int64_t t = a.step0; t < t_end; ++t) {
+        ZIPML_RTICK(5);
         // ============ the model of this step: digits of y_j = delta_j x_j, sum_j mid_j x_j
         // (the model was written by other workgroups: device-scope loads, four in flight per thread;
         // y_j waits in the gradient array until the scale is known)
@@ -222,8 +230,13 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
         }
         float rtot = 0.0f;                     // wave 0: sum of this workgroup's residuals
         __syncthreads();
+        ZIPML_RTICK(0);
 
-        // ============ tiles of 64 samples: dot pass, residuals, gradient pass
+        // ============ tiles of 64 samples: dot pass, residuals, gradient pass.  The tiles are
+        // dealt out in turn (tile T to workgroup T mod P).  Handing them out by a counter instead
+        // was tried: it costs an atomic per tile, makes the order of the fp32 sums -- and with it
+        // the last bits of the result -- depend on timing, and gained nothing: the workgroups
+        // finish within one tile of each other either way.
         for (int64_t T = p; T < NT; T += P) {
             const int64_t row0 = t * a.B + 64 * T;
             const float label = a.b[row0 + lane];      // (every wave: no load behind a branch)
@@ -294,43 +307,48 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
         }
 
         // ============ gradients of all workgroups -> model
+        ZIPML_RTICK(1);
         __syncthreads();
         float *const mine = a.part + (size_t)p * nfeat;
         for (int j = tid; j < nfeat; j += kThreads) store_dev(mine + j, gs[j]);
         if (tid == 0) store_dev(a.part + (size_t)P * nfeat + p, rtot);
         grid_sync();
+        ZIPML_RTICK(2);
         {
-            // sum of all residuals: every wave adds the P numbers in the same order
-            float rs = 0.0f;
-            for (int q0 = 0; q0 < P; q0 += 4 * kWave) {
+            // A wave sums 16 features over all workgroups: lane (n16, q4) takes workgroups q4,
+            // q4 + 4, ...  Everything it needs -- up to 64 partial gradients per lane, its share of
+            // the sums of residuals, the model -- is requested in one go; all sums are taken in a
+            // fixed order.
+            const int nblk = nfeat / 16;
+            const float *const rsum_all = a.part + (size_t)P * nfeat;
+            for (int jb = p * kWaves + wave; jb < nblk; jb += P * kWaves) {
+                const int j = jb * 16 + n16;
+                const float xj = load_dev(a.x + (j < a.d ? j : 0));
                 float rv[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int q = q0 + lane + e * kWave;
-                    rv[e] = q < P ? load_dev(a.part + (size_t)P * nfeat + q) : 0.0f;
+                    const int q = lane + e * kWave;
+                    rv[e] = load_dev(rsum_all + (q < P ? q : P - 1));
+                    rv[e] = q < P ? rv[e] : 0.0f;
                 }
-                rs += (rv[0] + rv[1]) + (rv[2] + rv[3]);
-            }
-            const float Rtot = wave_sum_dpp(rs);
-            // a wave sums 16 features over all workgroups: lane (n16, q4) takes workgroups q4, q4 + 4, ...
-            const int nblk = nfeat / 16;
-            for (int jb = p * kWaves + wave; jb < nblk; jb += P * kWaves) {
-                const int j = jb * 16 + n16;
                 float s = 0.0f;
-                int q = q4;
-                for (; q + 124 < P; q += 128) {          // thirty-two loads in flight
-                    float v[32];
+                for (int q0 = q4; q0 < P; q0 += 256) {      // (one round for up to 256 workgroups)
+                    float v[64];
 #pragma unroll
-                    for (int e = 0; e < 32; ++e) v[e] = load_dev(a.part + (size_t)(q + 4 * e) * nfeat + j);
+                    for (int e = 0; e < 64; ++e) {
+                        const int q = q0 + 4 * e;
+                        v[e] = load_dev(a.part + (size_t)(q < P ? q : P - 1) * nfeat + j);
+                    }
 #pragma unroll
-                    for (int e = 0; e < 32; ++e) s += v[e];
+                    for (int e = 0; e < 64; ++e) s += q0 + 4 * e < P ? v[e] : 0.0f;
                 }
-                for (; q < P; q += 4) s += load_dev(a.part + (size_t)q * nfeat + j);
+                float rs = (rv[0] + rv[1]) + (rv[2] + rv[3]);
+                for (int q = lane + 4 * kWave; q < P; q += kWave) rs += load_dev(rsum_all + q);   // (more than 256 workgroups)
+                const float Rtot = wave_sum_dpp(rs);
                 const float s0 = __shfl(s, n16, kWave), s1 = __shfl(s, 16 + n16, kWave);
                 const float s2 = __shfl(s, 32 + n16, kWave), s3 = __shfl(s, 48 + n16, kWave);
                 const float G = (s0 + s1) + (s2 + s3);
                 if (q4 == 0 && j < a.d) {
-                    const float xj = load_dev(a.x + j);
                     const float g = __fdiv_rn(a.mid[j] * Rtot + a.dl[j] * G, (float)a.B);
                     const float reg = a.l2 * xj;
                     const float stp = a.lr * (g + reg);
@@ -339,8 +357,14 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
                 }
             }
         }
+        ZIPML_RTICK(3);
         grid_sync();
+        ZIPML_RTICK(4);
     }
+#ifdef ZIPML_PHASE_TIMING
+    if (p == 0 && tid == 0)
+        for (int k = 0; k < 8; ++k) ((long long *)(a.part + (size_t)P * nfeat + P))[k] = prof_[k];   // spare words behind the sums
+#endif
 }
 
 template <int BITS, int KPI>
