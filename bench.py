@@ -170,6 +170,16 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    # ---- what a plain streaming read reaches on this machine: the library's fp32 loss kernel (reads
+    # 4 n d bytes once, nothing else) over 2 GiB
+    n_c = (2 << 30) // (4 * d)
+    A_c = torch.empty(n_c, d, dtype=torch.float32, device=dev).normal_()
+    b_c = torch.zeros(n_c, dtype=torch.float32, device=dev)
+    ws_c = torch.zeros(zipml.workspace_bytes(n_c, d, bits, B), dtype=torch.uint8, device=dev)
+    ceil_ms = timed(lambda: zipml.loss(b_c, x, n_c, d, ws_c, A=A_c, lda=d), reps=5)
+    read_ceiling = 4.0 * n_c * d / (ceil_ms * 1e-3) / 1e9
+    del A_c, b_c, ws_c
+
     # ---- the same epoch at larger minibatches (same resident data; not part of `value`):
     # 4x, 16x and the whole data set per step, and the whole-data-set step on 8x the samples
     # (random codes: only the rate matters there)
@@ -182,7 +192,8 @@ def main():
         assert zipml.sgd_status(wss) == 0
         nbytes = nn * (2 * d * bits / 8 + 4)
         sweep.append({"n": nn, "batch": batch, "ms_per_epoch": ms, "us_per_step": ms * 1e3 / (nn // batch),
-                      "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
+                      "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "frac_of_measured_read_ceiling": nbytes / (ms * 1e-3) / 1e9 / read_ceiling})
 
     if not args.batch:
         for mult in (4, 16):
@@ -221,7 +232,9 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(w.name, B),
                      "kernel": f"k_sgd<{bits}> (persistent epoch kernel)",
-                     "kernel_ms": kern_ms, "us_per_minibatch_step": kern_ms * 1e3 / (n // B)},
+                     "kernel_ms": kern_ms, "us_per_minibatch_step": kern_ms * 1e3 / (n // B),
+                     "measured_read_ceiling_GBps": read_ceiling,
+                     "frac_of_measured_read_ceiling": achieved / read_ceiling},
         "other_ms": {"levels": levels_ms, "quantize": quant_ms, "loss_fp32": loss_ms,
                      "loss_packed": loss_p_ms, "generate_and_upload_s": gen_s},
         "batch_sweep": sweep,
