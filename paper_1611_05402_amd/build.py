@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libzipml.so")
 SOURCES = ["zipml_quantize.hip", "zipml_sgd.hip", "zipml_loss.hip", "zipml_levels.hip"]
-HEADERS = ["zipml_device.h", "zipml_host.h", "zipml_sgd_mfma.h", "zipml_sgd_rows.h"]
+HEADERS = ["zipml_device.h", "zipml_host.h", "zipml_mfma_ops.h", "zipml_sgd_mfma.h", "zipml_sgd_rows.h"]
 
 # -ffp-contract=off: fp32/fp64 decision sequences must stay single IEEE operations (fused
 #   multiply-adds are written explicitly where they are wanted).

@@ -161,11 +161,19 @@ def test_quantize_optimal_levels_and_epoch_key():
 
 # ------------------------------------------------------------------ loss
 def test_loss_fp32_and_packed():
+    """fp32 rows and both packed copies; copy 2 at 2, 4 and 8 bits runs on the matrix cores when the
+    levels are evenly spaced (ragged n and d, an odd number of feature groups, many tiles per
+    workgroup) and on the table path when one feature's levels are not."""
     say("loss")
-    for (n, d, bits) in [(4096, 64, 4), (1000, 70, 3), (2048, 288, 8), (333, 5, 2)]:
+    for (n, d, bits, uneven) in [(4096, 64, 4, False), (1000, 70, 3, False), (2048, 288, 8, False),
+                                 (333, 5, 2, False), (70000, 1100, 8, False), (4096, 288, 4, True)]:
         w = synth.tiny(n=n, d=d)
         A, b = w.full()
         L = uniform_levels_np(d, bits, -1.0, 1.0)
+        if uneven:
+            L = L.copy()
+            L[7] = np.sort(np.random.default_rng(1).uniform(-1, 1, 1 << bits)).astype(np.float32)
+            L[7, 0], L[7, -1] = -1.0, 1.0
         p = GpuProblem(A, b, bits, 32)
         p.set_levels(L)
         p.quantize(3, 0)
