@@ -188,8 +188,14 @@ def main():
     def sweep_point(nn, p1s, p2s, bs, batch, reps=5):
         xs = torch.zeros(d, dtype=torch.float32, device=dev)
         wss = torch.zeros(zipml.workspace_bytes(nn, d, bits, batch), dtype=torch.uint8, device=dev)
-        ms = timed(lambda: zipml.sgd_epoch(p1s, p2s, lev, bs, nn, d, bits, xs, batch, w.lr, wss), reps)
-        assert zipml.sgd_status(wss) == 0
+        try:
+            ms = timed(lambda: zipml.sgd_epoch(p1s, p2s, lev, bs, nn, d, bits, xs, batch, w.lr, wss), reps)
+        except zipml.ZipmlError as e:       # e.g. a shape whose large minibatches no kernel takes
+            sweep.append({"n": nn, "batch": batch, "error": str(e)})
+            return
+        if zipml.sgd_status(wss) != 0:
+            sweep.append({"n": nn, "batch": batch, "error": zipml.strerror(zipml.sgd_status(wss))})
+            return
         nbytes = nn * (2 * d * bits / 8 + 4)
         sweep.append({"n": nn, "batch": batch, "ms_per_epoch": ms, "us_per_step": ms * 1e3 / (nn // batch),
                       "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -197,7 +203,8 @@ def main():
 
     if not args.batch:
         for mult in (4, 16):
-            sweep_point(n, p1, p2, bd, B * mult)
+            if n % (B * mult) == 0:
+                sweep_point(n, p1, p2, bd, B * mult)
         sweep_point(n, p1, p2, bd, n)
         n8 = 8 * n
         q1 = torch.randint(0, 256, (zipml.packed_bytes(n8, d, bits),), dtype=torch.uint8, device=dev)
