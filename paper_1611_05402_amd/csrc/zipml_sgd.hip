@@ -904,12 +904,26 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
                                                       int words, int clear_status,
                                                       const float *__restrict__ levels,
                                                       const float *__restrict__ x, int d, int K,
-                                                      double *bound, int *even)
+                                                      double *bound, int *even,
+                                                      float *dl = nullptr, float *mid = nullptr,
+                                                      int nfeat = 0, float off = 0.0f)
 {
     __shared__ double sb[256], sl[256], sy[256], sm[256];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
     for (int e = i; e < words; e += gridDim.x * blockDim.x) acc[e] = 0ull;
+    // per-feature constants of the sample-owner kernel: delta_j and lo_j + off * delta_j (zero for padding)
+    if (dl)
+        for (int j = i; j < nfeat; j += gridDim.x * blockDim.x) {
+            float dv = 0.0f, mv = 0.0f;
+            if (j < d) {
+                const float lo = levels[(size_t)j * K], hi = levels[(size_t)j * K + K - 1];
+                dv = (float)(((double)hi - (double)lo) / (double)(K - 1));
+                mv = lo + off * dv;
+            }
+            dl[j] = dv;
+            mid[j] = mv;
+        }
     // blocks 0 .. kEvenBlocks-1: is this block's share of the level tables evenly spaced (fp64
     // formula, rounded once)?  Asked only where the answer matters (K a multiple of 4): four
     // entries per load, the loads of a thread independent of each other.
@@ -1147,10 +1161,8 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
         return ZIPML_ELAUNCH;
     // status word, barrier counter, evenly-spaced check (no exchange words to clear)
     hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, r.status, r.sync,
-                       acc, 0, 1, levels, r.x, r.d, K, (double *)nullptr, even);
-    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
-    hipLaunchKernelGGL(k_rows_prepare, dim3((nfeat + 255) / 256), dim3(256), 0, s, levels, r.d, K, nfeat,
-                       BITS == 8 ? 128.0f : 0.0f, const_cast<float *>(r.dl), const_cast<float *>(r.mid));
+                       acc, 0, 1, levels, r.x, r.d, K, (double *)nullptr, even, const_cast<float *>(r.dl),
+                       const_cast<float *>(r.mid), nfeat, BITS == 8 ? 128.0f : 0.0f);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     void *params[] = {&r};
     if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(wgs), dim3(kThreads), params, (unsigned)shmem, s)))

@@ -27,7 +27,7 @@ struct RowsArgs {
     const uint32_t *p1, *p2;
     const float *b;
     float *x;
-    const float *dl, *mid;   // [NKB * 64] delta_j and lo_j + off * delta_j (zero beyond d), from k_rows_prepare
+    const float *dl, *mid;   // [NKB * 64] delta_j and lo_j + off * delta_j (zero beyond d), from k_sgd_prepare
     int64_t n_pad, n32;      // samples per feature group of copy 2, sample groups of copy 1
     int d, d32, NKB;         // features, feature groups, 64-feature blocks
     int64_t B;               // minibatch (multiple of 64)
@@ -42,22 +42,6 @@ struct RowsArgs {
     float *part;             // [gridDim.x][NKB * 64] per-workgroup gradients, then [gridDim.x] sums of residuals
     uint32_t spin_limit;
 };
-
-// delta_j and mid_j of every feature (zero for padding), once per launch.
-__global__ __launch_bounds__(256) void k_rows_prepare(const float *__restrict__ levels, int d, int K,
-                                                       int count, float off, float *dl, float *mid)
-{
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= count) return;
-    float dv = 0.0f, mv = 0.0f;
-    if (j < d) {
-        const float lo = levels[(size_t)j * K], hi = levels[(size_t)j * K + K - 1];
-        dv = (float)(((double)hi - (double)lo) / (double)(K - 1));
-        mv = lo + off * dv;
-    }
-    dl[j] = dv;
-    mid[j] = mv;
-}
 
 // KPI: 64-feature blocks per wave and item (at most 16 / BITS: 32 packed dwords per lane in flight
 // per item; less when the problem has fewer than 8 * KPI blocks).
