@@ -239,6 +239,36 @@ def sgd_epoch_e2e(codes1, codes2, levels, grid_idx, grid_lo, grid_step, b, bits,
     return (x, dbg) if debug else x
 
 
+# ---------------------------------------------------------------------------------------------
+# Compact storage of the two samples (Sec. 2.2, "Overhead of Storing Samples"): the two
+# quantisations of a value lie on the two ends of ONE interval of the level grid, so they differ
+# by at most one level.  Stored: a base level (b bits) and, per sample, one bit saying whether the
+# sample sits on the base level or on the next one: b + 2 bits instead of 2 b.
+# Reading taken here: the base is the smaller of the two codes (when both samples rounded up the
+# paper's "smallest number of the interval" would be one lower with both bits set; the decoded
+# samples and the size are the same, and this form needs the codes only).
+# ---------------------------------------------------------------------------------------------
+def compact_encode(codes1, codes2):
+    """(base, bit1, bit2) with codes_k = base + bit_k; ValueError if a pair differs by more than one."""
+    c1 = np.asarray(codes1).astype(np.int64)
+    c2 = np.asarray(codes2).astype(np.int64)
+    base = np.minimum(c1, c2)
+    u1, u2 = c1 - base, c2 - base
+    if u1.max(initial=0) > 1 or u2.max(initial=0) > 1:
+        raise ValueError("the two samples of a value differ by more than one level")
+    return base.astype(np.uint8), u1.astype(np.uint8), u2.astype(np.uint8)
+
+
+def compact_decode(base, bit1, bit2):
+    base = np.asarray(base).astype(np.int64)
+    return (base + np.asarray(bit1)).astype(np.uint8), (base + np.asarray(bit2)).astype(np.uint8)
+
+
+def compact_bits_per_value(bits, samples=2):
+    """Bits per value for `samples` ordered samples: the base level and one bit each."""
+    return bits + samples
+
+
 def loss(A, b, x):
     A, b, x = _f32(A), _f32(b), _f32(x)
     n, d = A.shape

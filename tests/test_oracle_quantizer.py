@@ -239,3 +239,44 @@ def test_double_sampled_gradient_monte_carlo_d64():
                     for j, (l, _) in enumerate(_outcomes(L, bits, a))])
     sen = Gn.std(axis=0) / np.sqrt(reps)
     assert np.all(np.abs(bias - err * x) < 5 * sen + 1e-9)
+
+
+# ------------------------------------------------------------------ compact storage of the two samples
+def test_compact_storage_of_two_samples():
+    """Sec. 2.2, "Overhead of Storing Samples": the two samples of a value differ by at most one
+    level, so a base level plus one bit per sample (b + 2 bits instead of 2 b) stores both."""
+    # the paper's example: 0.7 between the levels 0 and 1 -- base 0, one bit per sample
+    L = np.array([[0.0, 1.0]], np.float32)
+    seen = set()
+    for seed in range(40):
+        c1, c2 = oracle.quantize(np.array([[0.7]], np.float32), L, 1, seed, 0)
+        base, u1, u2 = oracle.compact_encode(c1, c2)
+        assert base.shape == (1, 1) and base[0, 0] == min(c1[0, 0], c2[0, 0])
+        assert (int(base[0, 0]) + int(u1[0, 0]), int(base[0, 0]) + int(u2[0, 0])) == (int(c1[0, 0]), int(c2[0, 0]))
+        seen.add((int(c1[0, 0]), int(c2[0, 0])))
+    assert seen == {(0, 0), (0, 1), (1, 0), (1, 1)}          # all four outcomes occur, all are stored
+    # every pair that can occur round-trips; pairs further apart cannot occur and are refused
+    for bits in (1, 2, 3, 8):
+        K = 1 << bits
+        a = np.array([(c, c) for c in range(K)] + [(c, c + 1) for c in range(K - 1)] +
+                     [(c + 1, c) for c in range(K - 1)], np.uint8)
+        base, u1, u2 = oracle.compact_encode(a[:, 0], a[:, 1])
+        assert set(np.unique(u1)) <= {0, 1} and set(np.unique(u2)) <= {0, 1} and base.max() <= K - 1
+        d1, d2 = oracle.compact_decode(base, u1, u2)
+        assert np.array_equal(d1, a[:, 0]) and np.array_equal(d2, a[:, 1])
+        assert oracle.compact_bits_per_value(bits) == bits + 2
+    with pytest.raises(ValueError):
+        oracle.compact_encode(np.array([0], np.uint8), np.array([2], np.uint8))
+    # the premise, on quantised data: the two copies never differ by more than one level, and do
+    # differ somewhere (per-feature levels, values inside, outside and on the levels)
+    rng = np.random.default_rng(3)
+    A = rng.uniform(-1.3, 1.3, (500, 37)).astype(np.float32)
+    A[::9] = 0.5
+    for bits in (1, 3, 8):
+        Lv = oracle.levels_uniform(np.full(37, -1, np.float32), np.full(37, 1, np.float32), bits)
+        c1, c2 = oracle.quantize(A, Lv, bits, 11, 2)
+        diff = c1.astype(np.int64) - c2.astype(np.int64)
+        assert np.abs(diff).max() == 1
+        base, u1, u2 = oracle.compact_encode(c1, c2)
+        d1, d2 = oracle.compact_decode(base, u1, u2)
+        assert np.array_equal(d1, c1) and np.array_equal(d2, c2)
