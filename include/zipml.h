@@ -106,6 +106,24 @@ int zipml_quantize_swapped(void *stream, const float *A_dev, int64_t n_rows, int
                            int64_t row0, int64_t n_total, const float *levels_dev, int bits,
                            uint64_t seed, uint32_t epoch, void *packed1s_dev, void *packed2s_dev);
 
+/* Compact storage of the two samples (Sec. 2.2, "Overhead of Storing Samples"): the two
+ * quantisations of a value differ by at most one level, so a base level and one bit per sample
+ * hold both, bits + 2 bits per value instead of 2 * bits.  packed_a_dev and packed_b_dev are the
+ * two copies in the SAME layout -- (packed2s, packed2): copy 1 and copy 2 sample-major, or
+ * (packed1, packed1s): copy 1 and copy 2 feature-major, see zipml_quantize_swapped -- and
+ * compact_dev holds zipml_compact_bytes(n, d, bits) bytes: per unit of 32 values the smaller of
+ * the two codes (bits dwords), then one dword of bits per copy saying which values sit one level
+ * above it.  A storage and transfer format: the epoch kernels read the packed copies, which
+ * zipml_compact_decode restores bit for bit.  zipml_compact_encode synchronises the stream and
+ * returns ZIPML_EINVAL if some pair of codes differs by more than one level (the arrays are then
+ * not two samples of the same values); it uses 256 bytes of workspace. */
+size_t zipml_compact_bytes(int64_t n, int64_t d, int bits);
+int zipml_compact_encode(void *stream, const void *packed_a_dev, const void *packed_b_dev, int64_t n,
+                         int64_t d, int bits, void *compact_dev, void *workspace_dev,
+                         size_t workspace_bytes);
+int zipml_compact_decode(void *stream, const void *compact_dev, int64_t n, int64_t d, int bits,
+                         void *packed_a_dev, void *packed_b_dev);
+
 /* One epoch of double-sampled minibatch SGD on F(x) = 1/(2n) sum_i (a_i^T x - b_i)^2
  * (Sec. 2 and eq. (5); the minibatch gradient is the mean over `batch` consecutive samples; the
  * n / batch steps run in storage order).  x_dev[d] is the fp32 master model, updated in place:

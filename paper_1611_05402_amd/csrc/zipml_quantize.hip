@@ -280,6 +280,73 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
     }
 }
 
+// Compact storage of two copies that are stored in the same layout (Sec. 2.2, "Overhead of
+// Storing Samples"): the two samples of a value differ by at most one level, so a base level and
+// one bit per sample hold both, b + 2 bits per value instead of 2 b.  One thread per packed unit
+// of 32 codes: [BITS dwords base = min of the two codes][1 dword: copy a sits one above the base]
+// [1 dword: copy b does].  Pairs further apart than one level cannot be stored: counted in *bad.
+template <int BITS>
+__global__ __launch_bounds__(256) void k_compact_encode(const uint32_t *__restrict__ pa,
+                                                        const uint32_t *__restrict__ pb, int64_t units,
+                                                        uint32_t *__restrict__ out, int *__restrict__ bad)
+{
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    uint32_t a[BITS], b[BITS], base[BITS];
+#pragma unroll
+    for (int q = 0; q < BITS; ++q) { a[q] = pa[u * BITS + q]; b[q] = pb[u * BITS + q]; base[q] = 0u; }
+    uint32_t ua = 0u, ub = 0u;
+    int wrong = 0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+        const uint32_t ca = unit_code<BITS>(a, k), cb = unit_code<BITS>(b, k);
+        const uint32_t lo = ca < cb ? ca : cb;
+        wrong |= (ca - lo > 1u) | (cb - lo > 1u);
+        unit_set<BITS>(base, k, lo);
+        ua |= ((ca - lo) & 1u) << k;
+        ub |= ((cb - lo) & 1u) << k;
+    }
+    uint32_t *dst = out + u * (BITS + 2);
+#pragma unroll
+    for (int q = 0; q < BITS; ++q) dst[q] = base[q];
+    dst[BITS] = ua;
+    dst[BITS + 1] = ub;
+    if (wrong) atomicAdd(bad, 1);
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void k_compact_decode(const uint32_t *__restrict__ in, int64_t units,
+                                                        uint32_t *__restrict__ pa, uint32_t *__restrict__ pb)
+{
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    const uint32_t *src = in + u * (BITS + 2);
+    uint32_t base[BITS], a[BITS], b[BITS];
+#pragma unroll
+    for (int q = 0; q < BITS; ++q) { base[q] = src[q]; a[q] = 0u; b[q] = 0u; }
+    const uint32_t ua = src[BITS], ub = src[BITS + 1];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+        const uint32_t lo = unit_code<BITS>(base, k);
+        unit_set<BITS>(a, k, (lo + ((ua >> k) & 1u)) & ((1u << BITS) - 1u));
+        unit_set<BITS>(b, k, (lo + ((ub >> k) & 1u)) & ((1u << BITS) - 1u));
+    }
+#pragma unroll
+    for (int q = 0; q < BITS; ++q) { pa[u * BITS + q] = a[q]; pb[u * BITS + q] = b[q]; }
+}
+
+template <int BITS>
+static int launch_compact(hipStream_t s, bool encode, const uint32_t *a, const uint32_t *b, int64_t units,
+                          uint32_t *compact, uint32_t *oa, uint32_t *ob, int *bad)
+{
+    const unsigned blocks = (unsigned)((units + 255) / 256);
+    if (encode)
+        hipLaunchKernelGGL(k_compact_encode<BITS>, dim3(blocks), dim3(256), 0, s, a, b, units, compact, bad);
+    else
+        hipLaunchKernelGGL(k_compact_decode<BITS>, dim3(blocks), dim3(256), 0, s, compact, units, oa, ob);
+    return hip_check(hipGetLastError());
+}
+
 template <int BITS>
 static int launch_quantize(hipStream_t s, const float *A, int64_t n_rows, int64_t d, int64_t lda,
                            int64_t row0, const Layout &lay, const float *levels, uint64_t seed,
@@ -381,6 +448,60 @@ extern "C" int zipml_unpack_codes(void *stream, const void *packed_dev, int copy
     const Layout lay = make_layout(n, d, bits);
     hipStream_t s = entry_stream(stream);
 #define CALL(B) launch_unpack<B>(s, (const uint32_t *)packed_dev, copy, lay, codes_dev)
+    ZIPML_DISPATCH_BITS(bits, CALL)
+#undef CALL
+}
+
+extern "C" size_t zipml_compact_bytes(int64_t n, int64_t d, int bits)
+{
+    if (n <= 0 || d <= 0 || !valid_bits(bits)) return 0;
+    const Layout lay = make_layout(n, d, bits);
+    return (size_t)lay.n_pad * (size_t)lay.d_pad / 32 * (size_t)(bits + 2) * 4;
+}
+
+extern "C" int zipml_compact_encode(void *stream, const void *packed_a_dev, const void *packed_b_dev,
+                                    int64_t n, int64_t d, int bits, void *compact_dev,
+                                    void *workspace_dev, size_t workspace_bytes)
+{
+    if (!packed_a_dev || !packed_b_dev || !compact_dev || n <= 0 || d <= 0 || !valid_bits(bits))
+        return ZIPML_EINVAL;
+    if (!workspace_dev || workspace_bytes < 256) return ZIPML_EWORKSPACE;
+    if (!aligned16(packed_a_dev) || !aligned16(packed_b_dev) || !aligned16(compact_dev) ||
+        !aligned16(workspace_dev))
+        return ZIPML_EALIGN;
+    const Layout lay = make_layout(n, d, bits);
+    const int64_t units = lay.n_pad * lay.d_pad / 32;
+    hipStream_t s = entry_stream(stream);
+    int *bad = (int *)workspace_dev;
+    if (hipMemsetAsync(bad, 0, sizeof(int), s) != hipSuccess) return ZIPML_ELAUNCH;
+    int rc = ZIPML_EINVAL;
+#define CALL(B) launch_compact<B>(s, true, (const uint32_t *)packed_a_dev, (const uint32_t *)packed_b_dev, \
+                                  units, (uint32_t *)compact_dev, nullptr, nullptr, bad)
+    switch (bits) {
+        case 1: rc = CALL(1); break; case 2: rc = CALL(2); break; case 3: rc = CALL(3); break;
+        case 4: rc = CALL(4); break; case 5: rc = CALL(5); break; case 6: rc = CALL(6); break;
+        case 7: rc = CALL(7); break; case 8: rc = CALL(8); break;
+    }
+#undef CALL
+    if (rc) return rc;
+    int bad_host = 0;
+    if (hipMemcpyAsync(&bad_host, bad, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return ZIPML_ELAUNCH;
+    return bad_host ? ZIPML_EINVAL : ZIPML_OK;     // some pair of codes differs by more than one level
+}
+
+extern "C" int zipml_compact_decode(void *stream, const void *compact_dev, int64_t n, int64_t d,
+                                    int bits, void *packed_a_dev, void *packed_b_dev)
+{
+    if (!packed_a_dev || !packed_b_dev || !compact_dev || n <= 0 || d <= 0 || !valid_bits(bits))
+        return ZIPML_EINVAL;
+    if (!aligned16(packed_a_dev) || !aligned16(packed_b_dev) || !aligned16(compact_dev)) return ZIPML_EALIGN;
+    const Layout lay = make_layout(n, d, bits);
+    const int64_t units = lay.n_pad * lay.d_pad / 32;
+    hipStream_t s = entry_stream(stream);
+#define CALL(B) launch_compact<B>(s, false, nullptr, nullptr, units, (uint32_t *)const_cast<void *>(compact_dev), \
+                                  (uint32_t *)packed_a_dev, (uint32_t *)packed_b_dev, nullptr)
     ZIPML_DISPATCH_BITS(bits, CALL)
 #undef CALL
 }

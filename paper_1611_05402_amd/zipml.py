@@ -21,7 +21,8 @@ PROX_NONE, PROX_L1, PROX_L2SQ, PROX_BOX = 0, 1, 2, 3
 OK, EINVAL, EALIGN, ERANGE, EWORKSPACE, ELAUNCH, EUNSUPPORTED, ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = ["zipml_strerror", "zipml_packed_bytes", "zipml_workspace_bytes", "zipml_levels",
-           "zipml_quantize", "zipml_quantize_swapped", "zipml_sgd_epoch", "zipml_sgd_epoch_l2",
+           "zipml_quantize", "zipml_quantize_swapped", "zipml_compact_bytes", "zipml_compact_encode",
+           "zipml_compact_decode", "zipml_sgd_epoch", "zipml_sgd_epoch_l2",
            "zipml_sgd_epoch_prox", "zipml_sgd_epoch_avg", "zipml_sgd_status", "zipml_loss",
            "zipml_unpack_codes", "zipml_debug_step"]
 
@@ -51,6 +52,14 @@ def lib() -> C.CDLL:
         L.zipml_strerror.argtypes = [C.c_int]
         L.zipml_packed_bytes.restype = C.c_size_t
         L.zipml_packed_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int]
+        L.zipml_compact_bytes.restype = C.c_size_t
+        L.zipml_compact_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int]
+        L.zipml_compact_encode.restype = C.c_int
+        L.zipml_compact_encode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int,
+                                           C.c_void_p, C.c_void_p, C.c_size_t]
+        L.zipml_compact_decode.restype = C.c_int
+        L.zipml_compact_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p,
+                                           C.c_void_p]
         L.zipml_workspace_bytes.restype = C.c_size_t
         L.zipml_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int, C.c_int64, C.c_int]
         vp, i64, i32, f32, u64, u32, sz = (C.c_void_p, C.c_int64, C.c_int, C.c_float, C.c_uint64,
@@ -159,6 +168,22 @@ def sgd_epoch_l2(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, l2, wo
                                     _ptr(b), n, d, bits, _ptr(x), batch, lr, l2, flags,
                                     _ptr(workspace), workspace.numel() * workspace.element_size()),
            "zipml_sgd_epoch_l2")
+
+
+def compact_bytes(n, d, bits):
+    return int(lib().zipml_compact_bytes(n, d, bits))
+
+
+def compact_encode(packed_a, packed_b, n, d, bits, compact, workspace, *, stream=None):
+    _check(lib().zipml_compact_encode(_stream(stream), _ptr(packed_a), _ptr(packed_b), n, d, bits,
+                                      _ptr(compact), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size()),
+           "zipml_compact_encode")
+
+
+def compact_decode(compact, n, d, bits, packed_a, packed_b, *, stream=None):
+    _check(lib().zipml_compact_decode(_stream(stream), _ptr(compact), n, d, bits, _ptr(packed_a),
+                                      _ptr(packed_b)), "zipml_compact_decode")
 
 
 def sgd_epoch_prox(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, prox, prox_coef,

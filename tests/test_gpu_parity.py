@@ -159,6 +159,51 @@ def test_quantize_optimal_levels_and_epoch_key():
         assert np.array_equal(p.codes(1), c1) and np.array_equal(p.codes(2), c2)
 
 
+# ------------------------------------------------------------------ compact storage
+@pytest.mark.parametrize("n,d,bits", [(4096, 64, 4), (1000, 70, 3), (2048, 288, 8), (333, 5, 1), (96, 224, 7)])
+def test_compact_storage_roundtrip_and_layout(n, d, bits):
+    """Base level + one bit per sample (Sec. 2.2, "Overhead of Storing Samples"): what the device
+    stores is the oracle's (min of the codes, bit, bit), it is (bits + 2) / (2 bits) of the two
+    packed copies, and decoding restores both copies bit for bit -- in both layouts."""
+    say("compact", n, d, bits)
+    w = synth.tiny(n=n, d=d)
+    A, b = w.full()
+    L = uniform_levels_np(d, bits, -1.0, 1.0)
+    p = GpuProblem(A, b, bits, 32)
+    p.set_levels(L)
+    p.quantize(17, 1)
+    p1s, p2s = torch.zeros_like(p.p1), torch.zeros_like(p.p2)
+    zipml.quantize_swapped(p.A, n, d, d, 0, n, p.levels, bits, 17, 1, p1s, p2s)
+    c1, c2 = oracle.quantize(A, L, bits, 17, 1)
+    base, u1, u2 = oracle.compact_encode(c1, c2)
+    nbytes = zipml.compact_bytes(n, d, bits)
+    assert nbytes * 2 * bits == 2 * zipml.packed_bytes(n, d, bits) * (bits + 2)
+    out = torch.zeros(n, d, dtype=torch.uint8, device=DEV)
+    # (a, b) = (copy 1, copy 2): sample-major pair (packed2s, packed2), feature-major pair (packed1, packed1s)
+    for copy, pa, pb in ((2, p2s, p.p2), (1, p.p1, p1s)):
+        comp = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+        zipml.compact_encode(pa, pb, n, d, bits, comp, p.ws)
+        units = comp.view(torch.int32).view(-1, bits + 2)
+        # the base plane is a packed array of its own, the two bit planes are 1-bit packed arrays
+        zipml.unpack_codes(units[:, :bits].contiguous().view(torch.uint8), copy, n, d, bits, out)
+        assert np.array_equal(out.cpu().numpy(), base)
+        for plane, want in ((bits, u1), (bits + 1, u2)):
+            zipml.unpack_codes(units[:, plane:plane + 1].contiguous().view(torch.uint8), copy, n, d, 1, out)
+            assert np.array_equal(out.cpu().numpy(), want)
+        qa, qb = torch.zeros_like(pa), torch.zeros_like(pb)
+        zipml.compact_decode(comp, n, d, bits, qa, qb)
+        assert torch.equal(qa, pa) and torch.equal(qb, pb)
+    # two arrays that are not samples of the same values are refused
+    if bits >= 2:
+        far = GpuProblem(-A, b, bits, 32)
+        far.set_levels(L)
+        far.quantize(17, 1)
+        comp = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+        with pytest.raises(zipml.ZipmlError) as e:
+            zipml.compact_encode(far.p2, p.p2, n, d, bits, comp, p.ws)
+        assert e.value.code == zipml.EINVAL
+
+
 # ------------------------------------------------------------------ loss
 def test_loss_fp32_and_packed():
     """fp32 rows and both packed copies; copy 2 at 2, 4 and 8 bits runs on the matrix cores when the
