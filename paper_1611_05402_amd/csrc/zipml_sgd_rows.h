@@ -12,8 +12,9 @@
 // the workgroups meet twice: after their tiles, to add up the per-workgroup gradients (each wave
 // sums 16 features over all workgroups, in a fixed order) and update the model in place; and after
 // that update.  Nothing else is exchanged, so the packed data streams at the rate the memory
-// system delivers it: every wave keeps one item (64 packed dwords per lane) in flight while it
-// feeds the previous one to the matrix cores.
+// system delivers it: every wave keeps one item (16 to 32 packed dwords per lane, requested with
+// non-temporal loads that no branch can skip) in flight while it feeds the previous one to the
+// matrix cores.
 //
 // Arithmetic is that of the matrix-core step loop: y and the residuals of a tile as 32-bit fixed
 // point in four signed base-256 digits, v_mfma_i32_16x16x64_i8 against the codes expanded to
