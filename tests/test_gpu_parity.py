@@ -716,6 +716,42 @@ def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, monkeypatch)
     assert rel_l2(x.cpu().numpy(), x_ref) <= TOL
 
 
+# ------------------------------------------------------------------ caller's stream
+def test_everything_runs_on_the_callers_stream():
+    """All device work is enqueued on the stream the caller passes: the same calls on a stream of
+    the caller's own (default priority) give the same bits as on the default stream."""
+    say("caller's stream")
+    w = synth.dense8(n=8192, d=288, batch=256)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    res = []
+    for own in (False, True):
+        st = torch.cuda.Stream() if own else torch.cuda.current_stream()
+        with torch.cuda.stream(st):
+            p = GpuProblem(A, b, w.bits, w.batch)
+            p.set_levels(L)
+            p.quantize(2, 0)
+            x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+            for _ in range(2):
+                p.epoch(x, 1e-3)
+            ws_big = torch.zeros(zipml.workspace_bytes(w.n, w.d, w.bits, 4096), dtype=torch.uint8, device=DEV)
+            y = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+            zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, y, 4096, 0.05, ws_big)   # replicas
+            assert zipml.sgd_status(ws_big) == 0
+            loss = p.loss(x, packed_copy=2)
+            st.synchronize()
+            res.append((p.p1.clone(), p.p2.clone(), x.clone(), y.clone(), loss))
+    torch.cuda.synchronize()
+    for u, v in zip(res[0][:4], res[1][:4]):
+        assert torch.equal(u, v)
+    assert res[0][4] == res[1][4]
+    c1, c2 = oracle.quantize(A, L, w.bits, 2, 0)
+    x_ref = np.zeros(w.d, np.float32)
+    for _ in range(2):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, 1e-3)
+    assert rel_l2(res[1][2].cpu().numpy(), x_ref) <= TOL
+
+
 # ------------------------------------------------------------------ edge cases
 def test_degenerate_inputs():
     say("edge cases")
