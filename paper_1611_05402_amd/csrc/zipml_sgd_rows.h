@@ -133,24 +133,34 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
     // in memory.)
     const uintptr_t copy1 = (uintptr_t)a.p1, copy_diff = (uintptr_t)a.p2 - (uintptr_t)a.p1;
     const uint32_t off_diff = dot_lo - grad_off;
-    const int64_t n_pad = a.n_pad, n32 = a.n32;
     const int d32 = a.d32;
+    // In both copies a 64-feature block is 8 * BITS * n_pad bytes from the next, and the 64 samples
+    // of a tile start 4 * BITS * row0 bytes into a feature group (copy 1: n32 * 32 = n_pad samples
+    // per group, 32 * BITS dwords per sample group).  So an address is
+    //   copy + 4 BITS row0 + kb * block_bytes + (a few hundred bytes that depend on sl) + lane offset,
+    // and only the first three terms need 64-bit arithmetic, once per block.
+    const uintptr_t block_bytes = (uintptr_t)8 * BITS * (uintptr_t)a.n_pad;
     // Every call requests the same number of loads, whatever the item, and no load sits behind a
     // branch: only then can the wait for an item leave exactly the next item's loads in flight.
     // (Blocks past the last one repeat it; nothing is computed from them.)
     auto issue = [&](int64_t row0, int k, uint32_t (&dst)[KPI][4][HW]) __attribute__((always_inline)) {
         const uintptr_t dm = (uintptr_t)0 - (uintptr_t)(k < NG ? 1 : 0);   // all ones: dot pass
+        const uintptr_t tile = copy1 + (copy_diff & dm) + (uintptr_t)(4 * BITS) * (uintptr_t)row0;
+        const int kb0 = wave + kWaves * KPI * (k < NG ? k : k - NG);
 #pragma unroll
         for (int j = 0; j < KPI; ++j) {
-            int kb = block_of(k, j);
+            int kb = kb0 + kWaves * j;
             kb = kb < NKB ? kb : NKB - 1;
-            const int whole = 2 * kb + 1 < d32 ? 1 : 0;
-            const uint32_t off = grad_off + ((off_diff + (dot_hi & (0u - (uint32_t)whole))) & (uint32_t)dm);
+            const uint32_t whole = 2 * kb + 1 < d32 ? ~0u : 0u;
+            const uintptr_t block = tile + (uintptr_t)kb * block_bytes;
+            const uint32_t off = grad_off + ((off_diff + (dot_hi & whole)) & (uint32_t)dm);
+            // second feature group of the block (copy 1, sl >= 2): half a block further
+            const uintptr_t second = (block_bytes >> 1) & (uintptr_t)(int64_t)(int32_t)whole;
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl) {
-                const int64_t dot_dw = ((int64_t)2 * kb * n_pad + row0 + 16 * sl) * BITS;
-                const int64_t grad_dw = (((int64_t)(2 * kb + (sl >> 1) * whole) * n32 + row0 / 32) * 32 + 16 * (sl & 1)) * BITS;
-                const uintptr_t base = copy1 + (copy_diff & dm) + 4 * (uintptr_t)(grad_dw + ((dot_dw - grad_dw) & (int64_t)dm));
+                const uintptr_t in_dot = (uintptr_t)(64 * BITS * sl);
+                const uintptr_t in_grad = (sl >> 1 ? second : 0) + (uintptr_t)(64 * BITS * (sl & 1));
+                const uintptr_t base = block + in_grad + ((in_dot - in_grad) & dm);
                 // (a pointer rebuilt from an integer: say that it points to global memory; the
                 // vector type carries the alignment)
                 typedef uint32_t words_t __attribute__((ext_vector_type(HW)));
