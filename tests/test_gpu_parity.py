@@ -13,7 +13,10 @@ from paper_1611_05402_amd import synth, zipml
 
 pytestmark = pytest.mark.gpu
 
-TOL = 1e-5   # relative L2 on model and loss (fp32 arithmetic)
+# Relative L2 on model and loss.  The oracle evaluates a step in fp64 and stores the model in fp32; the
+# kernels sum in fp32 in another order (about sqrt(d) 2^-24 per dot product) or exactly on fixed-point
+# digits (2^-29 of the largest element); SGD contracts these errors, the observed figure is 1e-7.
+TOL = 1e-5
 
 
 def say(*a):
