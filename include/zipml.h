@@ -191,7 +191,8 @@ int zipml_sgd_epoch_prox(void *stream, const void *packed1_dev, const void *pack
  * which needs both copies in both layouts: packed1s_dev / packed2s_dev from
  * zipml_quantize_swapped.  fp32 model; 2-, 4- or 8-bit evenly spaced levels; batch a multiple
  * of 64; more than 256 features (otherwise ZIPML_EUNSUPPORTED, through the status word if it is
- * the level tables that do not qualify).  l2 as in zipml_sgd_epoch_l2 (0 for plain least squares). */
+ * the level tables that do not qualify).  l2 as in zipml_sgd_epoch_l2 (0 for plain least squares).
+ * Large minibatches are taken as in zipml_sgd_epoch (chunks, replicas, sample owners). */
 int zipml_sgd_epoch_avg(void *stream, const void *packed1_dev, const void *packed2_dev,
                         const void *packed1s_dev, const void *packed2s_dev, const float *levels_dev,
                         const float *b_dev, int64_t n, int64_t d, int bits, float *x_dev,

@@ -1157,6 +1157,12 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
     if constexpr (BITS == 2)
         kern = kpi >= 4 ? (const void *)k_sgd_rows<2, 4> : kpi == 2 ? (const void *)k_sgd_rows<2, 2>
                                                                    : (const void *)k_sgd_rows<2, 1>;
+    if (r.p1s) {     // symmetrised estimator: the default item sizes only
+        kpi = BITS == 2 && r.NKB >= 2 * kWaves ? 2 : 1;
+        if constexpr (BITS == 8) kern = (const void *)k_sgd_rows<8, 1, true>;
+        if constexpr (BITS == 4) kern = (const void *)k_sgd_rows<4, 1, true>;
+        if constexpr (BITS == 2) kern = kpi == 2 ? (const void *)k_sgd_rows<2, 2, true> : (const void *)k_sgd_rows<2, 1, true>;
+    }
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
         return ZIPML_ELAUNCH;
     // status word, barrier counter, evenly-spaced check (no exchange words to clear)
@@ -1282,7 +1288,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
         if (int lrc = device_limits(cus, lds)) return lrc;
         const int NKB = (int)((lay.d32 + 1) / 2);
         // (the kernel's per-lane byte offsets are 32 bits wide: one feature group of copy 2 must fit)
-        if (split_ok && !avg && batch >= rows_min && batch / 64 >= cus &&
+        if (split_ok && batch >= rows_min && batch / 64 >= cus &&
             rows_lds_bytes(NKB) <= (size_t)lds && lay.n_pad * bits * 4 < ((int64_t)1 << 32) &&
             !getenv("ZIPML_NO_MFMA")) {
             unsigned char *wsb = (unsigned char *)workspace_dev;
@@ -1295,6 +1301,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
             RowsArgs r{};
             r.p1 = (const uint32_t *)packed1_dev;
             r.p2 = (const uint32_t *)packed2_dev;
+            r.p1s = avg ? (const uint32_t *)packed1s_dev : nullptr;
+            r.p2s = avg ? (const uint32_t *)packed2s_dev : nullptr;
             r.b = b_dev;
             r.x = x_dev;
             r.dl = rows;

@@ -16,6 +16,10 @@
 // non-temporal loads that no branch can skip) in flight while it feeds the previous one to the
 // matrix cores.
 //
+// The symmetrised estimator (Supp. A.4; AVG) runs every tile of samples twice, once per code pair
+// -- (copy 2, copy 1) and (copy 1 sample-major, copy 2 feature-major) -- into the same gradient,
+// which is then the sum over both pairs, and the sum of residuals the sum over both.
+//
 // Arithmetic is that of the matrix-core step loop: y and the residuals of a tile as 32-bit fixed
 // point in four signed base-256 digits, v_mfma_i32_16x16x64_i8 against the codes expanded to
 // bytes, exact integer sums, one rounding back to fp32 per tile and feature.  The fixed-point
@@ -26,6 +30,7 @@ namespace zipml {
 
 struct RowsArgs {
     const uint32_t *p1, *p2;
+    const uint32_t *p1s, *p2s;   // symmetrised estimator: copy 2 feature-major, copy 1 sample-major
     const float *b;
     float *x;
     const float *dl, *mid;   // [NKB * 64] delta_j and lo_j + off * delta_j (zero beyond d), from k_sgd_prepare
@@ -46,7 +51,7 @@ struct RowsArgs {
 
 // KPI: 64-feature blocks per wave and item (at most 16 / BITS: 32 packed dwords per lane in flight
 // per item; less when the problem has fewer than 8 * KPI blocks).
-template <int BITS, int KPI>
+template <int BITS, int KPI, bool AVG>
 __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
 {
     constexpr int HW = BITS / 2;          // packed dwords per lane operand (16 codes)
@@ -57,7 +62,9 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
     const int P = gridDim.x, p = blockIdx.x;
     const int NKB = a.NKB, nfeat = NKB * 64;
     const int NG = (NKB + kWaves * KPI - 1) / (kWaves * KPI);   // items per pass and tile
-    const int64_t NT = a.B / 64;                                  // tiles of a minibatch
+    // tiles of a minibatch; with two code pairs tile V is samples 64 (V / 2) .. of pair V % 2
+    constexpr int PS = AVG ? 1 : 0;
+    const int64_t NT = (a.B / 64) << PS;
 
     // ---- LDS
     int8_t *const ydig = (int8_t *)smem;                               // [NKB][4 digits][4 q][16]
@@ -132,6 +139,9 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
     // a selection between two captured variables would keep them, and everything around them,
     // in memory.)
     const uintptr_t copy1 = (uintptr_t)a.p1, copy_diff = (uintptr_t)a.p2 - (uintptr_t)a.p1;
+    // (second code pair: what the first copy moves by, and what the difference between the copies moves by)
+    const uintptr_t pair_diff = AVG ? (uintptr_t)a.p1s - (uintptr_t)a.p1 : 0;
+    const uintptr_t pair_copy_diff = AVG ? ((uintptr_t)a.p2s - (uintptr_t)a.p1s) - copy_diff : 0;
     const uint32_t off_diff = dot_lo - grad_off;
     const int d32 = a.d32;
     // In both copies a 64-feature block is 8 * BITS * n_pad bytes from the next, and the 64 samples
@@ -143,9 +153,13 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
     // Every call requests the same number of loads, whatever the item, and no load sits behind a
     // branch: only then can the wait for an item leave exactly the next item's loads in flight.
     // (Blocks past the last one repeat it; nothing is computed from them.)
-    auto issue = [&](int64_t row0, int k, uint32_t (&dst)[KPI][4][HW]) __attribute__((always_inline)) {
+    auto issue = [&](int64_t row0, int pair, int k, uint32_t (&dst)[KPI][4][HW]) __attribute__((always_inline)) {
         const uintptr_t dm = (uintptr_t)0 - (uintptr_t)(k < NG ? 1 : 0);   // all ones: dot pass
-        const uintptr_t tile = copy1 + (copy_diff & dm) + (uintptr_t)(4 * BITS) * (uintptr_t)row0;
+        uintptr_t tile = copy1 + (copy_diff & dm) + (uintptr_t)(4 * BITS) * (uintptr_t)row0;
+        if constexpr (AVG) {
+            const uintptr_t pm = (uintptr_t)0 - (uintptr_t)pair;            // all ones: second pair
+            tile += (pair_diff & pm) + (pair_copy_diff & pm & dm);
+        }
         const int kb0 = wave + kWaves * KPI * (k < NG ? k : k - NG);
 #pragma unroll
         for (int j = 0; j < KPI; ++j) {
@@ -176,7 +190,7 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
     const int64_t t_end = a.step0 + a.nsteps;
     // The packed data do not depend on the model: the first item of a step is requested before the
     // previous step's gradients are added up (here: before the first step's model is read).
-    if (p < NT) issue(a.step0 * a.B + 64 * (int64_t)p, 0, buf0);
+    if (p < NT) issue(a.step0 * a.B + 64 * (int64_t)(p >> PS), p & PS, 0, buf0);
 #ifdef ZIPML_PHASE_TIMING
     long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = wall_clock64();
@@ -233,7 +247,8 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
         // the last bits of the result -- depend on timing, and gained nothing: the workgroups
         // finish within one tile of each other either way.
         for (int64_t T = p; T < NT; T += P) {
-            const int64_t row0 = t * a.B + 64 * T;
+            const int64_t row0 = t * a.B + 64 * (T >> PS);
+            const int pair = (int)(T & PS);
             const float label = a.b[row0 + lane];      // (every wave: no load behind a branch)
             v4i cdot = {0, 0, 0, 0};
             // one item: request the next one, then feed this one to the matrix cores
@@ -241,9 +256,16 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
                 // (after the last tile of a step: the first tile of the next step; after the last
                 // step: this tile's first item again, never used)
                 const bool more = k + 1 < 2 * NG;
-                const int64_t row_next = T + P < NT ? row0 + 64 * (int64_t)P
-                                         : t + 1 < t_end ? (t + 1) * a.B + 64 * (int64_t)p : row0;
-                issue(more ? row0 : row_next, more ? k + 1 : 0, nxt);
+                if constexpr (AVG) {
+                    const int64_t t_next = T + P < NT ? t : t + 1 < t_end ? t + 1 : t;
+                    const int64_t T_next = T + P < NT ? T + P : t + 1 < t_end ? (int64_t)p : T;
+                    const int64_t row_next = t_next * a.B + 64 * (T_next >> 1);
+                    issue(more ? row0 : row_next, more ? pair : (int)(T_next & 1), more ? k + 1 : 0, nxt);
+                } else {
+                    const int64_t row_next = T + P < NT ? row0 + 64 * (int64_t)P
+                                             : t + 1 < t_end ? (t + 1) * a.B + 64 * (int64_t)p : row0;
+                    issue(more ? row0 : row_next, 0, more ? k + 1 : 0, nxt);
+                }
                 if (k == NG) {
                     // ---- residuals of the tile (wave 0), between the two passes
                     zpart[wave * 64 + lane] = combine_digits(cdot);
@@ -344,7 +366,8 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
                 const float s2 = __shfl(s, 32 + n16, kWave), s3 = __shfl(s, 48 + n16, kWave);
                 const float G = (s0 + s1) + (s2 + s3);
                 if (q4 == 0 && j < a.d) {
-                    const float g = __fdiv_rn(a.mid[j] * Rtot + a.dl[j] * G, (float)a.B);
+                    // (two code pairs: both sums run over twice the samples, and the estimator is their mean)
+                    const float g = __fdiv_rn(a.mid[j] * Rtot + a.dl[j] * G, (float)(a.B << PS));
                     const float reg = a.l2 * xj;
                     const float stp = a.lr * (g + reg);
                     const float v = xj - stp;
@@ -362,11 +385,11 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
 #endif
 }
 
-template <int BITS, int KPI>
+template <int BITS, int KPI, bool AVG = false>
 __global__ __launch_bounds__(kThreads, 1) void k_sgd_rows(RowsArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    sgd_rows<BITS, KPI>(a, smem);
+    sgd_rows<BITS, KPI, AVG>(a, smem);
 }
 
 // LDS of k_sgd_rows for NKB blocks of 64 features.

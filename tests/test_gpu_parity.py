@@ -536,10 +536,15 @@ def test_end_to_end_optimal_levels_bit_exact():
     ("lowbit_small", synth.lowbit, dict(n=8192, d=640, batch=1024), 0.05, 0.0),
     ("lssvm_4bit", synth.lssvm, dict(n=4096, d=288, bits=4, batch=128), 0.05, 0.05),
     ("dense8_b4096_chunks", synth.dense8, dict(n=8192, d=288, batch=4096), 0.05, 0.0),
+    # sample owners (two tiles per sample block, one per code pair)
+    ("dense8_b16384_rows", synth.dense8, dict(n=32768, d=288, batch=16384), 0.05, 0.0),
+    ("lowbit_full_batch_rows", synth.lowbit, dict(n=32768, d=96, batch=32768), 0.2, 0.0),
+    ("tomo4_b16384_rows", synth.tomo, dict(n=16384, d=1024, batch=16384), 0.5, 0.01),
 ])
-def test_symmetrised_estimator_matches_oracle(name, factory, kw, lr, l2):
+def test_symmetrised_estimator_matches_oracle(name, factory, kw, lr, l2, monkeypatch):
     """g = 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)] (Supp. A.4)."""
     say("averaged", name)
+    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")
     w = factory(**kw)
     A, b = w.full()
     L = _levels_for(w, A)
