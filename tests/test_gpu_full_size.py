@@ -66,6 +66,23 @@ def test_dense8_full_size_codes_epoch_and_loss():
             say(f"  epoch {ep}: rel L2 {err:.2e}")
             assert err <= TOL
         assert np.linalg.norm(x_ref) > 0
+    # the symmetrised estimator (Supp. A.4) at the headline minibatch (feature owners) and with one
+    # step per epoch (sample owners)
+    p1s, p2s = torch.zeros_like(p.p1), torch.zeros_like(p.p2)
+    zipml.quantize_swapped(p.A, w.n, w.d, w.d, 0, w.n, p.levels, w.bits, 0, 0, p1s, p2s)
+    for batch, lr in ((w.batch, w.lr), (w.n, 0.25)):
+        say(f"full-size dense8: symmetrised estimator, batch {batch}")
+        ws = torch.zeros(zipml.workspace_bytes(w.n, w.d, w.bits, batch), dtype=torch.uint8, device=DEV)
+        x_ref = np.zeros(w.d, np.float32)
+        x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        for ep in range(2):
+            x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, batch, lr, symmetric=True)
+            zipml.sgd_epoch_avg(p.p1, p.p2, p1s, p2s, p.levels, p.b, w.n, w.d, w.bits, x, batch, lr, ws)
+            assert zipml.sgd_status(ws) == 0
+            err = rel_l2(x.cpu().numpy(), x_ref)
+            say(f"  epoch {ep}: rel L2 {err:.2e}")
+            assert err <= TOL
+        assert np.linalg.norm(x_ref) > 0
 
 
 # Sampled minibatch steps of the wide / long shapes: the oracle quantises and steps through the
