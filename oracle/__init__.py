@@ -123,6 +123,32 @@ def levels_optimal(hist, lo, hi, bits):
     return L, G, mv.value
 
 
+def greedy_intervals(mom, k):
+    """Greedy merging of the M bins into at most 4k + 1 intervals (supplement, Algorithm 1, with
+    gamma = 1, delta = 1): (edge indices [P+1], moments [P, 3])."""
+    mom = np.ascontiguousarray(mom, np.float64)
+    M = mom.shape[0]
+    edge = np.empty(M + 1, np.int32)
+    out = np.empty((M, 3), np.float64)
+    lib().zo_greedy_intervals.restype = C.c_int
+    P = lib().zo_greedy_intervals(_p(mom), C.c_int(M), C.c_int(k), _p(edge), _p(out))
+    return edge[:P + 1].copy(), out[:P].copy()
+
+
+def levels_greedy(hist, lo, hi, bits):
+    """Dynamic program over the end points of the greedy intervals (Sec. 3.2)."""
+    hist = np.ascontiguousarray(hist, np.float64)
+    lo, hi = _f32(lo), _f32(hi)
+    d, M = hist.shape[0], hist.shape[1]
+    K = 1 << bits
+    L = np.empty((d, K), np.float32)
+    G = np.empty((d, K), np.uint16)
+    mv = C.c_double(0.0)
+    lib().zo_levels_greedy(_p(hist), _p(lo), _p(hi), C.c_int64(d), C.c_int(bits), C.c_int(M),
+                           _p(L), _p(G), C.byref(mv))
+    return L, G, mv.value
+
+
 def bracket(L_row, bits, v):
     L_row = _f32(L_row)
     frac = C.c_float(0.0)

@@ -27,7 +27,9 @@
  * normal-equations solution; DP == brute force over all level subsets; the
  * l2 term == textbook ridge SGD and its closed form; the proximal step ==
  * brute-force minimisation of its definition and the lasso / ridge / box
- * closed forms of an orthogonal design.
+ * closed forms of an orthogonal design; the greedy intervals == a partition
+ * worked out by hand, within twice the optimum of the dynamic program, and
+ * == the optimum on clustered data.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -241,6 +243,109 @@ void zo_levels_optimal(const double *hist, const float *lo, const float *hi, int
     if (mean_variance) *mean_variance = mv / (double)d;
     free(cand);
     free(idx);
+}
+
+/* Greedy merging of intervals (supplement, "A Greedy Algorithm for Finding
+ * Quantization Points", Algorithm 1), run on the M bins of the candidate
+ * grid instead of on single points: the starting partition has one interval
+ * per bin, an interval carries the moments (count, sum t, sum t^2) of its
+ * points, and the error of an interval [a, b] is
+ *     err = sum over its points of (b - t)(t - a) = -S2 + (a + b) S1 - a b S0.
+ * While more than 2 (1 + gamma) k + delta intervals are left: consecutive
+ * intervals are paired up (an odd one at the end stays as it is), every pair
+ * gets the error of the merged interval (moments of the left one plus those
+ * of the right one), the q = (1 + gamma) k pairs with the largest error stay
+ * split (equal errors: the pair further left first), all others are merged.
+ * gamma = 1, delta = 1 here: at most 4 k + 1 intervals come out (with
+ * delta = 0 a partition of 4 k + 1 intervals would never shrink), and their
+ * error is at most 2 OPT_k (the supplement's theorem).
+ * edge[0..P] receives the bin-edge indices of the partition (0 and M among
+ * them), mom[P][3] its moments; returns P. */
+int zo_greedy_intervals(const double *hist /*[M][3]*/, int M, int k, int *edge /*[M+1]*/,
+                        double *mom /*[M][3]*/)
+{
+    const int q = 2 * k, limit = 4 * k + 1;
+    int P = M;
+    for (int m = 0; m <= M; ++m) edge[m] = m;
+    memcpy(mom, hist, sizeof(double) * (size_t)M * 3);
+    double *e = malloc(sizeof(double) * (size_t)(M / 2 + 1));
+    int *keep = malloc(sizeof(int) * (size_t)(M / 2 + 1));
+    while (P > limit) {
+        const int pairs = P / 2;
+        for (int i = 0; i < pairs; ++i) {
+            const double a = (double)edge[2 * i] / (double)M, b = (double)edge[2 * i + 2] / (double)M;
+            const double s0 = mom[(2 * i) * 3 + 0] + mom[(2 * i + 1) * 3 + 0];
+            const double s1 = mom[(2 * i) * 3 + 1] + mom[(2 * i + 1) * 3 + 1];
+            const double s2 = mom[(2 * i) * 3 + 2] + mom[(2 * i + 1) * 3 + 2];
+            e[i] = -s2 + (a + b) * s1 - a * b * s0;
+        }
+        /* the q pairs with the largest error: pair i stays split if fewer than q pairs come before it
+         * in the order "larger error first, then further left" */
+        for (int i = 0; i < pairs; ++i) {
+            int before = 0;
+            for (int j = 0; j < pairs; ++j)
+                if (e[j] > e[i] || (e[j] == e[i] && j < i)) ++before;
+            keep[i] = before < q;
+        }
+        int out = 0;
+        for (int i = 0; i < pairs; ++i) {
+            if (keep[i]) {
+                for (int h = 0; h < 2; ++h) {
+                    edge[out] = edge[2 * i + h];
+                    for (int c = 0; c < 3; ++c) mom[out * 3 + c] = mom[(2 * i + h) * 3 + c];
+                    ++out;
+                }
+            } else {
+                const double s0 = mom[(2 * i) * 3 + 0] + mom[(2 * i + 1) * 3 + 0];
+                const double s1 = mom[(2 * i) * 3 + 1] + mom[(2 * i + 1) * 3 + 1];
+                const double s2 = mom[(2 * i) * 3 + 2] + mom[(2 * i + 1) * 3 + 2];
+                edge[out] = edge[2 * i];
+                mom[out * 3 + 0] = s0; mom[out * 3 + 1] = s1; mom[out * 3 + 2] = s2;
+                ++out;
+            }
+        }
+        if (P & 1) {
+            edge[out] = edge[P - 1];
+            for (int c = 0; c < 3; ++c) mom[out * 3 + c] = mom[(P - 1) * 3 + c];
+            ++out;
+        }
+        edge[out] = M;
+        P = out;
+    }
+    free(e);
+    free(keep);
+    return P;
+}
+
+/* Levels from the greedy intervals: their end points are the candidates of
+ * the dynamic program (Sec. 3.2, "2-Approximation in Almost-Linear Time").
+ * Same outputs as zo_levels_optimal; grid indices refer to the M-bin grid. */
+void zo_levels_greedy(const double *hist, const float *lo, const float *hi, int64_t d, int bits,
+                      int M, float *levels, uint16_t *grid_idx, double *mean_variance)
+{
+    int K = 1 << bits, s = K - 1;
+    int *edge = malloc(sizeof(int) * ((size_t)M + 1));
+    double *mom = malloc(sizeof(double) * (size_t)M * 3);
+    double *cand = malloc(sizeof(double) * ((size_t)M + 1));
+    int *idx = malloc(sizeof(int) * ((size_t)s + 1));
+    double mv = 0.0;
+    for (int64_t j = 0; j < d; ++j) {
+        const double *h = hist + (size_t)j * M * 3;
+        double cnt = 0.0;
+        for (int m = 0; m < M; ++m) cnt += h[m * 3];
+        const int P = zo_greedy_intervals(h, M, s, edge, mom);
+        for (int m = 0; m <= P; ++m) cand[m] = (double)edge[m] / (double)M;
+        double total = zo_dp_levels(mom, cand, P, s, idx);
+        if (cnt > 0.0) mv += total / cnt;
+        double l = (double)lo[j], w = (double)hi[j] - (double)lo[j];
+        for (int c = 0; c < K; ++c) {
+            const int g = edge[idx[c]];
+            if (grid_idx) grid_idx[j * K + c] = (uint16_t)g;
+            levels[j * K + c] = (float)(l + (w * (double)g) / (double)M);
+        }
+    }
+    if (mean_variance) *mean_variance = mv / (double)d;
+    free(edge); free(mom); free(cand); free(idx);
 }
 
 /* ------------------------------------------------------------------------- */

@@ -149,3 +149,83 @@ def test_hist_moments_and_levels_optimal_end_to_end():
     var_opt = total_variance(tj, G[0] / M)
     var_uni = total_variance(tj, np.arange(4) / 3)
     assert var_opt < 0.6 * var_uni
+
+
+# ------------------------------------------------------------------ greedy intervals (supplement, Algorithm 1)
+def test_greedy_intervals_worked_by_hand():
+    """M = 8 bins, k = 1 (2 pairs stay split, at most 5 intervals).  Errors of the merged pairs, by
+    the definition err = sum (b - t)(t - a):
+      round 1: [0,.25): .2*.05 + .15*.1 = .025   [.25,.5): .2*.05 = .010
+               [.5,.75): .2*.05 + .15*.1 + .05*.2 = .035   [.75,1]: .05*.2 = .010
+               -> first and third stay split: edges 0 1 2 4 5 6 8 (6 intervals)
+      round 2: [0,.25): .025   [.25,.625): .325*.05 + .075*.3 + .025*.35 = .0475
+               [.625,1]: .3*.075 + .05*.325 = .03875
+               -> second and third stay split: edges 0 2 4 5 6 8 (5 intervals, done)."""
+    t = np.array([0.05, 0.10, 0.30, 0.55, 0.60, 0.70, 0.95])
+    M = 8
+    mom = oracle.bin_moments(t, np.arange(M + 1) / M)
+    edge, out = oracle.greedy_intervals(mom, 1)
+    assert edge.tolist() == [0, 2, 4, 5, 6, 8]
+    assert out[:, 0].tolist() == [2, 1, 2, 1, 1]
+    assert np.allclose(out, oracle.bin_moments(t, edge / M), rtol=0, atol=1e-15)
+
+
+def test_greedy_intervals_ties_go_left():
+    """One point in the middle of each of 16 bins, k = 1: every number is a short dyadic fraction, so
+    equal errors are equal to the last bit and the rule for ties decides.
+      round 1: 8 equal pairs, the two on the left stay split: 0 1 2 3 4 6 8 10 12 14 16
+      round 2: pairs [0,2) [2,4) (2 points) [4,8) [8,12) [12,16) (4 points, larger): the first two
+               of the three large ones stay split: 0 2 4 6 8 10 12 16
+      round 3: [0,4) [4,8) [8,12) equal (the odd interval [12,16) is left alone): 0 2 4 6 8 12 16
+      round 4: [0,4) [4,8) (4 points) [8,16) (8 points): 0 2 4 8 12 16."""
+    M = 16
+    t = (np.arange(M) + 0.5) / M
+    edge, out = oracle.greedy_intervals(oracle.bin_moments(t, np.arange(M + 1) / M), 1)
+    assert edge.tolist() == [0, 2, 4, 8, 12, 16]
+    assert out[:, 0].tolist() == [2, 2, 4, 4, 4]
+
+
+@pytest.mark.parametrize("M,k,seed", [(64, 3, 0), (128, 7, 1), (256, 7, 2), (100, 4, 3), (512, 15, 4)])
+def test_greedy_intervals_within_twice_the_optimum(M, k, seed):
+    """The supplement's theorem with gamma = 1: at most 4k + 1 intervals whose error, taken from the
+    points by the definition, is at most 2 OPT_k (OPT_k from the dynamic program over all bin edges)."""
+    rng = np.random.default_rng(seed)
+    t = np.concatenate([rng.beta(0.6, 2.5, 4000), rng.uniform(0.7, 0.9, 500), [0.0, 1.0]])
+    cand = np.arange(M + 1) / M
+    mom = oracle.bin_moments(t, cand)
+    edge, out = oracle.greedy_intervals(mom, k)
+    P = len(edge) - 1
+    assert k <= P <= 4 * k + 1
+    assert edge[0] == 0 and edge[-1] == M and np.all(np.diff(edge) > 0)
+    assert np.allclose(out, oracle.bin_moments(t, edge / M), rtol=1e-12, atol=1e-12)
+    opt, _ = oracle.dp_levels(mom, cand, k)
+    assert opt > 0
+    assert total_variance(t, edge / M) <= 2.0 * opt * (1 + 1e-12)
+
+
+def test_levels_greedy_against_the_full_dynamic_program():
+    rng = np.random.default_rng(11)
+    n, d, M, bits = 4000, 4, 256, 3
+    A = np.exp(rng.standard_normal((n, d))).astype(np.float32)
+    # column 3: eight clusters on bin edges -> the optimum is zero and the greedy search must keep it
+    pos = np.array([0, 16, 40, 64, 100, 160, 200, 256]) / M
+    A[:, 3] = pos[rng.integers(0, 8, n)]
+    A[:8, 3] = pos
+    lo, hi = oracle.col_range(A)
+    hist = oracle.hist_moments(A, lo, hi, M)
+    Lg, Gg, mvg = oracle.levels_greedy(hist, lo, hi, bits)
+    Lo, Go, mvo = oracle.levels_optimal(hist, lo, hi, bits)
+    assert np.array_equal(Gg[3], (pos * M).astype(np.uint16)) and np.array_equal(Gg[3], Go[3])
+    assert np.all(Gg[:, 0] == 0) and np.all(Gg[:, -1] == M) and np.all(np.diff(Gg.astype(int), axis=1) > 0)
+    for j in range(d):
+        tg, _ = oracle.dp_levels(hist[j], np.arange(M + 1) / M, 7)
+        tj = (A[:, j].astype(np.float64) - lo[j]) / (float(hi[j]) - float(lo[j]))
+        vg = total_variance(tj, Gg[j] / M)
+        assert vg >= tg * (1 - 1e-9) - 1e-9            # k intervals cannot beat the optimum ...
+        assert vg <= 2.0 * tg * (1 + 1e-9) + 1e-9      # ... and stay within the factor the paper gives
+    assert mvo <= mvg * (1 + 1e-12) <= 2 * mvo * (1 + 1e-9) + 1e-12
+    # with no more than 4k + 1 bins nothing is merged: the plain dynamic program
+    hist2 = oracle.hist_moments(A, lo, hi, 29)
+    L1, G1, mv1 = oracle.levels_greedy(hist2, lo, hi, bits)
+    L2, G2, mv2 = oracle.levels_optimal(hist2, lo, hi, bits)
+    assert np.array_equal(G1, G2) and np.array_equal(L1, L2) and mv1 == mv2
