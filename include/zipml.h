@@ -49,6 +49,7 @@ extern "C" {
 /* ---- modes and flags ---------------------------------------------------------------------- */
 #define ZIPML_UNIFORM 0          /* 2^bits evenly spaced levels on [lo_j, hi_j]    (Sec. 2.1)     */
 #define ZIPML_OPTIMAL 1          /* variance-optimal levels by dynamic programming (Sec. 3)       */
+#define ZIPML_GREEDY 2           /* the same over the candidates a greedy search leaves (Sec. 3.2) */
 
 #define ZIPML_RANGE_GIVEN 1      /* zipml_levels: lo_dev / hi_dev are inputs                      */
 #define ZIPML_SYMMETRIC   2      /* zipml_levels: range [-M_j, M_j], M_j = max(|min|, |max|)
@@ -67,7 +68,7 @@ size_t zipml_packed_bytes(int64_t n, int64_t d, int bits);
 
 /* Bytes of device workspace that zipml_levels, zipml_sgd_epoch, zipml_debug_step and zipml_loss
  * need for a problem of this shape (one buffer serves all of them, one call at a time).
- * n_candidates may be 0 if ZIPML_OPTIMAL is never used. */
+ * n_candidates may be 0 if neither ZIPML_OPTIMAL nor ZIPML_GREEDY is used. */
 size_t zipml_workspace_bytes(int64_t n, int64_t d, int bits, int64_t batch, int n_candidates);
 
 /* Per-feature quantisation levels.
@@ -78,10 +79,18 @@ size_t zipml_workspace_bytes(int64_t n, int64_t d, int bits, int64_t batch, int 
  * levels_dev[d][2^bits] is written.  grid_idx_dev[d][2^bits] (optional, may be NULL) receives the
  * integer grid position of every level: c for UNIFORM, the chosen bin edge for OPTIMAL, so that
  * level = lo_j + (hi_j - lo_j) * grid_idx / grid_max with grid_max = 2^bits - 1 or n_candidates.
- * mean_variance_host (optional, OPTIMAL only) receives the objective of eq. (6) averaged over
- * features.  UNIFORM is asynchronous; OPTIMAL copies the bin moments to the host, runs the dynamic
- * program on the host cores and copies the levels back, so it synchronises the stream.
- * bits in 1..8; OPTIMAL needs 2^bits - 1 <= n_candidates <= 4096. */
+ * mean_variance_host (optional, OPTIMAL and GREEDY only) receives the objective of eq. (6)
+ * averaged over features.  UNIFORM is asynchronous.  OPTIMAL runs the dynamic program on the device
+ * when its tables fit in on-chip memory (then only a request for mean_variance_host synchronises
+ * the stream); otherwise it copies the bin moments to the host, runs the dynamic program on the
+ * host cores and copies the levels back, which synchronises the stream.
+ * GREEDY (Sec. 3.2, "2-Approximation in Almost-Linear Time"; supplement, Algorithm 1 with
+ * gamma = 1, delta = 1): the bins are first merged greedily into at most 4 (2^bits - 1) + 1
+ * intervals per feature, whose end points are the only candidates of the dynamic program; the
+ * levels are within the factor the paper gives of OPTIMAL's, for a dynamic program over ~4 * 2^bits
+ * instead of n_candidates points.  With n_candidates <= 4 (2^bits - 1) + 1 it is OPTIMAL.  Device
+ * only: ZIPML_EUNSUPPORTED if the tables do not fit (8 bits with more than 1021 candidates).
+ * bits in 1..8; OPTIMAL and GREEDY need 2^bits - 1 <= n_candidates <= 4096. */
 int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t d, int64_t lda, int bits,
                  int mode, int flags, int n_candidates, float *lo_dev, float *hi_dev,
                  float *levels_dev, uint16_t *grid_idx_dev, double *mean_variance_host,

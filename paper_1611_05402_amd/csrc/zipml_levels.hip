@@ -135,21 +135,32 @@ __host__ __device__ inline size_t dp_lds_bytes(int M, int s)
     const size_t W = (size_t)M + 1;
     return 6 * W * sizeof(double) + (((size_t)s + 1) * W * sizeof(uint16_t) + 15) / 16 * 16 + 64;
 }
+// With sel / count (the greedy search below): the candidates of feature j are the count[j] + 1 bin
+// edges sel[j][0 .. count[j]] and hist holds the moments of the intervals between them; Mcap is
+// the largest number of intervals a feature can have (it sizes the tables).
 __global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hist,
                                                    const float *__restrict__ lo,
-                                                   const float *__restrict__ hi, int64_t d, int M,
+                                                   const float *__restrict__ hi, int64_t d, int Mgrid,
                                                    int s, float *__restrict__ levels,
                                                    uint16_t *__restrict__ grid,
-                                                   double *__restrict__ objective)
+                                                   double *__restrict__ objective,
+                                                   const uint16_t *__restrict__ sel,
+                                                   const int *__restrict__ count, int Mcap)
 {
     extern __shared__ __align__(16) unsigned char dp_smem[];
-    const int W = M + 1, K = s + 1, tid = threadIdx.x;
-    double *C = (double *)dp_smem, *S1 = C + W, *S2 = S1 + W, *edge = S2 + W, *prev = edge + W,
-           *cur = prev + W;
-    uint16_t *arg = (uint16_t *)(cur + W);                       // [s+1][W]
+    const int K = s + 1, tid = threadIdx.x;
+    const int Wcap = Mcap + 1;
+    double *C = (double *)dp_smem, *S1 = C + Wcap, *S2 = S1 + Wcap, *edge = S2 + Wcap,
+           *prev = edge + Wcap, *cur = prev + Wcap;
+    uint16_t *arg = (uint16_t *)(dp_smem + 6 * (size_t)Wcap * sizeof(double));   // [s+1][W]
     const double INF = __longlong_as_double(0x7FF0000000000000ll);
     for (int64_t j = blockIdx.x; j < d; j += gridDim.x) {
-        const double *mom = hist + (size_t)j * M * 3;
+        const double *mom = hist + (size_t)j * Mgrid * 3;
+        const uint16_t *cand = sel ? sel + (size_t)j * (Mgrid + 1) : nullptr;
+        const int M = sel ? count[j] : Mgrid;
+        const int W = M + 1;
+        prev = edge + Wcap;
+        cur = prev + Wcap;
         __syncthreads();
         // prefix moments, in index order (three chains, one thread each)
         if (tid < 3) {
@@ -162,7 +173,7 @@ __global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hi
             }
         }
         for (int m = tid; m < W; m += 256) {
-            edge[m] = (double)m / (double)M;
+            edge[m] = (double)(cand ? (int)cand[m] : m) / (double)Mgrid;
             prev[m] = INF;
         }
         __syncthreads();
@@ -198,13 +209,123 @@ __global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hi
             const double l = (double)lo[j], w = (double)hi[j] - l;
             int m = M;
             for (int k = s; k >= 1; --k) {
-                if (grid) grid[(size_t)j * K + k] = (uint16_t)m;
-                levels[(size_t)j * K + k] = (float)(l + (w * (double)m) / (double)M);
+                const int g = cand ? (int)cand[m] : m;
+                if (grid) grid[(size_t)j * K + k] = (uint16_t)g;
+                levels[(size_t)j * K + k] = (float)(l + (w * (double)g) / (double)Mgrid);
                 m = arg[(size_t)k * W + m];
             }
             if (grid) grid[(size_t)j * K] = 0;
-            levels[(size_t)j * K] = (float)(l + (w * 0.0) / (double)M);
+            levels[(size_t)j * K] = (float)(l + (w * 0.0) / (double)Mgrid);
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Greedy merging of intervals (supplement, "A Greedy Algorithm for Finding Quantization Points",
+// Algorithm 1, with gamma = 1 and delta = 1), on the M bins of the candidate grid: one workgroup
+// per feature, the partition and the moments of its intervals in LDS.  While more than 4k + 1
+// intervals are left, consecutive intervals are paired up (an odd one at the end stays), every
+// pair gets the error of the merged interval [a, b], -S2 + (a + b) S1 - a b S0, from the sum of
+// the two intervals' moments; the 2k pairs with the largest error (equal errors: further left
+// first) stay split, the others are merged.  The end points that are left become the candidates
+// of the dynamic program (Sec. 3.2): the moments of the intervals replace the feature's bin
+// moments in place, sel[j][0 .. count[j]] are the bin edges.
+// Every pair's rank is found by counting (no sort: the order of equal errors is part of the
+// result); the partition is compacted in place, 256 pairs at a time: a pair's new position is
+// never behind its old one, so a block of pairs that has been read can be written before the
+// next block is read.
+__host__ __device__ inline size_t greedy_lds_bytes(int M)
+{
+    return (size_t)M * 3 * sizeof(double) + ((size_t)M / 2 + 2) * sizeof(double) +
+           ((size_t)M + 2 + 2 * ((size_t)M / 2 + 2)) * sizeof(int) + 64;
+}
+__global__ __launch_bounds__(256) void k_greedy_intervals(double *__restrict__ hist, int64_t d, int M,
+                                                          int k, uint16_t *__restrict__ sel,
+                                                          int *__restrict__ count)
+{
+    extern __shared__ __align__(16) unsigned char gr_smem[];
+    const int tid = threadIdx.x;
+    double *mom = (double *)gr_smem;                 // [M][3]
+    double *e = mom + (size_t)M * 3;                 // [M/2 + 2]
+    int *edge = (int *)(e + M / 2 + 2);              // [M + 2]
+    int *keep = edge + M + 2;                        // [M/2 + 2]
+    int *offs = keep + M / 2 + 2;                    // [M/2 + 2]
+    const int q = 2 * k, limit = 4 * k + 1;
+    for (int64_t j = blockIdx.x; j < d; j += gridDim.x) {
+        double *h = hist + (size_t)j * M * 3;
+        __syncthreads();
+        for (int m = tid; m < M * 3; m += 256) mom[m] = h[m];
+        for (int m = tid; m <= M; m += 256) edge[m] = m;
+        __syncthreads();
+        int P = M;
+        while (P > limit) {
+            const int pairs = P / 2;
+            for (int i = tid; i < pairs; i += 256) {
+                const double a = (double)edge[2 * i] / (double)M, b = (double)edge[2 * i + 2] / (double)M;
+                const double s0 = mom[(2 * i) * 3 + 0] + mom[(2 * i + 1) * 3 + 0];
+                const double s1 = mom[(2 * i) * 3 + 1] + mom[(2 * i + 1) * 3 + 1];
+                const double s2 = mom[(2 * i) * 3 + 2] + mom[(2 * i + 1) * 3 + 2];
+                e[i] = -s2 + (a + b) * s1 - a * b * s0;
+            }
+            __syncthreads();
+            for (int i = tid; i < pairs; i += 256) {
+                const double ei = e[i];
+                int before = 0;
+                for (int jj = 0; jj < pairs; ++jj) {
+                    const double ej = e[jj];
+                    before += (ej > ei || (ej == ei && jj < i)) ? 1 : 0;
+                }
+                keep[i] = before < q ? 1 : 0;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int out = 0;
+                for (int i = 0; i < pairs; ++i) { offs[i] = out; out += keep[i] ? 2 : 1; }
+                offs[pairs] = out;
+            }
+            __syncthreads();
+            const int odd = P & 1;
+            // the odd interval at the end: taken out before anything is overwritten
+            const int last_edge = edge[P - 1];
+            const double l0 = mom[(P - 1) * 3 + 0], l1 = mom[(P - 1) * 3 + 1], l2 = mom[(P - 1) * 3 + 2];
+            const int newP = offs[pairs] + odd;
+            __syncthreads();
+            for (int base = 0; base < pairs; base += 256) {
+                const int i = base + tid;
+                int e0 = 0, e1 = 0, kp = 0, o = 0;
+                double a0 = 0, a1 = 0, a2 = 0, b0 = 0, b1 = 0, b2 = 0;
+                if (i < pairs) {
+                    e0 = edge[2 * i]; e1 = edge[2 * i + 1]; kp = keep[i]; o = offs[i];
+                    a0 = mom[(2 * i) * 3 + 0]; a1 = mom[(2 * i) * 3 + 1]; a2 = mom[(2 * i) * 3 + 2];
+                    b0 = mom[(2 * i + 1) * 3 + 0]; b1 = mom[(2 * i + 1) * 3 + 1]; b2 = mom[(2 * i + 1) * 3 + 2];
+                }
+                __syncthreads();
+                if (i < pairs) {
+                    if (kp) {
+                        edge[o] = e0; edge[o + 1] = e1;
+                        mom[o * 3 + 0] = a0; mom[o * 3 + 1] = a1; mom[o * 3 + 2] = a2;
+                        mom[(o + 1) * 3 + 0] = b0; mom[(o + 1) * 3 + 1] = b1; mom[(o + 1) * 3 + 2] = b2;
+                    } else {
+                        edge[o] = e0;
+                        mom[o * 3 + 0] = a0 + b0; mom[o * 3 + 1] = a1 + b1; mom[o * 3 + 2] = a2 + b2;
+                    }
+                }
+            }
+            __syncthreads();
+            if (tid == 0) {
+                if (odd) {
+                    const int o = newP - 1;
+                    edge[o] = last_edge;
+                    mom[o * 3 + 0] = l0; mom[o * 3 + 1] = l1; mom[o * 3 + 2] = l2;
+                }
+                edge[newP] = M;
+            }
+            __syncthreads();
+            P = newP;
+        }
+        for (int m = tid; m < P * 3; m += 256) h[m] = mom[m];
+        for (int m = tid; m <= P; m += 256) sel[(size_t)j * (M + 1) + m] = (uint16_t)edge[m];
+        if (tid == 0) count[j] = P;
     }
 }
 
@@ -254,7 +375,9 @@ static size_t levels_workspace_bytes(int64_t d, int n_candidates)
     size_t keys = (size_t)round_up(d * 8, 256);
     size_t hist = (size_t)d * (size_t)n_candidates * 3 * sizeof(double);
     size_t objective = (size_t)d * sizeof(double);     // per-feature value of the dynamic program
-    return keys + hist + objective;
+    // candidates left by the greedy search: bin edges [d][n_candidates + 1] uint16, their number [d]
+    size_t greedy = n_candidates > 0 ? (size_t)round_up(d * ((int64_t)n_candidates + 1) * 2, 256) + (size_t)d * 4 : 0;
+    return keys + hist + objective + greedy;
 }
 
 }  // namespace zipml
@@ -279,16 +402,17 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
                             size_t workspace_bytes)
 {
     if (!lo_dev || !hi_dev || !levels_dev || d <= 0 || !valid_bits(bits)) return ZIPML_EINVAL;
-    if (mode != ZIPML_UNIFORM && mode != ZIPML_OPTIMAL) return ZIPML_EINVAL;
+    if (mode != ZIPML_UNIFORM && mode != ZIPML_OPTIMAL && mode != ZIPML_GREEDY) return ZIPML_EINVAL;
+    const bool search = mode == ZIPML_OPTIMAL || mode == ZIPML_GREEDY;
     if (flags & ~(ZIPML_RANGE_GIVEN | ZIPML_SYMMETRIC)) return ZIPML_EINVAL;
-    const bool need_data = !(flags & ZIPML_RANGE_GIVEN) || mode == ZIPML_OPTIMAL;
+    const bool need_data = !(flags & ZIPML_RANGE_GIVEN) || search;
     if (need_data && (!A_dev || n <= 0 || lda < d)) return ZIPML_EINVAL;
     const int K = 1 << bits;
-    if (mode == ZIPML_OPTIMAL && (n_candidates < K - 1 || n_candidates > 4096)) return ZIPML_EINVAL;
+    if (search && (n_candidates < K - 1 || n_candidates > 4096)) return ZIPML_EINVAL;
     if (!aligned16(lo_dev) || !aligned16(hi_dev) || !aligned16(levels_dev) ||
         (grid_idx_dev && !aligned16(grid_idx_dev)) || (A_dev && (reinterpret_cast<uintptr_t>(A_dev) & 3u)))
         return ZIPML_EALIGN;
-    const size_t need = levels_workspace_bytes(d, mode == ZIPML_OPTIMAL ? n_candidates : 0);
+    const size_t need = levels_workspace_bytes(d, search ? n_candidates : 0);
     if (need_data && (!workspace_dev || workspace_bytes < need || !aligned16(workspace_dev)))
         return ZIPML_EWORKSPACE;
     hipStream_t s = entry_stream(stream);
@@ -330,16 +454,37 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
     if (HIP_FAILED(hipGetDevice(&dev)) ||
         HIP_FAILED(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev)))
         return ZIPML_ELAUNCH;
-    const size_t dp_lds = dp_lds_bytes(M, sI);
-    if (dp_lds <= (size_t)lds_limit && !getenv("ZIPML_HOST_DP")) {
+    // GREEDY: the greedy search leaves at most 4 (K - 1) + 1 intervals per feature, whose end points
+    // are the candidates of the dynamic program; with no more bins than that nothing is merged and
+    // the search is the plain one.  Both steps run on the device (no host version).
+    const int Mcap = 4 * sI + 1;
+    const bool greedy = mode == ZIPML_GREEDY && M > Mcap;
+    const size_t dp_lds = greedy ? dp_lds_bytes(Mcap, sI) : dp_lds_bytes(M, sI);
+    if (greedy && (dp_lds > (size_t)lds_limit || greedy_lds_bytes(M) > (size_t)lds_limit))
+        return ZIPML_EUNSUPPORTED;
+    if (greedy || (dp_lds <= (size_t)lds_limit && !getenv("ZIPML_HOST_DP"))) {
         double *objective_dev = hist_dev + hcount;
         uint16_t *grid_dev = grid_idx_dev;       // may be null
+        uint16_t *sel_dev = nullptr;
+        int *count_dev = nullptr;
+        const unsigned blocks = (unsigned)(d < 2048 ? d : 2048);
+        if (greedy) {
+            sel_dev = (uint16_t *)(objective_dev + d);
+            count_dev = (int *)((unsigned char *)sel_dev + round_up(d * ((int64_t)M + 1) * 2, 256));
+            const size_t gr_lds = greedy_lds_bytes(M);
+            if (HIP_FAILED(hipFuncSetAttribute((const void *)k_greedy_intervals,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gr_lds)))
+                return ZIPML_ELAUNCH;
+            hipLaunchKernelGGL(k_greedy_intervals, dim3(blocks), dim3(256), gr_lds, s, hist_dev, d, M, sI,
+                               sel_dev, count_dev);
+            if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+        }
         if (HIP_FAILED(hipFuncSetAttribute((const void *)k_dp_levels,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dp_lds)))
             return ZIPML_ELAUNCH;
-        const unsigned blocks = (unsigned)(d < 2048 ? d : 2048);
         hipLaunchKernelGGL(k_dp_levels, dim3(blocks), dim3(256), dp_lds, s, hist_dev, lo_dev, hi_dev, d,
-                           M, sI, levels_dev, grid_dev, objective_dev);
+                           M, sI, levels_dev, grid_dev, objective_dev, (const uint16_t *)sel_dev,
+                           (const int *)count_dev, greedy ? Mcap : M);
         if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
         if (mean_variance_host) {
             std::vector<double> per_feature((size_t)d);

@@ -13,7 +13,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libzipml.so")
 
-UNIFORM, OPTIMAL = 0, 1
+UNIFORM, OPTIMAL, GREEDY = 0, 1, 2
 RANGE_GIVEN, SYMMETRIC = 1, 2
 SGD_STEPWISE, SGD_AVERAGED = 1, 2
 PROX_NONE, PROX_L1, PROX_L2SQ, PROX_BOX = 0, 1, 2, 3

@@ -103,6 +103,73 @@ def test_device_and_host_level_search_agree(monkeypatch):
         assert np.all(G[:, 0] == 0) and np.all(G[:, -1] == 512) and np.all(np.diff(G.astype(np.int32), axis=1) > 0)
 
 
+def test_greedy_levels_bit_exact_on_dyadic_data():
+    """Greedy merging of the bins, then the dynamic program over the end points that are left
+    (Sec. 3.2; supplement, Algorithm 1).  The values are multiples of 2^-10 on a given range [0, 1],
+    so the bin moments are exact whatever the order of their sums, and every later step has a fixed
+    order: levels, grid indices and objective must be those of the oracle, bit for bit."""
+    say("levels greedy: dyadic data")
+    rng = np.random.default_rng(5)
+    n, d = 6000, 40
+    t = np.concatenate([rng.beta(0.5, 3.0, (n // 2, d)), rng.beta(4.0, 1.5, (n - n // 2, d))])
+    t[:, 7] = rng.integers(0, 5, n) / 4.0                   # a column with five values
+    t[:, 8] = 0.375                                         # a constant column
+    A = (np.round(t * 1024) / 1024).astype(np.float32)
+    b = np.zeros(n, np.float32)
+    for bits, M in ((2, 256), (3, 512), (4, 1024), (5, 2000)):
+        p = GpuProblem(A, b, bits, 32, n_candidates=M)
+        mv = p.make_levels(zipml.GREEDY, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=M, want_mv=True)
+        hist = oracle.hist_moments(A, np.zeros(d, np.float32), np.ones(d, np.float32), M)
+        L, G, mv_ref = oracle.levels_greedy(hist, np.zeros(d, np.float32), np.ones(d, np.float32), bits)
+        say(f"  bits {bits}, {M} bins: objective {mv:.6e} (oracle {mv_ref:.6e})")
+        assert np.array_equal(p.grid.cpu().numpy().view(np.uint16), G)
+        assert np.array_equal(p.levels.cpu().numpy(), L)
+        assert mv == mv_ref
+        # not the plain search: on some feature the greedy candidates miss the optimum
+        Lo, Go, mvo = oracle.levels_optimal(hist, np.zeros(d, np.float32), np.ones(d, np.float32), bits)
+        assert mvo <= mv <= 2 * mvo
+    # with few bins nothing is merged: the plain search, on the device or on the host
+    p = GpuProblem(A, b, 3, 32, n_candidates=29)
+    p.make_levels(zipml.GREEDY, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=29)
+    g1 = p.grid.cpu().numpy().copy()
+    p.make_levels(zipml.OPTIMAL, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=29)
+    assert np.array_equal(g1, p.grid.cpu().numpy())
+    # tables that do not fit on the chip are refused
+    p = GpuProblem(A, b, 8, 32, n_candidates=2048)
+    with pytest.raises(zipml.ZipmlError) as e:
+        p.make_levels(zipml.GREEDY, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=2048)
+    assert e.value.code == zipml.EUNSUPPORTED
+
+
+def test_greedy_levels_on_float_data():
+    """Ordinary data: the device accumulates the bin moments with atomics, so their last bits --
+    and with them a near-tie in the greedy search -- may differ from the oracle's.  What must hold
+    either way: valid levels on the grid, an objective between the optimum and twice the optimum,
+    and the oracle's choice on nearly every feature."""
+    say("levels greedy: float data")
+    w = synth.e2e(n=6000, d=40, n_candidates=512)
+    A, b = w.full()
+    M, bits = 512, 3
+    p = GpuProblem(A, b, bits, 32, n_candidates=M)
+    mv = p.make_levels(zipml.GREEDY, 0, n_candidates=M, want_mv=True)
+    lo, hi = oracle.col_range(A)
+    hist = oracle.hist_moments(A, lo, hi, M)
+    L, G, mv_ref = oracle.levels_greedy(hist, lo, hi, bits)
+    _, _, mv_opt = oracle.levels_optimal(hist, lo, hi, bits)
+    Gg = p.grid.cpu().numpy().view(np.uint16)
+    Lg = p.levels.cpu().numpy()
+    assert np.all(Gg[:, 0] == 0) and np.all(Gg[:, -1] == M) and np.all(np.diff(Gg.astype(int), axis=1) > 0)
+    for j in range(w.d):
+        expect = (lo[j].astype(np.float64) + (float(hi[j]) - float(lo[j])) * Gg[j] / M)
+        assert np.array_equal(Lg[j], expect.astype(np.float32))
+    same = np.mean([np.array_equal(Gg[j], G[j]) for j in range(w.d)])
+    say(f"  objective {mv:.6e}, oracle {mv_ref:.6e}, optimum {mv_opt:.6e}; same levels on {same:.0%} of the features")
+    assert same > 0.9
+    assert mv_opt * (1 - 1e-9) <= mv <= 2 * mv_opt
+    if same == 1.0:
+        assert np.isclose(mv, mv_ref, rtol=1e-9)
+
+
 # ------------------------------------------------------------------ quantise
 QCASES = [
     # name, n, d, bits, level spec
