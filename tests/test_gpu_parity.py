@@ -116,7 +116,7 @@ def test_greedy_levels_bit_exact_on_dyadic_data():
     t[:, 8] = 0.375                                         # a constant column
     A = (np.round(t * 1024) / 1024).astype(np.float32)
     b = np.zeros(n, np.float32)
-    for bits, M in ((2, 256), (3, 512), (4, 1024), (5, 2000)):
+    for bits, M in ((2, 256), (3, 512), (4, 1024), (5, 2000), (3, 4096), (1, 77)):
         p = GpuProblem(A, b, bits, 32, n_candidates=M)
         mv = p.make_levels(zipml.GREEDY, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=M, want_mv=True)
         hist = oracle.hist_moments(A, np.zeros(d, np.float32), np.ones(d, np.float32), M)
@@ -128,6 +128,16 @@ def test_greedy_levels_bit_exact_on_dyadic_data():
         # not the plain search: on some feature the greedy candidates miss the optimum
         Lo, Go, mvo = oracle.levels_optimal(hist, np.zeros(d, np.float32), np.ones(d, np.float32), bits)
         assert mvo <= mv <= 2 * mvo
+    # more features than the launch has workgroups (each then takes several)
+    n2, d2, M2 = 512, 2100, 512
+    A2 = (rng.integers(0, 1025, (n2, d2)) ** 2 / 1024 ** 2 * 1024).round().astype(np.float32) / 1024
+    z2, o2 = np.zeros(d2, np.float32), np.ones(d2, np.float32)
+    p = GpuProblem(A2, np.zeros(n2, np.float32), 2, 32, n_candidates=M2)
+    mv = p.make_levels(zipml.GREEDY, 0, lo=z2, hi=o2, n_candidates=M2, want_mv=True)
+    L, G, mv_ref = oracle.levels_greedy(oracle.hist_moments(A2, z2, o2, M2), z2, o2, 2)
+    assert np.array_equal(p.grid.cpu().numpy().view(np.uint16), G)
+    assert np.array_equal(p.levels.cpu().numpy(), L)
+    assert np.isclose(mv, mv_ref, rtol=1e-12)      # (the mean over 2100 features is summed on the host)
     # with few bins nothing is merged: the plain search, on the device or on the host
     p = GpuProblem(A, b, 3, 32, n_candidates=29)
     p.make_levels(zipml.GREEDY, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=29)
