@@ -138,6 +138,24 @@ def test_greedy_levels_bit_exact_on_dyadic_data():
     assert np.array_equal(p.grid.cpu().numpy().view(np.uint16), G)
     assert np.array_equal(p.levels.cpu().numpy(), L)
     assert np.isclose(mv, mv_ref, rtol=1e-12)      # (the mean over 2100 features is summed on the host)
+    # The bin moments are gathered in one of two ways: many features -> a workgroup has all rows of
+    # its features and stores its bins; few features -> slabs of rows, added up in memory.  On this
+    # data both give the same moments exactly, so 300 features at once (first way: at 4096 bins one
+    # feature per workgroup) must get the levels that slices of 40 of them get (second way, the one
+    # compared with the oracle above).
+    n3, d3, M3 = 2048, 300, 4096
+    A3 = (rng.beta(0.7, 2.0, (n3, d3)) * 1024).round().astype(np.float32) / 1024
+    z3, o3 = np.zeros(d3, np.float32), np.ones(d3, np.float32)
+    p = GpuProblem(A3, np.zeros(n3, np.float32), 3, 32, n_candidates=M3)
+    p.make_levels(zipml.GREEDY, 0, lo=z3, hi=o3, n_candidates=M3)
+    G_all = p.grid.cpu().numpy().view(np.uint16).copy()
+    for c0 in range(0, d3, 40):
+        sl = slice(c0, min(c0 + 40, d3))
+        q = GpuProblem(np.ascontiguousarray(A3[:, sl]), np.zeros(n3, np.float32), 3, 32, n_candidates=M3)
+        q.make_levels(zipml.GREEDY, 0, lo=z3[sl], hi=o3[sl], n_candidates=M3)
+        assert np.array_equal(q.grid.cpu().numpy().view(np.uint16), G_all[sl])
+    L, G, _ = oracle.levels_greedy(oracle.hist_moments(A3[:, :8], z3[:8], o3[:8], M3), z3[:8], o3[:8], 3)
+    assert np.array_equal(G_all[:8], G)
     # with few bins nothing is merged: the plain search, on the device or on the host
     p = GpuProblem(A, b, 3, 32, n_candidates=29)
     p.make_levels(zipml.GREEDY, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=29)
