@@ -82,9 +82,41 @@ def test_argument_errors_are_codes_not_crashes(lib):
     assert sgd(n=1 << 20, d=1 << 20, bits=8, batch=32, mb=8, grid=fake, gmax=255) == zipml.ERANGE
     assert sgd(epoch=1 << 24) == zipml.EINVAL
     # levels
-    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, 2, 0, 0, fake, fake, fake, null, None, fake, 1 << 20) == zipml.EINVAL
+    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, 7, 0, 0, fake, fake, fake, null, None, fake, 1 << 20) == zipml.EINVAL   # no such mode
+    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, zipml.GREEDY, 0, 8, fake, fake, fake, null, None, fake, 1 << 20) == zipml.EINVAL   # M < 2^bits - 1
+    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, zipml.GREEDY, 0, 5000, fake, fake, fake, null, None, fake, 1 << 30) == zipml.EINVAL  # M > 4096
+    assert lib.zipml_levels(null, fake, 64, 8, 8, 4, zipml.GREEDY, 0, 512, fake, fake, fake, null, None, fake, 1024) == zipml.EWORKSPACE
+    # the workspace covers the candidates the greedy search leaves: edges [d][M + 1] uint16 and their number [d]
+    assert zipml.workspace_bytes(64, 8, 4, 16, 512) >= 8 * 512 * 24 + 8 * 8 + 8 * 513 * 2 + 8 * 4
     assert lib.zipml_levels(null, fake, 64, 8, 8, 4, zipml.OPTIMAL, 0, 8, fake, fake, fake, null, None, fake, 1 << 20) == zipml.EINVAL  # M < 2^bits - 1
     assert lib.zipml_levels(null, fake, 64, 8, 8, 4, zipml.UNIFORM, 0, 0, fake, fake, fake, null, None, fake, 8) == zipml.EWORKSPACE
+    # proximal step, symmetrised estimator
+    def prox(kind=zipml.PROX_L1, coef=0.1, n=64, batch=16, x=fake):
+        return lib.zipml_sgd_epoch_prox(null, fake, fake, fake, fake, n, 8, 4, x, batch, 0.1, 0.0, kind, coef,
+                                        0, fake, 1 << 20)
+    assert prox(kind=9) == zipml.EINVAL
+    assert prox(coef=-1.0) == zipml.EINVAL
+    assert prox(coef=float("nan")) == zipml.EINVAL
+    assert prox(batch=24) == zipml.EINVAL
+    assert prox(x=odd) == zipml.EALIGN
+
+    def avg(p1s=fake, p2s=fake, bits=4, batch=64, flags=0):
+        return lib.zipml_sgd_epoch_avg(null, fake, fake, p1s, p2s, fake, fake, 128, 8, bits, fake, batch, 0.1,
+                                       0.0, flags, fake, 1 << 20)
+    assert avg(p1s=null) == zipml.EINVAL
+    assert avg(p2s=odd) == zipml.EALIGN
+    assert avg(bits=3) == zipml.EUNSUPPORTED        # 2-, 4- or 8-bit codes only
+    assert avg(batch=32) == zipml.EUNSUPPORTED      # whole blocks of 64 samples
+    assert avg(flags=zipml.SGD_STEPWISE) == zipml.EUNSUPPORTED
+    # compact storage
+    assert zipml.compact_bytes(4096, 64, 4) == 4096 * 64 * 6 // 8
+    assert zipml.compact_bytes(1000, 70, 3) == 1024 * 96 * 5 // 8
+    assert zipml.compact_bytes(0, 64, 4) == 0 and zipml.compact_bytes(64, 64, 9) == 0
+    assert lib.zipml_compact_encode(null, fake, null, 64, 8, 4, fake, fake, 256) == zipml.EINVAL
+    assert lib.zipml_compact_encode(null, fake, fake, 64, 8, 4, fake, fake, 8) == zipml.EWORKSPACE
+    assert lib.zipml_compact_encode(null, fake, odd, 64, 8, 4, fake, fake, 256) == zipml.EALIGN
+    assert lib.zipml_compact_decode(null, fake, 64, 8, 0, fake, fake) == zipml.EINVAL
+    assert lib.zipml_compact_decode(null, odd, 64, 8, 4, fake, fake) == zipml.EALIGN
     # loss
     out = C.c_double(0)
     assert lib.zipml_loss(null, fake, 8, null, 2, null, 0, fake, fake, 0, 8, C.byref(out), fake, 1 << 20) == zipml.EINVAL
