@@ -376,7 +376,7 @@ __device__ __forceinline__ void sgd_rows(const RowsArgs &a, unsigned char *smem)
             }
         }
         ZIPML_RTICK(3);
-        grid_sync();
+        if (t + 1 < t_end) grid_sync();      // (after the last step the end of the kernel is the meeting)
         ZIPML_RTICK(4);
     }
 #ifdef ZIPML_PHASE_TIMING
