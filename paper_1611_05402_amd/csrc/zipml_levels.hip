@@ -93,11 +93,10 @@ __global__ void k_zero_f64(double *p, int64_t count)
 // Per-bin moments of the normalised values; hist is [d][M][3] fp64 (count, sum t, sum t^2).
 // One atomic per value and moment straight to memory ran at the rate the memory side takes
 // atomics (about 22 per ns: 18-28 ms for 65,536 x 2048 values).  Here a workgroup owns F
-// consecutive features -- as many as have their M bins in LDS -- and a slab of rows, adds into
-// LDS, and sends what is not zero to memory once at the end.  (LDS takes atomic additions, 32-bit
-// integer or fp64 alike, at about 0.4 per clock and compute unit; three per value is what bounds
-// the kernel now, at 1.4 ms for 65,536 x 2048 values.  The counts are 32-bit integers to save LDS.)  Thread t starts at value t of the
-// slab's rows x F values and moves on by 256, so a wave's lanes spread over features and rows.
+// consecutive features -- as many as have their M bins in LDS, F a divisor of 256 -- and a slab
+// of rows (all rows when the blocks of features fill the device), adds into LDS, and sends its
+// bins to memory once at the end: 0.44 ms for the same matrix.  The counts are 32-bit integers
+// to save LDS; the two sums are fp64.
 __global__ __launch_bounds__(256) void k_hist(const float *__restrict__ A, int64_t n, int64_t d,
                                               int64_t lda, int64_t rows_per_slab,
                                               const float *__restrict__ lo,
@@ -106,58 +105,58 @@ __global__ __launch_bounds__(256) void k_hist(const float *__restrict__ A, int64
 {
     extern __shared__ __align__(16) unsigned char hist_smem[];
     double *sh = (double *)hist_smem;                        // [F][M][2] sum t, sum t^2
-    double *base = sh + (size_t)F * M * 2;                   // [F] lo_j
-    double *width = base + F;                                // [F] hi_j - lo_j
-    uint32_t *cnt = (uint32_t *)(width + F);                 // [F][M] counts (a slab has fewer than 2^32 rows)
+    uint32_t *cnt = (uint32_t *)(sh + (size_t)F * M * 2);    // [F][M] counts (a slab has fewer than 2^32 rows)
     const int tid = threadIdx.x;
-    const int64_t j0 = (int64_t)blockIdx.x * F;
+    // Blocks go round the 8 dies in turn, and neighbouring blocks of features share the cache
+    // lines of every row: block b takes features block (b % 8) * (gridDim.x / 8) + b / 8, so that
+    // neighbours run on one die at about the same time.  (gridDim.x is a multiple of 8; blocks
+    // past the last features block leave.)
+    const int64_t fb = (int64_t)(blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+    const int64_t j0 = fb * F;
+    if (j0 >= d) return;
     const int nf = (int)(d - j0 < F ? d - j0 : F);
     const int64_t i0 = (int64_t)blockIdx.y * rows_per_slab;
     const int64_t i1 = i0 + rows_per_slab < n ? i0 + rows_per_slab : n;
     for (int e = tid; e < nf * M * 2; e += 256) sh[e] = 0.0;
     for (int e = tid; e < nf * M; e += 256) cnt[e] = 0u;
-    if (tid < nf) {
-        base[tid] = (double)lo[j0 + tid];
-        width[tid] = (double)hi[j0 + tid] - (double)lo[j0 + tid];
-    }
     __syncthreads();
-    if (i0 < i1) {
-        // value number v of the slab: row i0 + v / nf, feature v % nf; v advances by 256.  Eight
-        // values are requested before the first is used (one workgroup per compute unit: the
-        // loads in flight are what hides the memory latency).
-        constexpr int U = 8;
-        const int step_rows = 256 / nf, step_f = 256 % nf;
-        int64_t i = i0 + tid / nf;
-        int f = tid % nf;
-        while (i < i1) {
+    // F divides 256: thread t keeps feature t % F for good (its range in registers) and takes the
+    // rows t / F, t / F + 256 / F, ...  Sixteen values are requested before the first is used, with
+    // loads that no branch can skip (rows past the slab repeat its last row and are not counted):
+    // a load behind a branch makes the compiler wait for it on the spot, and one workgroup per
+    // compute unit has nothing else to hide that latency with.  Nothing in the loop reads LDS, so
+    // the additions are never waited for.
+    const int f = tid % F;
+    const bool live_col = f < nf;
+    if (i0 < i1 && live_col) {
+        constexpr int U = 16;
+        const int rows_step = 256 / F;
+        const double l = (double)lo[j0 + f], w = (double)hi[j0 + f] - (double)lo[j0 + f];
+        const float *col = A + j0 + f;
+        double *hf = sh + (size_t)f * M * 2;
+        uint32_t *cf = cnt + (size_t)f * M;
+        for (int64_t i = i0 + tid / F; i < i1; i += (int64_t)U * rows_step) {
             float a[U];
-            int fu[U];
-            bool live[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                live[u] = i < i1;
-                fu[u] = f;
-                a[u] = live[u] ? A[i * lda + j0 + f] : 0.0f;
-                i += step_rows;
-                f += step_f;
-                if (f >= nf) { f -= nf; ++i; }
+                const int64_t r = i + (int64_t)u * rows_step;
+                a[u] = col[(r < i1 ? r : i1 - 1) * lda];
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (!live[u]) continue;
-                const double l = base[fu[u]], w = width[fu[u]];
-                double t = 0.0;
-                if (w > 0.0) {
-                    t = ((double)a[u] - l) / w;
-                    t = t < 0.0 ? 0.0 : t;
-                    t = t > 1.0 ? 1.0 : t;
+                if (i + (int64_t)u * rows_step < i1) {
+                    double t = 0.0;
+                    if (w > 0.0) {
+                        t = ((double)a[u] - l) / w;
+                        t = t < 0.0 ? 0.0 : t;
+                        t = t > 1.0 ? 1.0 : t;
+                    }
+                    int m = (int)(t * (double)M);
+                    if (m > M - 1) m = M - 1;
+                    atomicAdd(cf + m, 1u);
+                    unsafeAtomicAdd(hf + 2 * m, t);
+                    unsafeAtomicAdd(hf + 2 * m + 1, t * t);
                 }
-                int m = (int)(t * (double)M);
-                if (m > M - 1) m = M - 1;
-                double *h = sh + ((size_t)fu[u] * M + m) * 2;
-                atomicAdd(cnt + fu[u] * M + m, 1u);
-                unsafeAtomicAdd(h + 0, t);
-                unsafeAtomicAdd(h + 1, t * t);
             }
         }
     }
@@ -518,7 +517,7 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
         const int Fmax = hist_features(M, lds_limit);
         int F = 1;
         int64_t best = -1;
-        for (int f = 1; f <= Fmax; ++f) {
+        for (int f = 1; f <= Fmax; f *= 2) {      // (F divides 256)
             const int64_t rounds = ((d + f - 1) / f + cus - 1) / cus;
             if (best < 0 || rounds * f <= best) { best = rounds * f; F = f; }
         }
@@ -532,7 +531,7 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
         if (HIP_FAILED(hipFuncSetAttribute((const void *)k_hist, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)hl)))
             return ZIPML_ELAUNCH;
-        hipLaunchKernelGGL(k_hist, dim3((unsigned)fblocks, (unsigned)hs), dim3(256), hl, s, A_dev, n, d, lda,
+        hipLaunchKernelGGL(k_hist, dim3((unsigned)round_up(fblocks, 8), (unsigned)hs), dim3(256), hl, s, A_dev, n, d, lda,
                            hrows, lo_dev, hi_dev, M, F, hs == 1 ? 1 : 0, hist_dev);
         if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     }
