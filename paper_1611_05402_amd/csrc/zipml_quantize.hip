@@ -5,6 +5,7 @@
 // it reads the fp32 tile with coalesced 512-byte row segments, takes the rounding decision for both
 // copies (one Philox block per copy covers 4 neighbouring features), transposes the codes through
 // LDS and writes sample-major units for copy 2 and feature-major units for copy 1.
+#include <type_traits>
 #include "zipml_device.h"
 #include "zipml_host.h"
 
@@ -150,24 +151,25 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
     const int64_t total_groups = (n_rows + 31) / 32;
     const int64_t g_begin = (int64_t)blockIdx.x * groups_per_block;
     const int64_t g_end = g_begin + groups_per_block < total_groups ? g_begin + groups_per_block : total_groups;
-    const bool vec = vec_ok && col + 3 < d;
-
-    auto fetch = [&](int64_t rg_local, float (&v)[2][4]) {
+    // The loop below exists twice: for workgroups all of whose threads fetch four features with one
+    // 16-byte load, and for the others (the last block of features, unaligned rows).  The fetches are
+    // loads that no branch can skip -- rows and features past the end repeat the last ones and are
+    // never used -- because a load behind a branch makes the compiler wait for every load in flight
+    // where the first value is used, the next round's included, and that undoes the prefetch.
+    auto run = [&](auto vec_tag) __attribute__((always_inline)) {
+    constexpr bool VEC = decltype(vec_tag)::value;
+    auto fetch = [&](int64_t rg_local, float (&v)[2][4]) __attribute__((always_inline)) {
+        const int64_t rgc = rg_local < g_end ? rg_local : g_end - 1;
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
-            const int64_t i = rg_local * 32 + pass * 16 + (tid >> 4);
+            const int64_t i = rgc * 32 + pass * 16 + (tid >> 4);
+            const float *src = A + (i < n_rows ? i : n_rows - 1) * lda;
+            if constexpr (VEC) {
+                const float4 q = *reinterpret_cast<const float4 *>(src + col);
+                v[pass][0] = q.x; v[pass][1] = q.y; v[pass][2] = q.z; v[pass][3] = q.w;
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[pass][e] = 0.0f;
-            if (rg_local < g_end && i < n_rows && col < d) {
-                const float *src = A + i * lda + col;
-                if (vec) {
-                    const float4 q = *reinterpret_cast<const float4 *>(src);
-                    v[pass][0] = q.x; v[pass][1] = q.y; v[pass][2] = q.z; v[pass][3] = q.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (col + e < d) v[pass][e] = src[e];
-                }
+                for (int e = 0; e < 4; ++e) v[pass][e] = src[col + e < d ? col + e : d - 1];
             }
         }
     };
@@ -244,6 +246,9 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
 #pragma unroll
             for (int e = 0; e < 4; ++e) vcur[pass][e] = vnxt[pass][e];
     }
+    };
+    if (vec_ok && col0 + kTileCols <= d) run(std::true_type{});
+    else run(std::false_type{});
 }
 
 template <int BITS>
