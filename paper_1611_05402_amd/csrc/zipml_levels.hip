@@ -250,8 +250,14 @@ __global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hi
                 double best = INF;
                 int bj = k - 1;
                 if (m >= k) {
+                    // (this end point's own terms stay in registers; four j at a time, so that the
+                    // LDS reads of one are in flight while the arithmetic of another runs)
+                    const double dm = edge[m], s2m = S2[m], s1m = S1[m], cm = C[m];
+#pragma unroll 4
                     for (int jj = k - 1; jj <= m - 1; ++jj) {
-                        const double v = prev[jj] + V(jj, m);
+                        const double dj = edge[jj];
+                        const double vjm = -(s2m - S2[jj]) + (dj + dm) * (s1m - S1[jj]) - dj * dm * (cm - C[jj]);
+                        const double v = prev[jj] + vjm;
                         if (v < best) { best = v; bj = jj; }
                     }
                     arg[(size_t)k * W + m] = (uint16_t)bj;
