@@ -155,10 +155,10 @@ def test_hist_moments_and_levels_optimal_end_to_end():
 def test_greedy_intervals_worked_by_hand():
     """M = 8 bins, k = 1 (2 pairs stay split, at most 5 intervals).  Errors of the merged pairs, by
     the definition err = sum (b - t)(t - a):
-      round 1: [0,.25): .2*.05 + .15*.1 = .025   [.25,.5): .2*.05 = .010
+      pass 1:  [0,.25): .2*.05 + .15*.1 = .025   [.25,.5): .2*.05 = .010
                [.5,.75): .2*.05 + .15*.1 + .05*.2 = .035   [.75,1]: .05*.2 = .010
                -> first and third stay split: edges 0 1 2 4 5 6 8 (6 intervals)
-      round 2: [0,.25): .025   [.25,.625): .325*.05 + .075*.3 + .025*.35 = .0475
+      pass 2:  [0,.25): .025   [.25,.625): .325*.05 + .075*.3 + .025*.35 = .0475
                [.625,1]: .3*.075 + .05*.325 = .03875
                -> second and third stay split: edges 0 2 4 5 6 8 (5 intervals, done)."""
     t = np.array([0.05, 0.10, 0.30, 0.55, 0.60, 0.70, 0.95])
@@ -173,11 +173,11 @@ def test_greedy_intervals_worked_by_hand():
 def test_greedy_intervals_ties_go_left():
     """One point in the middle of each of 16 bins, k = 1: every number is a short dyadic fraction, so
     equal errors are equal to the last bit and the rule for ties decides.
-      round 1: 8 equal pairs, the two on the left stay split: 0 1 2 3 4 6 8 10 12 14 16
-      round 2: pairs [0,2) [2,4) (2 points) [4,8) [8,12) [12,16) (4 points, larger): the first two
+      pass 1:  8 equal pairs, the two on the left stay split: 0 1 2 3 4 6 8 10 12 14 16
+      pass 2:  pairs [0,2) [2,4) (2 points) [4,8) [8,12) [12,16) (4 points, larger): the first two
                of the three large ones stay split: 0 2 4 6 8 10 12 16
-      round 3: [0,4) [4,8) [8,12) equal (the odd interval [12,16) is left alone): 0 2 4 6 8 12 16
-      round 4: [0,4) [4,8) (4 points) [8,16) (8 points): 0 2 4 8 12 16."""
+      pass 3:  [0,4) [4,8) [8,12) equal (the odd interval [12,16) is left alone): 0 2 4 6 8 12 16
+      pass 4:  [0,4) [4,8) (4 points) [8,16) (8 points): 0 2 4 8 12 16."""
     M = 16
     t = (np.arange(M) + 0.5) / M
     edge, out = oracle.greedy_intervals(oracle.bin_moments(t, np.arange(M + 1) / M), 1)
