@@ -527,6 +527,10 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
             const int64_t rounds = ((d + f - 1) / f + cus - 1) / cus;
             if (best < 0 || rounds * f <= best) { best = rounds * f; F = f; }
         }
+        if (const char *env = getenv("ZIPML_HIST_FEATURES")) {   // tuning override: a power of two that fits
+            const int v = atoi(env);
+            if (v >= 1 && v <= Fmax && (v & (v - 1)) == 0) F = v;
+        }
         const size_t hl = hist_lds_bytes(M, F);
         if (hl > (size_t)lds_limit) return ZIPML_EUNSUPPORTED;
         const int64_t fblocks = (d + F - 1) / F;
