@@ -123,3 +123,14 @@ def test_argument_errors_are_codes_not_crashes(lib):
     assert lib.zipml_loss(null, null, 0, null, 2, null, 0, fake, fake, 64, 8, C.byref(out), fake, 1 << 20) == zipml.EINVAL
     assert lib.zipml_loss(null, fake, 8, null, 2, null, 0, fake, fake, 64, 8, C.byref(out), fake, 8) == zipml.EWORKSPACE
     assert lib.zipml_sgd_status(null, null, 0) == zipml.EWORKSPACE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; bench.py says so instead of starting ranks."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
