@@ -17,7 +17,9 @@ _SRC = os.path.join(_HERE, "zipml_oracle.c")
 _SO = os.path.join(_HERE, "libzipml_oracle.so")
 
 # -ffp-contract=off: the oracle's fp32 decision sequences must stay single IEEE ops.
-_CFLAGS = ["-O1", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-std=c11"]
+# -fopenmp: only zo_sgd_epoch_threads (the all-cores leg of the benchmark's baseline) has a
+# parallel region; every other function runs on the calling thread.
+_CFLAGS = ["-O1", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-std=c11", "-fopenmp"]
 
 
 def build(force: bool = False) -> str:
@@ -232,6 +234,21 @@ def sgd_epoch(codes1, codes2, levels, b, bits, x, batch, lr, symmetric=False, l2
                        C.c_int(int(symmetric)), C.c_float(l2), C.c_int(prox_kind),
                        C.c_float(prox_coef))
     return x
+
+
+def sgd_epoch_threads(codes1, codes2, levels, b, bits, x, batch, lr, threads):
+    """The plain epoch of sgd_epoch with the rows of a minibatch shared out over host threads
+    (partial gradients added in thread order); returns (new fp32 model, threads used)."""
+    codes1 = np.ascontiguousarray(codes1, np.uint8)
+    codes2 = np.ascontiguousarray(codes2, np.uint8)
+    levels, b = _f32(levels), _f32(b)
+    x = _f32(x).copy()
+    n, d = codes1.shape
+    f = lib().zo_sgd_epoch_threads
+    f.restype = C.c_int
+    used = f(_p(codes1), _p(codes2), _p(levels), _p(b), C.c_int64(n), C.c_int64(d), C.c_int(bits),
+             _p(x), C.c_int64(batch), C.c_float(lr), C.c_int(threads))
+    return x, int(used)
 
 
 def sgd_epoch_e2e(codes1, codes2, levels, grid_idx, grid_lo, grid_step, b, bits, x, batch, lr,

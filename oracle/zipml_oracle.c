@@ -29,13 +29,19 @@
  * brute-force minimisation of its definition and the lasso / ridge / box
  * closed forms of an orthogonal design; the greedy intervals == a partition
  * worked out by hand, within twice the optimum of the dynamic program, and
- * == the optimum on clustered data.
+ * == the optimum on clustered data; one end-to-end step at minibatches of 96
+ * to 200 samples == an independent fp64 step (integer dots, residual bits,
+ * the mean gradient to one unit in the last place, Q4 and the update from
+ * that gradient); the all-cores epoch == the plain epoch.
  * No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 /* ------------------------------------------------------------------------- */
 /* Counter-based random numbers: Philox4x32-10 (Salmon, Moraes, Dror, Shaw,  */
@@ -550,6 +556,52 @@ void zo_sgd_epoch(const uint8_t *codes1, const uint8_t *codes2, const float *lev
     free(r2); free(r1); free(g);
 }
 
+/* The same epoch (eq. (5), plain estimator, no regulariser) with the rows of each minibatch
+ * shared out over `threads` host threads: thread k takes the k-th contiguous share of the rows,
+ * forms their residuals and its own partial sum of the gradient in fp64; the partial sums are
+ * added in thread order.  With one thread it is zo_sgd_epoch operation for operation; with more
+ * only the association of the fp64 sum over the batch changes.  Returns the number of threads the
+ * parallel regions ran with. */
+int zo_sgd_epoch_threads(const uint8_t *codes1, const uint8_t *codes2, const float *levels,
+                         const float *b, int64_t n, int64_t d, int bits, float *x, int64_t batch,
+                         float lr, int threads)
+{
+    int K = 1 << bits;
+    if (threads < 1) threads = 1;
+    double *gp = malloc(sizeof(double) * (size_t)d * (size_t)threads);
+    int used = 1;
+    for (int64_t t = 0; t < n / batch; ++t) {
+        const uint8_t *c1 = codes1 + t * batch * d, *c2 = codes2 + t * batch * d;
+        const float *bb = b + t * batch;
+#pragma omp parallel num_threads(threads)
+        {
+            int k = 0, nt = 1;
+#ifdef _OPENMP
+            k = omp_get_thread_num();
+            nt = omp_get_num_threads();
+#endif
+            if (k == 0) used = nt;
+            int64_t i0 = batch * k / nt, i1 = batch * (k + 1) / nt;
+            double *g = gp + (size_t)k * (size_t)d;
+            for (int64_t j = 0; j < d; ++j) g[j] = 0.0;
+            for (int64_t i = i0; i < i1; ++i) {
+                double z = 0.0;
+                for (int64_t j = 0; j < d; ++j)
+                    z += (double)levels[j * K + c2[i * d + j]] * (double)x[j];
+                double r = z - (double)bb[i];
+                for (int64_t j = 0; j < d; ++j) g[j] += (double)levels[j * K + c1[i * d + j]] * r;
+            }
+        }
+        for (int64_t j = 0; j < d; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < used; ++k) acc += gp[(size_t)k * (size_t)d + j];
+            x[j] = (float)((double)x[j] - (double)lr * (acc / (double)batch));
+        }
+    }
+    free(gp);
+    return used;
+}
+
 /* ------------------------------------------------------------------------- */
 /* End-to-end low precision (Supp. C-E):                                     */
 /*   g = Q4( Q1(a) ( Q2(a)^T Q3(x) - b ) ),  x <- x - lr g  in full          */
@@ -562,9 +614,11 @@ void zo_sgd_epoch(const uint8_t *codes1, const uint8_t *codes2, const float *lev
 /*     so the dot is an exact integer sum  acc_i = sum_j G[j][c2_ij] * m_j;  */
 /*   - z_i = fp32( sigma * (lo * sum_j m_j + step * acc_i) ) in fp64;        */
 /*   - r_i = z_i - b_i in fp32;                                              */
-/*   - g_j: per block of 32 consecutive samples one chain of fp32 fused     */
-/*     multiply-adds in sample order, block sums added in block order, then  */
-/*     one fp32 division by the batch size;                                  */
+/*   - g_j = (1/B) sum_i L[j][c1_ij] r_i, the mean of eq. (5), rounded to   */
+/*     fp32 once: every product of two fp32 numbers is exact in fp64, the    */
+/*     sum runs in fp64 in sample order and is divided by the batch size in  */
+/*     fp64 (the paper fixes no order; fp64 makes the order immaterial to    */
+/*     the fp32 result except in a 2^-29 fraction of the cases);             */
 /*   - Q4 and the update in fp32, multiply then subtract.                    */
 /* Optional debug outputs (any may be NULL) capture the LAST step:           */
 /*   dbg_m[d] model codes, dbg_acc[batch] integer dots, dbg_r[batch],        */
@@ -604,18 +658,13 @@ int zo_sgd_epoch_e2e(const uint8_t *codes1, const uint8_t *codes2, const float *
                        ((double)grid_lo * (double)summ + (double)grid_step * (double)a);
             r[i] = (float)z - bb[i];
         }
-        /* gradient pass on copy 1: blocks of 32 consecutive samples of the batch; inside a
-         * block one fp32 fused-multiply-add chain in sample order starting from zero; the block
-         * sums are added in block order; one fp32 division by the batch size */
+        /* gradient pass on copy 1: the mean over the batch of Q1(a_i) r_i, summed in fp64 in
+         * sample order (each product is exact) and rounded to fp32 once */
         for (int64_t j = 0; j < d; ++j) {
-            float sum = 0.0f;
-            for (int64_t blk = 0; blk < batch; blk += 32) {
-                float a = 0.0f;
-                for (int64_t i = blk; i < blk + 32 && i < batch; ++i)
-                    a = fmaf(levels[j * K + c1[i * d + j]], r[i], a);
-                sum = sum + a;
-            }
-            g[j] = sum / (float)batch;
+            double sum = 0.0;
+            for (int64_t i = 0; i < batch; ++i)
+                sum += (double)levels[j * K + c1[i * d + j]] * (double)r[i];
+            g[j] = (float)(sum / (double)batch);
         }
         /* Q4: quantise the gradient (Supp. D), then full-precision update */
         if (grad_bits > 0) {

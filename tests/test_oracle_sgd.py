@@ -348,6 +348,82 @@ def test_e2e_integer_dot_equals_float_dot_of_decoded_values():
     assert np.array_equal(gq, dbg["gq"])
 
 
+def _ulp_diff(a, b):
+    """Distance in units of the last place between two fp32 arrays of the same sign pattern."""
+    ai = np.asarray(a, np.float32).view(np.int32).astype(np.int64)
+    bi = np.asarray(b, np.float32).view(np.int32).astype(np.int64)
+    ai = np.where(ai < 0, -(ai & 0x7FFFFFFF), ai)
+    bi = np.where(bi < 0, -(bi & 0x7FFFFFFF), bi)
+    return np.abs(ai - bi)
+
+
+@pytest.mark.parametrize("batch,gb", [(96, 8), (200, 8), (160, 0), (96, 3)])
+def test_e2e_step_with_many_samples_equals_independent_fp64_step(batch, gb):
+    """One end-to-end step (Supp. E) at minibatch sizes that are several times, and not a
+    multiple of, any power-of-two block: the gradient before Q4 is the exact mean of eq. (5)
+    rounded to fp32 (NumPy fp64 matrix product of the decoded copies), and the returned model is
+    x - lr * sigma_g * codes (resp. x - lr * g) in fp32.  A dropped, repeated or misordered run of
+    samples anywhere in the batch changes g by far more than the one unit in the last place
+    allowed here."""
+    rng = np.random.default_rng(100 + batch)
+    n, d, bits, lr = 2 * batch, 37, 4, np.float32(0.07)
+    lo, hi = 0.0, 1.0
+    L = oracle.levels_uniform([lo] * d, [hi] * d, bits)
+    G, glo, gstep = _uniform_grid(d, bits, lo, hi)
+    c1 = rng.integers(0, 16, (n, d)).astype(np.uint8)
+    c2 = rng.integers(0, 16, (n, d)).astype(np.uint8)
+    b = rng.standard_normal(n).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    step = 1                                            # the second minibatch: rows batch .. 2 batch
+    got, dbg = oracle.sgd_epoch_e2e(c1, c2, L, G, glo, gstep, b, bits, x0, batch, lr, gb, 8, 5, 1,
+                                    first_step=step, num_steps=1, debug=True)
+    rows = slice(step * batch, (step + 1) * batch)
+    m, sigma = oracle.quantize_vec(x0, 8, 5, 1, step, 3)
+    assert np.array_equal(m, dbg["m"])
+    # integer dots and residuals from the definition, in NumPy
+    acc = G[np.arange(d)[None, :], c2[rows]].astype(np.int64) @ m.astype(np.int64)
+    assert np.array_equal(acc, dbg["acc"])
+    z = np.float64(sigma) * (np.float64(glo) * m.sum() + np.float64(gstep) * acc)
+    r = z.astype(np.float32) - b[rows]
+    assert np.array_equal(r.view(np.uint32), dbg["r"].view(np.uint32))
+    # the mean gradient over ALL samples of the minibatch
+    A1 = np.take_along_axis(L.T, c1[rows].astype(np.int64), axis=0).astype(np.float64)
+    g = (A1.T @ r.astype(np.float64) / batch).astype(np.float32)
+    assert _ulp_diff(dbg["g"], g).max() <= 1
+    # leaving out any 32 consecutive samples is visible at that tolerance
+    keep = np.ones(batch, bool)
+    keep[32:64] = False
+    g_drop = (A1[keep].T @ r[keep].astype(np.float64) / batch).astype(np.float32)
+    assert _ulp_diff(dbg["g"], g_drop).max() > 1000
+    # Q4 and the update, from the oracle's own g
+    if gb:
+        gq, sg = oracle.quantize_vec(dbg["g"], gb, 5, 1, step, 4)
+        assert np.array_equal(gq, dbg["gq"])
+        x_ref = x0 - lr * (np.float32(sg) * gq.astype(np.float32))
+    else:
+        x_ref = x0 - lr * dbg["g"]
+    assert np.array_equal(got.view(np.uint32), x_ref.astype(np.float32).view(np.uint32))
+
+
+def test_threaded_epoch_is_the_plain_epoch():
+    """The all-cores form of the epoch (rows of a minibatch over threads, partial gradients added
+    in thread order): one thread is the plain epoch bit for bit, several threads only
+    re-associate an fp64 sum."""
+    w = synth.tiny(n=1024, d=48, batch=64)
+    A, b = w.full()
+    L = oracle.levels_uniform([-1] * w.d, [1] * w.d, 4)
+    c1, c2 = oracle.quantize(A, L, 4, 3, 0)
+    x0 = np.zeros(w.d, np.float32)
+    ref = oracle.sgd_epoch(c1, c2, L, b, 4, x0, 64, 0.05)
+    one, used = oracle.sgd_epoch_threads(c1, c2, L, b, 4, x0, 64, 0.05, 1)
+    assert used == 1 and np.array_equal(one.view(np.uint32), ref.view(np.uint32))
+    for threads in (2, 3, 8):
+        many, used = oracle.sgd_epoch_threads(c1, c2, L, b, 4, x0, 64, 0.05, threads)
+        assert 1 <= used <= threads
+        assert np.linalg.norm(many.astype(np.float64) - ref) <= 1e-6 * np.linalg.norm(ref)
+        assert _ulp_diff(many, ref).max() <= 2
+
+
 def test_e2e_step_ranges_compose():
     w = synth.tiny(n=256, d=16, batch=16)
     A, b = w.full()
