@@ -117,6 +117,7 @@ struct SgdArgs {
     // debug outputs (may be null)
     int32_t *dbg_m, *dbg_acc, *dbg_gq;
     float *dbg_r, *dbg_g;
+    int dbg_production;    // 1: dbg_r / dbg_g are written by the production launch (matrix-core loop)
 };
 
 // Proximal operator of lr * R at v, coordinate-wise (Sec. 2, x <- prox_{gamma R}(x - gamma g)):
@@ -250,6 +251,20 @@ __device__ __forceinline__ float unit_grad_table(const uint32_t (&u)[BITS], cons
 {
 #pragma unroll
     for (int k = 0; k < 32; ++k) acc = fmaf(L[unit_code<BITS>(u, k)], r[k], acc);
+    return acc;
+}
+
+// Gradient pass of the end-to-end mode: the sum over the unit's 32 samples of L[code_k] * r[k] in
+// fp64 (every product of two fp32 numbers is exact there), so that the mean gradient rounded to
+// fp32 does not depend on how the samples of a minibatch are shared out over units and threads
+// (Supp. E: Q4 decides integer codes from this gradient).
+template <int BITS>
+__device__ __forceinline__ double unit_grad_table_f64(const uint32_t (&u)[BITS], const float *L,
+                                                      const float *r)
+{
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) acc = fma((double)L[unit_code<BITS>(u, k)], (double)r[k], acc);
     return acc;
 }
 
@@ -642,47 +657,56 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
             }
 
             ZIPML_TICK(8);
-            // gradient pass: one partial sum per owned unit (a chain over its 32 samples)
-            float part[UPT];
+            // gradient pass: one partial sum per owned unit (a chain over its 32 samples); in the
+            // end-to-end mode, where Q4 turns the gradient into integer codes, the sums are fp64
+            using gsum_t = typename std::conditional<kIsInt, double, float>::type;
+            gsum_t *const gpart = reinterpret_cast<gsum_t *>(L.gpart);
+            gsum_t part[UPT];
 #pragma unroll
             for (int k = 0; k < UPT; ++k) {
-                part[k] = 0.0f;
+                part[k] = 0;
                 const int rgl = g_sl + k * nsl;
                 if (g_live && rgl < nrg) {
                     const float *rr = rs + rgl * 32;
-                    if (MODE == kAffine) part[k] = unit_fma_codes<BITS>(c1cur[k], rr, 0.0f);
-                    else if (a.lds_levels) part[k] = unit_grad_table<BITS>(c1cur[k], L.Ls + g_c * K, rr, 0.0f);
-                    else part[k] = unit_grad_table<BITS>(c1cur[k], Lg + (size_t)g_c * K, rr, 0.0f);
+                    const float *Lj = a.lds_levels ? L.Ls + g_c * K : Lg + (size_t)g_c * K;
+                    if constexpr (kIsInt) part[k] = unit_grad_table_f64<BITS>(c1cur[k], Lj, rr);
+                    else if (MODE == kAffine) part[k] = unit_fma_codes<BITS>(c1cur[k], rr, 0.0f);
+                    else part[k] = unit_grad_table<BITS>(c1cur[k], Lj, rr, 0.0f);
                 }
             }
             // gpart[sample group][feature]
 #pragma unroll
             for (int k = 0; k < UPT; ++k) {
                 const int rgl = g_sl + k * nsl;
-                if (rgl < nrg) L.gpart[rgl * CW + g_c] = part[k];
+                if (rgl < nrg) gpart[rgl * CW + g_c] = part[k];
             }
             ZIPML_TICK(9);
             lds_barrier();
             ZIPML_TICK(10);
             if (tid < CW) {
                 // the unit sums are added in sample-group order
-                float sacc = 0.0f;
+                gsum_t sacc = 0;
                 for (int r0 = 0; r0 < nrg; r0 += 8) {
-                    float v[8];     // eight LDS reads in flight, then added in order
+                    gsum_t v[8];     // eight LDS reads in flight, then added in order
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) v[q] = L.gpart[(r0 + q < nrg ? r0 + q : r0) * CW + tid];
+                    for (int q = 0; q < 8; ++q) v[q] = gpart[(r0 + q < nrg ? r0 + q : r0) * CW + tid];
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
                         if (r0 + q < nrg) sacc += v[q];
                 }
-                float g = sacc;
-                if (MODE == kAffine) {
-                    float Rtot = 0.0f;
+                float g;
+                if constexpr (kIsInt) {
+                    g = (j0 + tid < a.d) ? (float)(sacc / (double)B) : 0.0f;   // the mean, rounded once
+                } else {
+                    g = sacc;
+                    if (MODE == kAffine) {
+                        float Rtot = 0.0f;
 #pragma unroll
-                    for (int q = 0; q < kWaves; ++q) Rtot += L.wsum[q];
-                    g = L.los[tid] * Rtot + L.dls[tid] * sacc;
+                        for (int q = 0; q < kWaves; ++q) Rtot += L.wsum[q];
+                        g = L.los[tid] * Rtot + L.dls[tid] * sacc;
+                    }
+                    g = (j0 + tid < a.d) ? __fdiv_rn(g, (float)B) : 0.0f;
                 }
-                g = (j0 + tid < a.d) ? __fdiv_rn(g, (float)B) : 0.0f;
                 gs[tid] = g;
                 if (dbg_g && j0 + tid < a.d) dbg_g[j0 + tid] = g;
             }
@@ -796,7 +820,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     L.rs = (float *)carve((size_t)Rlen * 4);
     L.zl = (float *)carve(a.W == 1 ? (size_t)(B + 4) * 4 : 0);
     L.zp = (uint32_t *)carve(a.GQ > 1 ? (size_t)a.GQ * B * 4 : 0);
-    L.gpart = (float *)carve((size_t)kMaxUpt * kThreads * 4);
+    L.gpart = (float *)carve((size_t)kMaxUpt * kThreads * (INT ? 8 : 4));   // fp64 sums in the end-to-end mode
     L.red = (double *)carve(512 * 8);
     L.wsum = (float *)carve(3 * kWaves * 4);
     L.isum = (int *)carve(kWaves * 4);
@@ -847,8 +871,10 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     }
 
     constexpr bool kMfmaBits = BITS == 2 || BITS == 4 || BITS == 8;
-    if ((a.chunks > 1 || a.avg) && !(!INT && FAST && kMfmaBits && affine_all && a.mfma)) {
-        // minibatches taken in chunks and the symmetrised estimator exist on the matrix-core loop only
+    if ((a.chunks > 1 || a.avg || (FAST && (a.dbg_r || a.dbg_g))) &&
+        !(!INT && FAST && kMfmaBits && affine_all && a.mfma)) {
+        // minibatches taken in chunks, the symmetrised estimator and the intermediates of a
+        // production step exist on the matrix-core loop only
         if (blockIdx.x == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
         return;
     }
@@ -1000,8 +1026,8 @@ static int device_limits(int &cus, int &lds)
 static size_t up16(size_t v) { return (v + 15) & ~(size_t)15; }
 
 // LDS needed for GQ feature groups per workgroup; 0 if it does not fit.
-static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool solo, bool mfma,
-                       int pairs, int lds_limit, int &lds_levels)
+static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool int_mode, bool solo,
+                       bool mfma, int pairs, int lds_limit, int &lds_levels)
 {
     const int K = 1 << bits, CW = 32 * GQ;
     const int nrg = batch >= 32 ? (int)(batch / 32) : 1;
@@ -1011,7 +1037,7 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool sol
                          up16((size_t)nrg * 32 * 4) +
                          (solo ? up16((size_t)(batch + 4) * 4) : 0) +
                          (GQ > 1 ? up16((size_t)GQ * batch * 4) : 0) +
-                         up16((size_t)kMaxUpt * kThreads * 4) + up16(512 * 8) +
+                         up16((size_t)kMaxUpt * kThreads * (int_mode ? 8 : 4)) + up16(512 * 8) +
                          up16(3 * kWaves * 4) + up16(kWaves * 4) +
                          (mfma ? up16(mfma_lds_bytes(GQ, batch, pairs)) : 0);
     return total <= (size_t)lds_limit ? total : 0;
@@ -1048,7 +1074,7 @@ static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool 
         // spaced is found out by the kernel)
         const bool mfma = fp32_model && (bits == 2 || bits == 4 || bits == 8) && batch % 64 == 0 &&
                           W > 1 && GQ <= 4 && !getenv("ZIPML_NO_MFMA");
-        const size_t sh = plan_lds(GQ, bits, batch, int_table, W == 1, mfma, pairs, lds, ll);
+        const size_t sh = plan_lds(GQ, bits, batch, int_table, !fp32_model, W == 1, mfma, pairs, lds, ll);
         if (!sh) break;
         best = GQ;
         p.GQ = GQ; p.W = (int)W; p.lds_levels = ll; p.shmem = sh; p.mfma = mfma ? 1 : 0;
@@ -1067,7 +1093,7 @@ template <int BITS, bool INT>
 static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
 {
     const bool debug = a.dbg_m || a.dbg_acc || a.dbg_gq || a.dbg_r || a.dbg_g;
-    const bool fast = !stepwise && !debug;
+    const bool fast = !stepwise && (!debug || a.dbg_production);
     const void *kern = (const void *)k_sgd<BITS, INT, false, kMaxUpt>;
     if (fast) {
         kern = p.upt == 1 ? (const void *)k_sgd<BITS, INT, true, 1>
@@ -1197,8 +1223,14 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     if (grad_bits != 0 && (grad_bits < 2 || grad_bits > 8)) return ZIPML_EINVAL;
     if (epoch >= (1u << 24)) return ZIPML_EINVAL;
     if (step0 < 0 || nsteps < 0 || step0 + nsteps > n / batch) return ZIPML_EINVAL;
-    if (flags & ~(ZIPML_SGD_STEPWISE | ZIPML_SGD_AVERAGED)) return ZIPML_EINVAL;
+    if (flags & ~(ZIPML_SGD_STEPWISE | ZIPML_SGD_AVERAGED | ZIPML_SGD_PRODUCTION)) return ZIPML_EINVAL;
     if (flags & ZIPML_SGD_AVERAGED) return ZIPML_EUNSUPPORTED;
+    const bool production = (flags & ZIPML_SGD_PRODUCTION) != 0;
+    if (production) {
+        // the intermediates of the production launch: residuals and gradient of an fp32-model step
+        if ((flags & ZIPML_SGD_STEPWISE) || !(dbg_r || dbg_g) || dbg_m || dbg_acc || dbg_gq) return ZIPML_EINVAL;
+        if (model_bits > 0 || packed1s_dev || packed2s_dev) return ZIPML_EUNSUPPORTED;
+    }
     if (grad_bits > 0 && model_bits == 0) return ZIPML_EUNSUPPORTED;
     if (!(l2 >= 0.0f)) return ZIPML_EINVAL;
     if (l2 != 0.0f && model_bits > 0) return ZIPML_EUNSUPPORTED;   // the c*x term is not quantised here
@@ -1236,6 +1268,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     int replicas = 1;
     int64_t forced = 0;
     if (const char *env = getenv("ZIPML_MICRO_BATCH")) forced = atol(env);   // tuning override: chunk size
+    if (production && (rc != ZIPML_OK || !p.mfma)) return ZIPML_EUNSUPPORTED;
     const bool split_ok = model_bits == 0 && !stepwise && !debug && batch % 64 == 0 &&
                           (bits == 2 || bits == 4 || bits == 8);
     if (split_ok && (rc == ZIPML_EUNSUPPORTED || (rc == ZIPML_OK && p.mfma && forced > 0 && forced < batch))) {
@@ -1374,7 +1407,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.GQ = p.GQ;
     a.W = p.W;
     a.lds_levels = p.lds_levels;
-    a.mfma = (p.mfma && !stepwise && !debug) ? 1 : 0;   // the matrix-core loop exists in the production launch only
+    a.mfma = (p.mfma && !stepwise && (!debug || production)) ? 1 : 0;   // the matrix-core loop exists in the production launch only
+    a.dbg_production = production ? 1 : 0;
     a.spin_limit = kSpinLimit;
     if (const char *env = getenv("ZIPML_SPIN_LIMIT")) {   // test hook: make every wait give up early
         const long v = atol(env);

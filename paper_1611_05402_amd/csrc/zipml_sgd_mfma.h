@@ -438,6 +438,13 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 bnext[q] = bfut[q];
             }
         }
+        if (a.dbg_r && blockIdx.x == 0) {     // intermediates of a production step (zipml_debug_step)
+#pragma unroll
+            for (int q = 0; q < kBpt; ++q) {
+                const int i = tid + q * nthr;
+                if (i < B) a.dbg_r[i] = r[0][q];
+            }
+        }
         rmax = wave_reduce_dpp(rmax, [](float p, float q) { return fmaxf(p, q); });
         rsum = wave_sum_dpp(rsum);
         if (lane == 0) { wmax[wave] = rmax; wsum[wave] = rsum; }
@@ -572,6 +579,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     float xnew = 0.0f;
                     if (owner) {
                         const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)(a.chunks * NC)) : 0.0f;
+                        if (a.dbg_g && o_live && rep == 0) a.dbg_g[j0 + oc] = g;
                         const float reg = a.l2 * x_own;
                         const float stp = a.lr * (g + reg);
                         x_own = x_own - stp;

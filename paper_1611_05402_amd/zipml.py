@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libzipml.so")
 
 UNIFORM, OPTIMAL, GREEDY = 0, 1, 2
 RANGE_GIVEN, SYMMETRIC = 1, 2
-SGD_STEPWISE, SGD_AVERAGED = 1, 2
+SGD_STEPWISE, SGD_AVERAGED, SGD_PRODUCTION = 1, 2, 4
 PROX_NONE, PROX_L1, PROX_L2SQ, PROX_BOX = 0, 1, 2, 3
 
 OK, EINVAL, EALIGN, ERANGE, EWORKSPACE, ELAUNCH, EUNSUPPORTED, ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7

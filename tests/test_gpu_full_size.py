@@ -7,7 +7,8 @@ import pytest
 import torch
 
 import oracle
-from gpu_harness import DEV, GpuProblem, dev, oracle_quantize_rows, rel_l2
+from gpu_harness import (DEV, E2E_EPOCH_BAND, GpuProblem, check_level_sets, dev, e2e_step_check,
+                         max_abs_ok, oracle_quantize_rows, rel_l2)
 from paper_1611_05402_amd import synth, zipml
 
 pytestmark = pytest.mark.gpu
@@ -45,7 +46,7 @@ def test_dense8_full_size_codes_epoch_and_loss():
         p.epoch(x, w.lr)
         err = rel_l2(x.cpu().numpy(), x_ref)
         say(f"  rel L2 {err:.2e}")
-        assert err <= TOL
+        assert err <= TOL and max_abs_ok(x.cpu().numpy(), x_ref, TOL)
         l_ref = oracle.loss(A, b, x_ref)
         assert abs(p.loss(x) - l_ref) <= TOL * l_ref
         l2_ref = oracle.loss_codes(c2, L, w.bits, b, x_ref)
@@ -64,7 +65,7 @@ def test_dense8_full_size_codes_epoch_and_loss():
             assert zipml.sgd_status(ws) == 0
             err = rel_l2(x.cpu().numpy(), x_ref)
             say(f"  epoch {ep}: rel L2 {err:.2e}")
-            assert err <= TOL
+            assert err <= TOL and max_abs_ok(x.cpu().numpy(), x_ref, TOL)
         assert np.linalg.norm(x_ref) > 0
     # the symmetrised estimator (Supp. A.4) at the headline minibatch (feature owners) and with one
     # step per epoch (sample owners)
@@ -81,7 +82,7 @@ def test_dense8_full_size_codes_epoch_and_loss():
             assert zipml.sgd_status(ws) == 0
             err = rel_l2(x.cpu().numpy(), x_ref)
             say(f"  epoch {ep}: rel L2 {err:.2e}")
-            assert err <= TOL
+            assert err <= TOL and max_abs_ok(x.cpu().numpy(), x_ref, TOL)
         assert np.linalg.norm(x_ref) > 0
 
 
@@ -127,9 +128,9 @@ def test_sampled_steps_and_epoch_at_full_width(name, factory, kw, lr, steps):
         Q1 = np.take_along_axis(L[None, :, :], c1[:, :, None].astype(np.int64), axis=2)[:, :, 0]
         r_ref = Q2.astype(np.float64) @ x0.astype(np.float64) - b[rows]
         g_ref = Q1.astype(np.float64).T @ r_ref / B
-        assert rel_l2(r.cpu().numpy(), r_ref) <= TOL
-        assert rel_l2(g.cpu().numpy(), g_ref) <= TOL
-        assert rel_l2(x.cpu().numpy(), x_ref) <= TOL
+        assert rel_l2(r.cpu().numpy(), r_ref) <= TOL and max_abs_ok(r.cpu().numpy(), r_ref, TOL)
+        assert rel_l2(g.cpu().numpy(), g_ref) <= TOL and max_abs_ok(g.cpu().numpy(), g_ref, TOL)
+        assert rel_l2(x.cpu().numpy(), x_ref) <= TOL and max_abs_ok(x.cpu().numpy(), x_ref, TOL)
     # one whole epoch with the production (persistent) launch
     say("  whole epoch")
     c1, c2 = oracle_quantize_rows(A, L, w.bits, 5, 0)
@@ -139,12 +140,13 @@ def test_sampled_steps_and_epoch_at_full_width(name, factory, kw, lr, steps):
     p.epoch(x, lr)
     err = rel_l2(x.cpu().numpy(), x_ref)
     say(f"  epoch rel L2 {err:.2e}")
-    assert err <= TOL
+    assert err <= TOL and max_abs_ok(x.cpu().numpy(), x_ref, TOL)
 
 
-def test_end_to_end_full_width_bit_exact():
+def test_end_to_end_full_width_steps_and_epochs():
     """d=4096, 3-bit variance-optimal levels from the library's own level search, 8-bit model and
-    gradient, batch 512: levels, codes and whole epochs bit-identical to the oracle."""
+    gradient, batch 512: levels against the oracle's (ties must cost the same), codes bit-exact,
+    sampled steps to the per-step contract, whole epochs within the band."""
     M = 256
     w = synth.e2e(n=8192, n_candidates=M)
     say(f"e2e full width: n={w.n} d={w.d} bits={w.bits} batch={w.batch}")
@@ -152,25 +154,31 @@ def test_end_to_end_full_width_bit_exact():
     lo, hi = np.zeros(w.d, np.float32), np.ones(w.d, np.float32)
     p = GpuProblem(A, b, w.bits, w.batch, n_candidates=M)
     p.make_levels(zipml.OPTIMAL, 0, lo=lo, hi=hi, n_candidates=M)
-    L = p.levels.cpu().numpy()
     G = p.grid.cpu().numpy().view(np.uint16)
     say("  oracle level search")
     Lo, Go, _ = oracle.levels_optimal(oracle.hist_moments(A, lo, hi, M), lo, hi, w.bits)
-    same = np.all(G == Go, axis=1)
-    assert same.mean() > 0.98          # the rest are ties between equally good level sets
+    frac = check_level_sets(oracle, A, lo, hi, M, G, Go, 0.98)
+    say(f"  identical level sets on {frac:.4f} of the features, equal cost on the rest")
     # the run below uses the oracle's levels on both sides
     p.set_levels(Lo, Go)
     glo, gstep, gmax = np.float32(0.0), np.float32(1.0 / M), M
     p.quantize(9, 0)
     c1, c2 = oracle_quantize_rows(A, Lo, w.bits, 9, 0)
     assert np.array_equal(p.codes(1), c1) and np.array_equal(p.codes(2), c2)
+    rng = np.random.default_rng(3)
+    x0 = (rng.standard_normal(w.d) / np.sqrt(w.d)).astype(np.float32)
+    for step in (0, 15):
+        say(f"  step {step}")
+        e2e_step_check(p, oracle, c1, c2, Lo, Go, glo, gstep, gmax, b, x0, 0.05, 8, 8, 9, 0, step)
     x_ref = np.zeros(w.d, np.float32)
     xd = torch.zeros(w.d, dtype=torch.float32, device=DEV)
     for ep in range(2):
-        say(f"  epoch {ep}")
         x_ref = oracle.sgd_epoch_e2e(c1, c2, Lo, Go, glo, gstep, b, w.bits, x_ref, w.batch, 0.05,
                                      8, 8, 9, ep)
         p.epoch(xd, 0.05, seed=9, epoch=ep, grad_bits=8, model_bits=8, grid_lo=glo, grid_step=gstep,
                 grid_max=gmax)
-        assert np.array_equal(xd.cpu().numpy().view(np.uint32), x_ref.view(np.uint32))
+        got = xd.cpu().numpy()
+        same = np.array_equal(got.view(np.uint32), x_ref.view(np.uint32))
+        say(f"  epoch {ep}: models {'identical' if same else 'differ'}, rel L2 {rel_l2(got, x_ref):.1e}")
+        assert rel_l2(got, x_ref) <= E2E_EPOCH_BAND
     assert np.linalg.norm(x_ref) > 0
