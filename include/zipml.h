@@ -210,6 +210,27 @@ int zipml_sgd_epoch_avg(void *stream, const void *packed1_dev, const void *packe
                         int64_t batch, float lr, float l2, int flags, void *workspace_dev,
                         size_t workspace_bytes);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: zipml_sgd_epoch with its workspace taken from a fixed
+ * array of ZIPML_STATIC_WORKSPACE_BYTES bytes that is part of the library's code object (every GPU
+ * the library runs on holds its own copy until the process ends).  The call allocates and frees
+ * nothing and calls no allocating routine; the address of the array on the current device is
+ * looked up on the first call on that device (make that call outside a capture).
+ * Arguments as zipml_sgd_epoch, without the workspace.  status_dev (device, one int, 4-byte
+ * aligned, required) receives what zipml_sgd_status would return for the call -- ZIPML_OK,
+ * ZIPML_ETIMEOUT or ZIPML_EUNSUPPORTED -- once the work enqueued on the stream is done.
+ * ZIPML_EWORKSPACE (with a line on stderr that names both sizes) if
+ * zipml_workspace_bytes(n, d, bits, batch, 0) exceeds ZIPML_STATIC_WORKSPACE_BYTES.
+ * All calls on one GPU share the one array, and it keeps what the last call left in it (a call
+ * clears what it needs cleared): calls that overlap in time on one GPU -- two streams, two host
+ * threads -- race and give undefined results; serialise them or use zipml_sgd_epoch. */
+#define ZIPML_STATIC_WORKSPACE_BYTES (8u << 20)
+int zipml_sgd_epoch_static(void *stream, const void *packed1_dev, const void *packed2_dev,
+                           const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
+                           float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d,
+                           int bits, float *x_dev, int64_t batch, float lr, int grad_bits,
+                           int model_bits, uint64_t seed, uint32_t epoch, int flags, int *status_dev);
+
 /* Waits for the stream and returns the status word the last zipml_sgd_epoch / zipml_debug_step
  * left in this workspace: ZIPML_OK or ZIPML_ETIMEOUT. */
 int zipml_sgd_status(void *stream, const void *workspace_dev, size_t workspace_bytes);

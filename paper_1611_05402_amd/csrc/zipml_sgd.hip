@@ -38,6 +38,7 @@
 
 #include <math.h>
 #include <algorithm>
+#include <mutex>
 #include <stdlib.h>
 
 namespace zipml {
@@ -1209,7 +1210,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
                    uint64_t seed, uint32_t epoch, int flags, int64_t step0, int64_t nsteps,
                    int32_t *dbg_m, int32_t *dbg_acc, float *dbg_r, float *dbg_g, int32_t *dbg_gq,
                    void *workspace_dev, size_t workspace_bytes, int prox = ZIPML_PROX_NONE,
-                   float prox_coef = 0.0f)
+                   float prox_coef = 0.0f, int *status_dev = nullptr)
 {
     if (!packed1_dev || !packed2_dev || !levels_dev || !b_dev || !x_dev) return ZIPML_EINVAL;
     if (prox != ZIPML_PROX_NONE && prox != ZIPML_PROX_L1 && prox != ZIPML_PROX_L2SQ && prox != ZIPML_PROX_BOX)
@@ -1353,7 +1354,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
             r.l2 = l2;
             r.prox = prox;
             r.prox_coef = prox_coef;
-            r.status = (int *)(wsb + Workspace::kStatus);
+            r.status = status_dev ? status_dev : (int *)(wsb + Workspace::kStatus);
             r.sync = (uint32_t *)(wsb + Workspace::kSync);
             r.even = (const int *)(wsb + Workspace::kEven);
             r.spin_limit = kSpinLimit;
@@ -1414,7 +1415,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
         const long v = atol(env);
         if (v >= 0 && v <= (long)kSpinLimit) a.spin_limit = (uint32_t)v;
     }
-    a.status = (int *)(ws + Workspace::kStatus);
+    a.status = status_dev ? status_dev : (int *)(ws + Workspace::kStatus);
     a.sync = (uint32_t *)(ws + Workspace::kSync);
     a.nrm = (double *)(ws + Workspace::kNorm);
     a.acc = (uint64_t *)(ws + Workspace::kAcc);
@@ -1515,6 +1516,61 @@ extern "C" int zipml_debug_step(void *stream, const void *packed1_dev, const voi
                    grid_lo, grid_step, grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits,
                    model_bits, seed, epoch, flags, step, 1, model_codes_dev, acc_dev, r_dev, g_dev, grad_codes_dev,
                    workspace_dev, workspace_bytes);
+}
+
+// ---------------------------------------------------------------------------------------------
+// zipml_sgd_epoch for callers that cannot allocate: the workspace is a fixed array inside the
+// library's code object.  `scratch` below is, in host code, only a stand-in for the symbol: its
+// device address differs from device to device and is looked up once per device with
+// hipGetSymbolAddress; everything after that uses the address found, never the name.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[ZIPML_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device; null: not looked up yet
+
+int static_scratch(void **out)
+{
+    int dev = 0;
+    if (HIP_FAILED(hipGetDevice(&dev))) return ZIPML_ELAUNCH;
+    if (dev < 0 || dev >= kMaxDevices) return ZIPML_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (HIP_FAILED(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) || !p) return ZIPML_ELAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ZIPML_OK;
+}
+}  // namespace
+
+extern "C" int zipml_sgd_epoch_static(void *stream, const void *packed1_dev, const void *packed2_dev,
+                                      const float *levels_dev, const uint16_t *grid_idx_dev,
+                                      float grid_lo, float grid_step, int grid_max,
+                                      const float *b_dev, int64_t n, int64_t d, int bits,
+                                      float *x_dev, int64_t batch, float lr, int grad_bits,
+                                      int model_bits, uint64_t seed, uint32_t epoch, int flags,
+                                      int *status_dev)
+{
+    if (!status_dev || (reinterpret_cast<uintptr_t>(status_dev) & 3u)) return ZIPML_EINVAL;
+    const size_t need = zipml_workspace_bytes(n, d, bits, batch, 0);
+    if (need == 0) return ZIPML_EINVAL;
+    if (need > (size_t)ZIPML_STATIC_WORKSPACE_BYTES) {
+        fprintf(stderr, "libzipml: zipml_sgd_epoch_static: this shape needs %zu bytes of workspace, the "
+                        "built-in one has %zu; use zipml_sgd_epoch with a workspace of the caller's\n",
+                need, (size_t)ZIPML_STATIC_WORKSPACE_BYTES);
+        return ZIPML_EWORKSPACE;
+    }
+    void *ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    const int64_t steps = (batch > 0 && n > 0 && n % batch == 0) ? n / batch : 0;
+    return run_sgd(stream, packed1_dev, packed2_dev, nullptr, nullptr, levels_dev, grid_idx_dev,
+                   grid_lo, grid_step, grid_max, b_dev, n, d, bits, x_dev, batch, lr, 0.0f, grad_bits,
+                   model_bits, seed, epoch, flags, 0, steps, nullptr, nullptr, nullptr, nullptr, nullptr,
+                   ws, (size_t)ZIPML_STATIC_WORKSPACE_BYTES, ZIPML_PROX_NONE, 0.0f, status_dev);
 }
 
 extern "C" int zipml_sgd_status(void *stream, const void *workspace_dev, size_t workspace_bytes)

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libzipml.so")
 UNIFORM, OPTIMAL, GREEDY = 0, 1, 2
 RANGE_GIVEN, SYMMETRIC = 1, 2
 SGD_STEPWISE, SGD_AVERAGED, SGD_PRODUCTION = 1, 2, 4
+STATIC_WORKSPACE_BYTES = 8 << 20
 PROX_NONE, PROX_L1, PROX_L2SQ, PROX_BOX = 0, 1, 2, 3
 
 OK, EINVAL, EALIGN, ERANGE, EWORKSPACE, ELAUNCH, EUNSUPPORTED, ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7
@@ -23,7 +24,8 @@ OK, EINVAL, EALIGN, ERANGE, EWORKSPACE, ELAUNCH, EUNSUPPORTED, ETIMEOUT = 0, -1,
 EXPORTS = ["zipml_strerror", "zipml_packed_bytes", "zipml_workspace_bytes", "zipml_levels",
            "zipml_quantize", "zipml_quantize_swapped", "zipml_compact_bytes", "zipml_compact_encode",
            "zipml_compact_decode", "zipml_sgd_epoch", "zipml_sgd_epoch_l2",
-           "zipml_sgd_epoch_prox", "zipml_sgd_epoch_avg", "zipml_sgd_status", "zipml_loss",
+           "zipml_sgd_epoch_prox", "zipml_sgd_epoch_avg", "zipml_sgd_epoch_static", "zipml_sgd_status",
+           "zipml_loss",
            "zipml_unpack_codes", "zipml_debug_step"]
 
 
@@ -76,6 +78,8 @@ def lib() -> C.CDLL:
         sgd = [vp, vp, vp, vp, vp, f32, f32, i32, vp, i64, i64, i32, vp, i64, f32, i32, i32, u64, u32]
         L.zipml_sgd_epoch.restype = i32
         L.zipml_sgd_epoch.argtypes = sgd + [i32, vp, sz]
+        L.zipml_sgd_epoch_static.restype = i32
+        L.zipml_sgd_epoch_static.argtypes = sgd + [i32, vp]
         L.zipml_sgd_epoch_l2.restype = i32
         L.zipml_sgd_epoch_l2.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, i64, f32, f32, i32, vp, sz]
         L.zipml_sgd_epoch_prox.restype = i32
@@ -160,6 +164,15 @@ def sgd_epoch(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, workspace
                      bits, x, batch, lr, grad_bits, model_bits, seed, epoch, stream)
     _check(lib().zipml_sgd_epoch(*args, flags, _ptr(workspace),
                                  workspace.numel() * workspace.element_size()), "zipml_sgd_epoch")
+
+
+def sgd_epoch_static(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, status, *, grid_idx=None,
+                     grid_lo=0.0, grid_step=0.0, grid_max=0, grad_bits=0, model_bits=0, seed=0, epoch=0,
+                     flags=0, stream=None):
+    """zipml_sgd_epoch on the library's built-in workspace (no allocation); `status`: int32 tensor."""
+    args = _sgd_args(packed1, packed2, levels_t, grid_idx, grid_lo, grid_step, grid_max, b, n, d,
+                     bits, x, batch, lr, grad_bits, model_bits, seed, epoch, stream)
+    _check(lib().zipml_sgd_epoch_static(*args, flags, _ptr(status)), "zipml_sgd_epoch_static")
 
 
 def sgd_epoch_l2(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, l2, workspace, *, flags=0,

@@ -125,6 +125,25 @@ def test_argument_errors_are_codes_not_crashes(lib):
     assert lib.zipml_sgd_status(null, null, 0) == zipml.EWORKSPACE
 
 
+def test_static_workspace_entry_point_argument_errors(lib):
+    """zipml_sgd_epoch_static validates before it touches the GPU: a missing or misaligned status
+    word, an invalid shape, and a shape whose workspace exceeds the built-in array are codes."""
+    null = None
+    fake = C.c_void_p(0x1000)
+    odd = C.c_void_p(0x1002)
+
+    def call(n=64, d=8, bits=4, batch=16, status=fake):
+        return lib.zipml_sgd_epoch_static(null, fake, fake, fake, null, 0.0, 0.0, 0, fake, n, d, bits,
+                                          fake, batch, 0.1, 0, 0, 0, 0, 0, status)
+    assert call(status=null) == zipml.EINVAL
+    assert call(status=odd) == zipml.EINVAL
+    assert call(bits=9) == zipml.EINVAL
+    assert call(n=0) == zipml.EINVAL
+    n_big = 1 << 20
+    assert lib.zipml_workspace_bytes(n_big, 16384, 4, n_big, 0) > zipml.STATIC_WORKSPACE_BYTES
+    assert call(n=n_big, d=16384, batch=n_big) == zipml.EWORKSPACE
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build runs on one GPU; bench.py says so instead of starting ranks."""
     import subprocess
