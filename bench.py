@@ -1,11 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark: double-sampled low-precision SGD epochs on one MI355X.
 
-One timed "step" is one full pass of the SGD hot path over the resident quantised data set
-(one zipml_sgd_epoch call = n / batch sequential minibatch steps: dot pass over copy 2,
-residuals, gradient pass over copy 1, model update).  The workload is the dense 8-bit
-least-squares problem (n = 65,536, d = 2,048, batch 256) with both packed copies already in
-HBM.  Prints ONE JSON line.
+One timed "step" is one full pass of the SGD hot path over the resident quantised data set (one
+zipml_sgd_epoch call = n / batch sequential minibatch steps: [model quantisation,] dot pass over
+copy 2, residuals, gradient pass over copy 1, [gradient quantisation,] model update).  Every
+workload of the benchmark spec beyond the tiny one is generated on the device at its full size,
+quantised by the library, and timed with both packed copies resident in HBM:
+
+  dense8  n=65,536   d=2,048   8-bit uniform levels             batch 256
+  lowbit  n=1,048,576 d=512    2-bit, per-column ranges         batch 1,024
+  tomo    n=262,144  d=16,384  4-bit uniform levels on [0,1]    batch 512   (4 GiB of codes)
+  e2e     n=524,288  d=4,096   3-bit variance-optimal levels from 1,024 candidates,
+                               8-bit model and gradient         batch 512
+
+The headline (`value`, `roofline`, `config.workload`) is the largest of them, the tomography
+shape; `configs` carries the same figures for all four.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -20,20 +29,26 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+HEADLINE = "tomo"
+ALL = ["dense8", "lowbit", "tomo", "e2e"]
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20, help="timed epochs")
+    ap.add_argument("--steps", type=int, default=20, help="timed epochs per workload")
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="dense8", choices=["tiny", "dense8", "lowbit"])
+    ap.add_argument("--workload", default="all", choices=["all", "tiny"] + ALL,
+                    help="all: the four full-size workloads, headline = tomo; else only that one")
     ap.add_argument("--batch", type=int, default=0, help="override the minibatch size")
+    ap.add_argument("--rows", type=int, default=0, help="override the number of samples (development)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the batch sweep and the timings of the other entry points")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0, help="per leg of the oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also launch plain device copies of known size (untimed), so that a "
-                         "rocprofv3 --pmc run of this command yields the HBM counter scale")
+                    help="also launch plain streaming reads and copies of known size (untimed), so "
+                         "that a rocprofv3 --pmc run of this command yields the HBM counter scale")
     return ap.parse_args()
 
 
@@ -54,25 +69,183 @@ def recorded_traffic(workload, batch):
     return None
 
 
-def cpu_baseline(w, A_rows, b_rows, L, seconds):
-    """The oracle's epoch loop, as it stands, timed on one host core on the first rows of
-    the same workload."""
+class Problem:
+    """One workload resident on the GPU: packed copies, levels, labels, workspace."""
+
+
+def prepare(name, args, torch, zipml, synth, dev):
+    """Generates the workload on the device chunk by chunk, computes its levels and quantises it
+    with the library.  The fp32 rows are kept only where a later call needs them."""
+    factory = synth.WORKLOADS[name]
+    n_full = args.rows or {"tiny": 4096, "dense8": 65536, "lowbit": 1048576, "tomo": 262144, "e2e": 524288}[name]
+    w = synth.light(factory, n_full)
+    if args.batch:
+        w.batch = args.batch
+    n, d, bits, B = w.n, w.d, w.bits, w.batch
+    K = 1 << bits
+    P = Problem()
+    P.w, P.name = w, name
+    t0 = time.perf_counter()
+    n_cand = w.n_candidates if w.levels == "optimal" else 0
+    P.ws = torch.zeros(zipml.workspace_bytes(n, d, bits, B, n_cand), dtype=torch.uint8, device=dev)
+    P.lev = torch.zeros(d, K, dtype=torch.float32, device=dev)
+    P.grid = torch.zeros(d, K, dtype=torch.int16, device=dev)
+    P.lo = torch.zeros(d, dtype=torch.float32, device=dev)
+    P.hi = torch.zeros(d, dtype=torch.float32, device=dev)
+    P.p1 = torch.zeros(zipml.packed_bytes(n, d, bits), dtype=torch.uint8, device=dev)
+    P.p2 = torch.zeros_like(P.p1)
+    P.b = torch.zeros(n, dtype=torch.float32, device=dev)
+    # levels that need the data (per-column ranges, level search) keep the fp32 rows resident;
+    # fixed ranges are quantised chunk by chunk as the rows are generated
+    keep = w.range_mode != "fixed" or w.levels == "optimal" or name == "dense8"
+    P.A = torch.empty(n, d, dtype=torch.float32, device=dev) if keep else None
+    P.A_head = P.b_head = None
+    fixed = w.range_mode == "fixed" and w.levels == "uniform"
+    if fixed:
+        P.lo.fill_(w.lo)
+        P.hi.fill_(w.hi)
+        zipml.levels(None, n, d, d, bits, zipml.UNIFORM, zipml.RANGE_GIVEN, 0, P.lo, P.hi, P.lev, P.grid, P.ws)
+    chunk = 8192 if d <= 4096 else 4096
+    head_rows = min(n, 4096)
+    for r0, A, b in synth.device_chunks(w, dev, chunk):
+        rows = A.shape[0]
+        P.b[r0:r0 + rows] = b
+        if r0 == 0:
+            P.A_head, P.b_head = A[:head_rows].cpu().numpy(), b[:head_rows].cpu().numpy()
+        if keep:
+            P.A[r0:r0 + rows] = A
+        if fixed:
+            zipml.quantize(A, rows, d, d, r0, n, P.lev, bits, 0, 0, P.p1, P.p2)
+        del A, b
+    torch.cuda.synchronize()
+    P.gen_s = time.perf_counter() - t0
+    P.grid_lo = P.grid_step = 0.0
+    P.grid_max = 0
+    t0 = time.perf_counter()
+    if not fixed:
+        if w.levels == "optimal":
+            # per-feature variance-optimal levels on the common grid [lo, hi] / n_candidates
+            P.lo.fill_(w.lo)
+            P.hi.fill_(w.hi)
+            zipml.levels(P.A, n, d, d, bits, zipml.OPTIMAL, zipml.RANGE_GIVEN, w.n_candidates, P.lo, P.hi,
+                         P.lev, P.grid, P.ws)
+            P.grid_lo, P.grid_step, P.grid_max = w.lo, (w.hi - w.lo) / w.n_candidates, w.n_candidates
+        else:
+            flags = zipml.SYMMETRIC if w.range_mode == "symmetric" else 0
+            zipml.levels(P.A, n, d, d, bits, zipml.UNIFORM, flags, 0, P.lo, P.hi, P.lev, P.grid, P.ws)
+        zipml.quantize(P.A, n, d, d, 0, n, P.lev, bits, 0, 0, P.p1, P.p2)
+    elif w.model_bits:
+        P.grid_lo, P.grid_step, P.grid_max = w.lo, (w.hi - w.lo) / (K - 1), K - 1
+    torch.cuda.synchronize()
+    P.levels_quantize_s = time.perf_counter() - t0
+    if keep and name != "dense8":
+        P.A = None          # only the dense workload times the fp32 entry points afterwards
+    return P
+
+
+def run_epochs(P, args, torch, zipml):
+    """Warm-up epochs, then K timed epochs with a HIP event after each; returns the figures."""
+    w = P.w
+    n, d, bits, B = w.n, w.d, w.bits, w.batch
+    x = torch.zeros(d, dtype=torch.float32, device=P.b.device)
+    kw = {}
+    if w.model_bits:
+        kw = dict(grid_idx=P.grid, grid_lo=P.grid_lo, grid_step=P.grid_step, grid_max=P.grid_max,
+                  grad_bits=w.grad_bits, model_bits=w.model_bits)
+    epoch_no = [0]
+
+    def epoch():
+        zipml.sgd_epoch(P.p1, P.p2, P.lev, P.b, n, d, bits, x, B, w.lr, P.ws, seed=0, epoch=epoch_no[0], **kw)
+        epoch_no[0] += 1
+
+    for _ in range(args.warmup):
+        epoch()
+    st = zipml.sgd_status(P.ws)
+    assert st == 0, zipml.strerror(st)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for k in range(args.steps):
+        epoch()
+        ev[k + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    st = zipml.sgd_status(P.ws)
+    assert st == 0, zipml.strerror(st)
+    per_epoch_ms = [ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)]
+    kern_ms = sum(per_epoch_ms) / len(per_epoch_ms)
+    alg_bytes = n * (2 * d * bits / 8 + 4)            # both packed copies once + labels
+    gbps = alg_bytes / (kern_ms * 1e-3) / 1e9
+    loss = zipml.loss(P.b, x, n, d, P.ws, packed=P.p2, copy=2, levels_t=P.lev, bits=bits)
+    mode = (f"{w.model_bits}-bit model and {w.grad_bits}-bit gradient" if w.model_bits else "fp32 model")
+    lv = (f"{bits}-bit variance-optimal levels from {w.n_candidates} candidates" if w.levels == "optimal"
+          else f"{bits}-bit uniform levels" + (" on per-column ranges" if w.range_mode != "fixed" else ""))
+    P.x = x
+    return {
+        "name": P.name,
+        "workload": f"{P.name}: n={n}, d={d}, {lv}, batch {B}, lr {w.lr}, {mode}",
+        "n": n, "d": d, "bits": bits, "batch": B,
+        "minibatch_steps_per_epoch": n // B,
+        "packed_bytes_per_epoch": int(alg_bytes),
+        "ms_per_epoch": kern_ms,
+        "ms_per_epoch_wall": wall / args.steps * 1e3,
+        "us_per_minibatch_step": kern_ms * 1e3 / (n // B),
+        "samples_per_s": args.steps * n / wall,
+        "packed_GBps": gbps,
+        "frac_hbm_peak": gbps / HBM_PEAK_GBS,
+        "loss_on_copy2_after_run": loss,
+        "generate_s": P.gen_s, "levels_and_quantize_s": P.levels_quantize_s,
+    }
+
+
+def cpu_baseline(P, seconds, threads):
+    """The oracle's epoch loop, as it stands, on the first rows of the workload: one thread, and
+    (plain estimator only) the rows of a minibatch over all host threads."""
     import numpy as np
     import oracle
-    c1, c2 = oracle.quantize(A_rows, L, w.bits, 0, 0)
+    w = P.w
+    B = w.batch
+    n_s = min(P.A_head.shape[0], max(B, (4096 if w.d <= 4096 else 1024)))
+    n_s -= n_s % B
+    A, b = P.A_head[:n_s], P.b_head[:n_s]
+    L = P.lev.cpu().numpy()
+    c1, c2 = oracle.quantize(A, L, w.bits, 0, 0)
     x = np.zeros(w.d, np.float32)
-    n_s = A_rows.shape[0]
+    G = P.grid.cpu().numpy().view(np.uint16)
+
+    def one(x, ep):
+        if w.model_bits:
+            return oracle.sgd_epoch_e2e(c1, c2, L, G, P.grid_lo, P.grid_step, b, w.bits, x, B, w.lr,
+                                        w.grad_bits, w.model_bits, 0, ep)
+        return oracle.sgd_epoch(c1, c2, L, b, w.bits, x, B, w.lr)
+
     t0 = time.perf_counter()
     passes = 0
     while True:
-        x = oracle.sgd_epoch(c1, c2, L, b_rows, w.bits, x, w.batch, w.lr)
+        x = one(x, passes)
         passes += 1
         el = time.perf_counter() - t0
         if el >= seconds:
             break
-    return {"value": passes * n_s / el, "unit": "samples/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {n_s} of {w.n} samples (d={w.d}, batch {w.batch}), {passes} passes "
-                      f"of the oracle epoch loop in {el:.1f} s, single thread"}
+    what = f"first {n_s} of {w.n} samples of {P.name} (d={w.d}, batch {B})"
+    single = {"value": passes * n_s / el, "unit": "samples/s", "cores": 1, "kind": "oracle",
+              "sample": f"{what}, {passes} passes of the oracle epoch loop in {el:.1f} s, one thread"}
+    many = None
+    if not w.model_bits:
+        x = np.zeros(w.d, np.float32)
+        t0 = time.perf_counter()
+        passes, used = 0, 1
+        while True:
+            x, used = oracle.sgd_epoch_threads(c1, c2, L, b, w.bits, x, B, w.lr, threads)
+            passes += 1
+            el = time.perf_counter() - t0
+            if el >= seconds:
+                break
+        many = {"value": passes * n_s / el, "unit": "samples/s", "cores": used, "kind": "oracle",
+                "sample": f"{what}, {passes} passes in {el:.1f} s, rows of each minibatch over {used} "
+                          f"threads, partial gradients added in thread order"}
+    return single, many
 
 
 def main():
@@ -84,40 +257,14 @@ def main():
     import numpy as np
     import torch
 
-    import oracle  # only for the cpu_baseline leg and the level table check
     from paper_1611_05402_amd import synth, zipml
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     zipml.lib()   # fails loudly if the HIP library is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = synth.WORKLOADS[args.workload]()
-    if args.batch:
-        w.batch = args.batch
-    n, d, bits, B = w.n, w.d, w.bits, w.batch
-    K = 1 << bits
-
-    # ---- synthetic data, resident in HBM before anything is timed
-    t0 = time.perf_counter()
-    ws = torch.zeros(zipml.workspace_bytes(n, d, bits, B), dtype=torch.uint8, device=dev)
-    lev = torch.zeros(d, K, dtype=torch.float32, device=dev)
-    lo = torch.zeros(d, dtype=torch.float32, device=dev)
-    hi = torch.zeros(d, dtype=torch.float32, device=dev)
-    p1 = torch.zeros(zipml.packed_bytes(n, d, bits), dtype=torch.uint8, device=dev)
-    p2 = torch.zeros_like(p1)
-    bd = torch.zeros(n, dtype=torch.float32, device=dev)
-    chunk = 8192
-    A_head = b_head = None
-    Ad_full = torch.empty(n, d, dtype=torch.float32, device=dev)
-    for r0 in range(0, n, chunk):
-        r1 = min(n, r0 + chunk)
-        A = w.rows(r0, r1)
-        b = w.labels(r0, r1, A)
-        if r0 == 0:
-            A_head, b_head = A, b
-        Ad_full[r0:r1].copy_(torch.from_numpy(A))
-        bd[r0:r1].copy_(torch.from_numpy(b))
-    gen_s = time.perf_counter() - t0
+    names = ALL if args.workload == "all" else [args.workload]
+    headline = HEADLINE if HEADLINE in names else names[0]
 
     def timed(fn, reps=3):
         fn()                      # first call: code object load, not what is being timed
@@ -130,66 +277,117 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps   # ms
 
-    if w.range_mode == "fixed":
-        lo.fill_(w.lo)
-        hi.fill_(w.hi)
-        flags = zipml.RANGE_GIVEN
-    else:
-        flags = zipml.SYMMETRIC if w.range_mode == "symmetric" else 0
-    levels_ms = timed(lambda: zipml.levels(Ad_full, n, d, d, bits, zipml.UNIFORM, flags, 0, lo, hi,
-                                           lev, None, ws))
-    quant_ms = timed(lambda: zipml.quantize(Ad_full, n, d, d, 0, n, lev, bits, 0, 0, p1, p2))
-
-    x = torch.zeros(d, dtype=torch.float32, device=dev)
-
-    def epoch():
-        zipml.sgd_epoch(p1, p2, lev, bd, n, d, bits, x, B, w.lr, ws)
-
-    for _ in range(args.warmup):
-        epoch()
-    assert zipml.sgd_status(ws) == 0
-    torch.cuda.synchronize()
-    # K epochs, bracketed by synchronize; HIP events on the launch stream give the device time
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t0 = time.perf_counter()
-    ev[0].record()
-    for k in range(args.steps):
-        epoch()
-        ev[k + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    assert zipml.sgd_status(ws) == 0
-    per_epoch_ms = [ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)]
-    kern_ms = sum(per_epoch_ms) / len(per_epoch_ms)
-
+    # ---- what a plain streaming read reaches on this machine: back-to-back launches of the library's
+    # streaming kernel over 4 GiB, timed by events only (no host synchronisation in between)
+    probe = torch.empty(4 << 30, dtype=torch.uint8, device=dev)
+    probe.view(torch.int32).random_(0, 1 << 30)
+    sink = torch.zeros(64, dtype=torch.int32, device=dev)
+    read_ms = timed(lambda: zipml.debug_stream(probe, sink), reps=8)
+    read_ceiling = probe.numel() / (read_ms * 1e-3) / 1e9
     if args.copy_calibration:
-        # a copy of known size on the same stream: 256 MiB read + 256 MiB written per launch
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
+        # launches of known traffic for the counter scale: 1 GiB read; 1 GiB read + 1 GiB written
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         for _ in range(3):
-            dst.copy_(src)
+            zipml.debug_stream(probe, sink, nbytes=1 << 30)
+            zipml.debug_stream(probe, sink, dst=dst, nbytes=1 << 30)
         torch.cuda.synchronize()
+        del dst
+    del probe
 
-    # ---- what a plain streaming read reaches on this machine: the library's fp32 loss kernel (reads
-    # 4 n d bytes once, nothing else) over 2 GiB
-    n_c = (2 << 30) // (4 * d)
-    A_c = torch.empty(n_c, d, dtype=torch.float32, device=dev).normal_()
-    b_c = torch.zeros(n_c, dtype=torch.float32, device=dev)
-    ws_c = torch.zeros(zipml.workspace_bytes(n_c, d, bits, B), dtype=torch.uint8, device=dev)
-    ceil_ms = timed(lambda: zipml.loss(b_c, x, n_c, d, ws_c, A=A_c, lda=d), reps=5)
-    read_ceiling = 4.0 * n_c * d / (ceil_ms * 1e-3) / 1e9
-    del A_c, b_c, ws_c
+    results, extras, baseline = [], {}, None
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16))
+    for name in names:
+        P = prepare(name, args, torch, zipml, synth, dev)
+        res = run_epochs(P, args, torch, zipml)
+        res["frac_of_measured_stream_read"] = res["packed_GBps"] / read_ceiling
+        res["hbm_traffic_bytes_per_epoch"] = recorded_traffic(name, P.w.batch)
+        results.append(res)
+        if name == headline and not args.no_cpu_baseline:
+            baseline = cpu_baseline(P, args.cpu_seconds, threads)
+        if name == "dense8" and not args.no_extras:
+            extras = dense_extras(P, args, torch, zipml, timed)
+        del P
+        torch.cuda.empty_cache()
 
-    # ---- the same epoch at larger minibatches (same resident data; not part of `value`):
-    # 4x, 16x and the whole data set per step, and the whole-data-set step on 8x the samples
-    # (random codes: only the rate matters there)
+    head = [r for r in results if r["name"] == headline][0]
+    model_dtype = ("i32 dot products on 8-bit model codes, f64 gradient sums, f32 master model"
+                   if headline == "e2e" else "f32 (model, residuals; sums taken exactly on i8 digits)")
+    out = {
+        "metric": "double-sampled SGD samples/sec (packed-data GB/s and % of HBM peak in roofline)",
+        "value": head["samples_per_s"],
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_epoch_wall"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": model_dtype,
+        "data": "synthetic",
+        "config": {"workload": head["workload"],
+                   "minibatch_steps_per_epoch": head["minibatch_steps_per_epoch"],
+                   "packed_bytes_per_epoch": head["packed_bytes_per_epoch"]},
+        "packed_GBps": head["packed_GBps"],
+        "roofline": {"bound": "hbm", "achieved": head["packed_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": head["frac_hbm_peak"], "traffic": head["hbm_traffic_bytes_per_epoch"],
+                     "kernel": f"k_sgd<{head['bits']}> (persistent epoch kernel, one launch per epoch)",
+                     "kernel_ms": head["ms_per_epoch"],
+                     "us_per_minibatch_step": head["us_per_minibatch_step"],
+                     "measured_stream_read_GBps": read_ceiling,
+                     "frac_of_measured_stream_read": head["packed_GBps"] / read_ceiling},
+        "configs": results,
+        "paper_context": "paper reports ratios only: up to 6.5x over a 32-bit FPGA implementation "
+                         "or 10-core Hogwild! (other hardware; not a target)",
+    }
+    out.update(extras)
+    if baseline:
+        out["cpu_baseline"] = baseline[0]
+        if baseline[1]:
+            out["cpu_baseline_all_cores"] = baseline[1]
+    print(json.dumps(out), flush=True)
+    # release everything and drain the device before the interpreter starts tearing modules down
+    del results, out
+    torch.cuda.synchronize()
+
+
+def dense_extras(P, args, torch, zipml, timed):
+    """On the dense 8-bit workload: the other entry points, and the same epoch at larger
+    minibatches (not part of `value`)."""
+    w = P.w
+    n, d, bits, B = w.n, w.d, w.bits, w.batch
+    dev = P.b.device
+    x = P.x
+    other = {}
+    other["levels_uniform"] = timed(lambda: zipml.levels(P.A, n, d, d, bits, zipml.UNIFORM, zipml.RANGE_GIVEN, 0,
+                                                         P.lo, P.hi, P.lev, None, P.ws))
+    q1, q2 = torch.zeros_like(P.p1), torch.zeros_like(P.p2)
+    other["quantize"] = timed(lambda: zipml.quantize(P.A, n, d, d, 0, n, P.lev, bits, 0, 0, q1, q2))
+    del q1, q2
+    other["loss_fp32"] = timed(lambda: zipml.loss(P.b, x, n, d, P.ws, A=P.A, lda=d))
+    other["loss_packed"] = timed(lambda: zipml.loss(P.b, x, n, d, P.ws, packed=P.p2, copy=2, levels_t=P.lev, bits=bits))
+    try:
+        lo2, hi2 = torch.zeros_like(P.lo), torch.zeros_like(P.hi)
+        lev3 = torch.zeros(d, 8, dtype=torch.float32, device=dev)
+        ws3 = torch.zeros(zipml.workspace_bytes(n, d, 3, B, 1024), dtype=torch.uint8, device=dev)
+        lev2 = torch.zeros_like(P.lev)
+        other["levels_with_range_scan"] = timed(
+            lambda: zipml.levels(P.A, n, d, d, bits, zipml.UNIFORM, 0, 0, lo2, hi2, lev2, None, ws3))
+        other["levels_optimal_3bit_1024bins"] = timed(
+            lambda: zipml.levels(P.A, n, d, d, 3, zipml.OPTIMAL, 0, 1024, lo2, hi2, lev3, None, ws3))
+        other["levels_greedy_3bit_1024bins"] = timed(
+            lambda: zipml.levels(P.A, n, d, d, 3, zipml.GREEDY, 0, 1024, lo2, hi2, lev3, None, ws3))
+        del ws3, lev3
+    except zipml.ZipmlError as e:
+        other["error"] = str(e)
+
     sweep = []
 
     def sweep_point(nn, p1s, p2s, bs, batch, reps=5):
         xs = torch.zeros(d, dtype=torch.float32, device=dev)
         wss = torch.zeros(zipml.workspace_bytes(nn, d, bits, batch), dtype=torch.uint8, device=dev)
         try:
-            ms = timed(lambda: zipml.sgd_epoch(p1s, p2s, lev, bs, nn, d, bits, xs, batch, w.lr, wss), reps)
+            ms = timed(lambda: zipml.sgd_epoch(p1s, p2s, P.lev, bs, nn, d, bits, xs, batch, w.lr, wss), reps)
         except zipml.ZipmlError as e:       # e.g. a shape whose large minibatches no kernel takes
             sweep.append({"n": nn, "batch": batch, "error": str(e)})
             return
@@ -198,82 +396,19 @@ def main():
             return
         nbytes = nn * (2 * d * bits / 8 + 4)
         sweep.append({"n": nn, "batch": batch, "ms_per_epoch": ms, "us_per_step": ms * 1e3 / (nn // batch),
-                      "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                      "frac_of_measured_read_ceiling": nbytes / (ms * 1e-3) / 1e9 / read_ceiling})
+                      "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
 
     if not args.batch:
         for mult in (4, 16):
             if n % (B * mult) == 0:
-                sweep_point(n, p1, p2, bd, B * mult)
-        sweep_point(n, p1, p2, bd, n)
+                sweep_point(n, P.p1, P.p2, P.b, B * mult)
+        sweep_point(n, P.p1, P.p2, P.b, n)
         n8 = 8 * n
         q1 = torch.randint(0, 256, (zipml.packed_bytes(n8, d, bits),), dtype=torch.uint8, device=dev)
         q2 = torch.randint(0, 256, (zipml.packed_bytes(n8, d, bits),), dtype=torch.uint8, device=dev)
         sweep_point(n8, q1, q2, torch.randn(n8, device=dev), n8)
         del q1, q2
-
-    loss_ms = timed(lambda: zipml.loss(bd, x, n, d, ws, A=Ad_full, lda=d))
-    final_loss = zipml.loss(bd, x, n, d, ws, A=Ad_full, lda=d)
-    loss_p_ms = timed(lambda: zipml.loss(bd, x, n, d, ws, packed=p2, copy=2, levels_t=lev, bits=bits))
-
-    # the data-dependent level computations on the same matrix (their results are not used by the
-    # timed epochs): column ranges + uniform levels, and the 3-bit level search over 1024 bins,
-    # plain dynamic program and greedy candidates
-    level_ms = {}
-    try:
-        lo2, hi2 = torch.zeros_like(lo), torch.zeros_like(hi)
-        lev3 = torch.zeros(d, 8, dtype=torch.float32, device=dev)
-        ws3 = torch.zeros(zipml.workspace_bytes(n, d, 3, B, 1024), dtype=torch.uint8, device=dev)
-        lev2 = torch.zeros_like(lev)
-        level_ms["levels_with_range_scan"] = timed(
-            lambda: zipml.levels(Ad_full, n, d, d, bits, zipml.UNIFORM, 0, 0, lo2, hi2, lev2, None, ws3))
-        level_ms["levels_optimal_3bit_1024bins"] = timed(
-            lambda: zipml.levels(Ad_full, n, d, d, 3, zipml.OPTIMAL, 0, 1024, lo2, hi2, lev3, None, ws3))
-        level_ms["levels_greedy_3bit_1024bins"] = timed(
-            lambda: zipml.levels(Ad_full, n, d, d, 3, zipml.GREEDY, 0, 1024, lo2, hi2, lev3, None, ws3))
-        del ws3, lev3
-    except zipml.ZipmlError as e:
-        level_ms["error"] = str(e)
-
-    samples_per_s = args.steps * n / wall
-    alg_bytes = n * (2 * d * bits / 8 + 4)            # both packed copies once + labels
-    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
-    out = {
-        "metric": "double-sampled SGD samples/sec (packed-data GB/s and % of HBM peak in roofline)",
-        "value": samples_per_s,
-        "unit": "samples/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": wall / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32 (model, residuals; sums taken exactly on i8 digits)",
-        "data": "synthetic",
-        "config": {"workload": f"{w.name}: n={n}, d={d}, {bits}-bit uniform levels, batch {B}, "
-                               f"lr {w.lr}, fp32 model", "minibatch_steps_per_epoch": n // B,
-                   "packed_bytes_per_epoch": int(alg_bytes)},
-        "packed_GBps": alg_bytes * args.steps / wall / 1e9,
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(w.name, B),
-                     "kernel": f"k_sgd<{bits}> (persistent epoch kernel)",
-                     "kernel_ms": kern_ms, "us_per_minibatch_step": kern_ms * 1e3 / (n // B),
-                     "measured_read_ceiling_GBps": read_ceiling,
-                     "frac_of_measured_read_ceiling": achieved / read_ceiling},
-        "other_ms": {"levels": levels_ms, "quantize": quant_ms, "loss_fp32": loss_ms,
-                     "loss_packed": loss_p_ms, **level_ms, "generate_and_upload_s": gen_s},
-        "batch_sweep": sweep,
-        "final_loss": final_loss,
-        "paper_context": "paper reports ratios only: up to 6.5x over a 32-bit FPGA implementation "
-                         "or 10-core Hogwild! (other hardware; not a target)",
-    }
-    if not args.no_cpu_baseline:
-        n_s = min(n, 4096 if d >= 1024 else 16384)
-        n_s -= n_s % B
-        L = oracle.levels_uniform(lo.cpu().numpy(), hi.cpu().numpy(), bits)
-        out["cpu_baseline"] = cpu_baseline(w, A_head[:n_s], b_head[:n_s], L, args.cpu_seconds)
-    print(json.dumps(out), flush=True)
+    return {"other_ms": other, "batch_sweep": sweep}
 
 
 if __name__ == "__main__":

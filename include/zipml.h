@@ -159,7 +159,8 @@ int zipml_compact_decode(void *stream, const void *compact_dev, int64_t n, int64
  * and batch a multiple of 64 (taken in chunks by replicas of the workgroups, or by workgroups that
  * own samples instead of features); otherwise ZIPML_EUNSUPPORTED, which for level tables that
  * turn out not to be evenly spaced arrives through zipml_sgd_status with x_dev left untouched.
- * The call is asynchronous; a failed grid-wide wait is reported by zipml_sgd_status. */
+ * The call is asynchronous; a failed grid-wide wait is reported by zipml_sgd_status (ZIPML_ETIMEOUT):
+ * the kernel then still runs to its end, and x_dev holds undefined values afterwards. */
 int zipml_sgd_epoch(void *stream, const void *packed1_dev, const void *packed2_dev,
                     const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
                     float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d,
@@ -196,7 +197,7 @@ int zipml_sgd_epoch_prox(void *stream, const void *packed1_dev, const void *pack
                          float *x_dev, int64_t batch, float lr, float l2, int prox, float prox_coef,
                          int flags, void *workspace_dev, size_t workspace_bytes);
 
-/* The same epoch with the symmetrised estimator (Supp. A.4: lower variance at no extra
+/* The same epoch with the symmetrised estimator (Supp. B.2 "Double Sampling", footnote: lower variance at no extra
  * randomness; the form the authors report running):
  *   g = 1/2 mean_i [ Q1(a_i) (Q2(a_i)^T x - b_i) + Q2(a_i) (Q1(a_i)^T x - b_i) ],
  * which needs both copies in both layouts: packed1s_dev / packed2s_dev from
@@ -267,6 +268,31 @@ int zipml_debug_step(void *stream, const void *packed1_dev, const void *packed2_
                      int model_bits, uint64_t seed, uint32_t epoch, int64_t step, int flags,
                      int32_t *model_codes_dev, int32_t *acc_dev, float *r_dev, float *g_dev,
                      int32_t *grad_codes_dev, void *workspace_dev, size_t workspace_bytes);
+
+/* A plain streaming pass of known size, for measurements: reads `bytes` bytes (a multiple of 16)
+ * at src_dev once, XORs all their 32-bit words into *sink_dev (which the caller clears beforehand)
+ * and, if dst_dev is not NULL, also stores them there (a copy).  Asynchronous.  It gives the
+ * streaming-read rate of the machine for a roofline, and a launch whose HBM traffic is known, by
+ * which hardware byte counters can be scaled. */
+int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t bytes,
+                       uint32_t *sink_dev);
+
+/* Development knobs: process-wide overrides of choices the library otherwise makes by itself, for
+ * sweeps, A/B measurements and tests that steer kernel selection (the library never reads the
+ * environment).  value = -1 restores the automatic choice.  Values out of a knob's range are
+ * ignored by the code that consults it.  Returns ZIPML_EINVAL for an unknown knob. */
+#define ZIPML_KNOB_TARGET_WORKGROUPS 0  /* preferred number of feature-owner workgroups (default 32)  */
+#define ZIPML_KNOB_NO_MATRIX_CORES   1  /* 1: evenly spaced levels stay on the vector-ALU step loop    */
+#define ZIPML_KNOB_CHUNK_SAMPLES     2  /* chunk size of minibatches taken in chunks                    */
+#define ZIPML_KNOB_MAX_REPLICAS      3  /* most replicas of the workgroups that share the chunks        */
+#define ZIPML_KNOB_ROWS_MIN_BATCH    4  /* smallest minibatch for the sample-owner kernel (>= 16384)    */
+#define ZIPML_KNOB_ROWS_ITEM_BLOCKS  5  /* 64-feature blocks per wave and item of that kernel           */
+#define ZIPML_KNOB_ROWS_WORKGROUPS   6  /* its number of workgroups                                     */
+#define ZIPML_KNOB_SPIN_LIMIT        7  /* polls before a device-wide wait gives up (0: at once)        */
+#define ZIPML_KNOB_HOST_DP           8  /* 1: the dynamic program of zipml_levels runs on the host     */
+#define ZIPML_KNOB_HIST_FEATURES     9  /* features per workgroup of the bin-moment kernel              */
+#define ZIPML_KNOB_COUNT            10
+int zipml_debug_set(int knob, int64_t value);
 
 #ifdef __cplusplus
 }

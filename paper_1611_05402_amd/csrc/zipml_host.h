@@ -1,6 +1,7 @@
 // Host-side helpers shared by the libzipml entry points.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdio.h>
 #include <stdint.h>
@@ -74,6 +75,13 @@ struct Workspace {
         return ((size_t)(kMaxRowsWgs + 2) * (size_t)round_up(d, 64) + kMaxRowsWgs + 64) * 4;
     }
 };
+
+// Development knobs (zipml_debug_set): process-wide overrides of choices the library otherwise
+// makes by itself, used by sweeps and by tests that steer kernel selection.  -1 = automatic.
+// The library never reads the environment.
+constexpr int kKnobs = ZIPML_KNOB_COUNT;
+inline std::atomic<long long> g_knob[kKnobs] = {};   // value + 1, so that zero-initialised means "automatic"
+inline long long knob(int k) { return g_knob[k].load(std::memory_order_relaxed) - 1; }
 
 // Called on entry of every API function: hipGetLastError() is sticky per host thread, so an
 // error left behind by an earlier, unrelated runtime call of the caller (e.g. a pointer query on

@@ -527,10 +527,8 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
             const int64_t rounds = ((d + f - 1) / f + cus - 1) / cus;
             if (best < 0 || rounds * f <= best) { best = rounds * f; F = f; }
         }
-        if (const char *env = getenv("ZIPML_HIST_FEATURES")) {   // tuning override: a power of two that fits
-            const int v = atoi(env);
-            if (v >= 1 && v <= Fmax && (v & (v - 1)) == 0) F = v;
-        }
+        // development override: a power of two that fits
+        if (const long long v = knob(ZIPML_KNOB_HIST_FEATURES); v >= 1 && v <= Fmax && (v & (v - 1)) == 0) F = (int)v;
         const size_t hl = hist_lds_bytes(M, F);
         if (hl > (size_t)lds_limit) return ZIPML_EUNSUPPORTED;
         const int64_t fblocks = (d + F - 1) / F;
@@ -556,7 +554,7 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
     const size_t dp_lds = greedy ? dp_lds_bytes(Mcap, sI) : dp_lds_bytes(M, sI);
     if (greedy && (dp_lds > (size_t)lds_limit || greedy_lds_bytes(M) > (size_t)lds_limit))
         return ZIPML_EUNSUPPORTED;
-    if (greedy || (dp_lds <= (size_t)lds_limit && !getenv("ZIPML_HOST_DP"))) {
+    if (greedy || (dp_lds <= (size_t)lds_limit && knob(ZIPML_KNOB_HOST_DP) <= 0)) {
         double *objective_dev = hist_dev + hcount;
         uint16_t *grid_dev = grid_idx_dev;       // may be null
         uint16_t *sel_dev = nullptr;
@@ -645,6 +643,13 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
                                        hipMemcpyHostToDevice, s) != hipSuccess)
         return ZIPML_ELAUNCH;
     if (hipStreamSynchronize(s) != hipSuccess) return ZIPML_ELAUNCH;
+    return ZIPML_OK;
+}
+
+extern "C" int zipml_debug_set(int knob_id, int64_t value)
+{
+    if (knob_id < 0 || knob_id >= ZIPML_KNOB_COUNT || value < -1) return ZIPML_EINVAL;
+    g_knob[knob_id].store((long long)value + 1, std::memory_order_relaxed);
     return ZIPML_OK;
 }
 

@@ -325,9 +325,55 @@ static int launch_loss_mfma(hipStream_t s, const uint32_t *p, const Layout &lay,
     return blocks;
 }
 
+// A plain streaming kernel of known size: reads `n16` 16-byte words once (non-temporal loads, four
+// in flight per thread), XORs their dwords into *sink, and, with dst, stores them as well.
+__global__ __launch_bounds__(256) void k_stream_probe(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                      size_t n16, uint32_t *sink)
+{
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const u4 *in = reinterpret_cast<const u4 *>(src);
+    u4 *out = reinterpret_cast<u4 *>(dst);
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t x = 0;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        u4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = __builtin_nontemporal_load(in + i + k * stride);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (out) __builtin_nontemporal_store(v[k], out + i + k * stride);
+            x ^= v[k][0] ^ v[k][1] ^ v[k][2] ^ v[k][3];
+        }
+    }
+    for (; i < n16; i += stride) {
+        const u4 v = __builtin_nontemporal_load(in + i);
+        if (out) __builtin_nontemporal_store(v, out + i);
+        x ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+    x = wave_reduce_dpp(x, [](uint32_t p, uint32_t q) { return p ^ q; });
+    if ((threadIdx.x & (kWave - 1)) == 0) atomicXor(sink, x);
+}
+
 }  // namespace zipml
 
 using namespace zipml;
+
+extern "C" int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t bytes,
+                                  uint32_t *sink_dev)
+{
+    if (!src_dev || !sink_dev || bytes == 0 || bytes % 16 != 0) return ZIPML_EINVAL;
+    if (!aligned16(src_dev) || (dst_dev && !aligned16(dst_dev)) || (reinterpret_cast<uintptr_t>(sink_dev) & 3u))
+        return ZIPML_EALIGN;
+    hipStream_t s = entry_stream(stream);
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 256 * 4 - 1) / (256 * 4);
+    const unsigned blocks = (unsigned)(want < 1 ? 1 : want > 4096 ? 4096 : want);
+    hipLaunchKernelGGL(k_stream_probe, dim3(blocks), dim3(256), 0, s, (const uint4 *)src_dev, (uint4 *)dst_dev,
+                       n16, sink_dev);
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+    return ZIPML_OK;
+}
 
 extern "C" int zipml_loss(void *stream, const float *A_dev, int64_t lda, const void *packed_dev,
                           int copy, const float *levels_dev, int bits, const float *b_dev,
@@ -362,7 +408,7 @@ extern "C" int zipml_loss(void *stream, const float *A_dev, int64_t lda, const v
         // copy 2, 2/4/8 bits: matrix-core kernel (needs room for its flags behind the partials)
         const size_t flags_at = (size_t)(kLossMaxBlocks + 1) * sizeof(double);
         if (copy == 2 && (bits == 2 || bits == 4 || bits == 8) &&
-            workspace_bytes >= flags_at + kLossEvenBlocks * sizeof(int) && !getenv("ZIPML_NO_MFMA")) {
+            workspace_bytes >= flags_at + kLossEvenBlocks * sizeof(int) && knob(ZIPML_KNOB_NO_MATRIX_CORES) <= 0) {
             int dev = 0, lds = 0;
             if (hipGetDevice(&dev) == hipSuccess &&
                 hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess) {

@@ -1050,10 +1050,8 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool int
 // bound the choice from both sides.
 static int target_workgroups()
 {
-    if (const char *env = getenv("ZIPML_TARGET_W")) {   // tuning override: preferred workgroup count
-        const int v = atoi(env);
-        if (v >= 1 && v <= 512) return v;
-    }
+    const long long v = knob(ZIPML_KNOB_TARGET_WORKGROUPS);   // development override
+    if (v >= 1 && v <= 512) return (int)v;
     return 32;
 }
 
@@ -1074,7 +1072,7 @@ static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool 
         // than one workgroup, at most 8 feature tiles of 16 (whether the levels are evenly
         // spaced is found out by the kernel)
         const bool mfma = fp32_model && (bits == 2 || bits == 4 || bits == 8) && batch % 64 == 0 &&
-                          W > 1 && GQ <= 4 && !getenv("ZIPML_NO_MFMA");
+                          W > 1 && GQ <= 4 && knob(ZIPML_KNOB_NO_MATRIX_CORES) <= 0;
         const size_t sh = plan_lds(GQ, bits, batch, int_table, !fp32_model, W == 1, mfma, pairs, lds, ll);
         if (!sh) break;
         best = GQ;
@@ -1171,10 +1169,7 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
     // blocks per wave and item: as many as the registers hold, fewer for narrow problems
     // (measured: short items are best at 4 and 8 bits, 5.8-5.9 TB/s; 2-bit codes want two blocks)
     int kpi = BITS == 2 ? 2 : 1;
-    if (const char *env = getenv("ZIPML_ROWS_KPI")) {   // tuning override (at most 32 / BITS)
-        const int v = atoi(env);
-        if (v >= 1 && v <= 32 / BITS) kpi = v;
-    }
+    if (const long long v = knob(ZIPML_KNOB_ROWS_ITEM_BLOCKS); v >= 1 && v <= 32 / BITS) kpi = (int)v;   // development override
     while (kpi > 1 && (r.NKB < kWaves * kpi || (kpi & (kpi - 1)))) --kpi;
     const void *kern = nullptr;
     if constexpr (BITS == 8) kern = kpi >= 2 ? (const void *)k_sgd_rows<8, 2> : (const void *)k_sgd_rows<8, 1>;
@@ -1268,7 +1263,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     const bool debug = dbg_m || dbg_acc || dbg_r || dbg_g || dbg_gq;
     int replicas = 1;
     int64_t forced = 0;
-    if (const char *env = getenv("ZIPML_MICRO_BATCH")) forced = atol(env);   // tuning override: chunk size
+    if (knob(ZIPML_KNOB_CHUNK_SAMPLES) > 0) forced = knob(ZIPML_KNOB_CHUNK_SAMPLES);   // development override: chunk size
     if (production && (rc != ZIPML_OK || !p.mfma)) return ZIPML_EUNSUPPORTED;
     const bool split_ok = model_bits == 0 && !stepwise && !debug && batch % 64 == 0 &&
                           (bits == 2 || bits == 4 || bits == 8);
@@ -1300,10 +1295,7 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
             // The chunks of a minibatch are independent: R replicas of the W workgroups take every
             // R-th chunk each (R a power of two that divides the number of chunks).
             int64_t cap = std::min<int64_t>(cus / p.W, Workspace::kMaxReplicas);
-            if (const char *env = getenv("ZIPML_REPLICAS")) {   // tuning override: at most this many
-                const long v = atol(env);
-                if (v >= 1) cap = std::min<int64_t>(cap, v);
-            }
+            if (const long long v = knob(ZIPML_KNOB_MAX_REPLICAS); v >= 1) cap = std::min<int64_t>(cap, v);   // development override
             while (replicas * 2 <= cap && chunks % (replicas * 2) == 0) replicas *= 2;
         }
     }
@@ -1314,24 +1306,19 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
         // It pays from about two tiles of 64 samples per compute unit on (a step costs two
         // device-wide barriers and a reduction over all workgroups), earlier for wide problems.
         int64_t rows_min = lay.d_pad >= 8192 ? Workspace::kRowsMinBatch : 2 * Workspace::kRowsMinBatch;
-        if (const char *env = getenv("ZIPML_ROWS_MIN_BATCH")) {   // tuning override (not below the workspace's rule)
-            const long v = atol(env);
-            if (v >= Workspace::kRowsMinBatch) rows_min = v;
-        }
+        // development override (not below the workspace's rule)
+        if (const long long v = knob(ZIPML_KNOB_ROWS_MIN_BATCH); v >= Workspace::kRowsMinBatch) rows_min = v;
         int cus = 0, lds = 0;
         if (int lrc = device_limits(cus, lds)) return lrc;
         const int NKB = (int)((lay.d32 + 1) / 2);
         // (the kernel's per-lane byte offsets are 32 bits wide: one feature group of copy 2 must fit)
         if (split_ok && batch >= rows_min && batch / 64 >= cus &&
             rows_lds_bytes(NKB) <= (size_t)lds && lay.n_pad * bits * 4 < ((int64_t)1 << 32) &&
-            !getenv("ZIPML_NO_MFMA")) {
+            knob(ZIPML_KNOB_NO_MATRIX_CORES) <= 0) {
             unsigned char *wsb = (unsigned char *)workspace_dev;
             float *rows = (float *)(wsb + Workspace::sgd_bytes(batch) + (size_t)round_up(d, 64) * 4);
             int wgs = std::min(cus, Workspace::kMaxRowsWgs);
-            if (const char *env = getenv("ZIPML_ROWS_WGS")) {   // tuning override
-                const int v = atoi(env);
-                if (v >= 1 && v <= Workspace::kMaxRowsWgs) wgs = v;
-            }
+            if (const long long v = knob(ZIPML_KNOB_ROWS_WORKGROUPS); v >= 1 && v <= Workspace::kMaxRowsWgs) wgs = (int)v;   // development override
             RowsArgs r{};
             r.p1 = (const uint32_t *)packed1_dev;
             r.p2 = (const uint32_t *)packed2_dev;
@@ -1358,10 +1345,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
             r.sync = (uint32_t *)(wsb + Workspace::kSync);
             r.even = (const int *)(wsb + Workspace::kEven);
             r.spin_limit = kSpinLimit;
-            if (const char *env = getenv("ZIPML_SPIN_LIMIT")) {   // test hook: make every wait give up early
-                const long v = atol(env);
-                if (v >= 0 && v <= (long)kSpinLimit) r.spin_limit = (uint32_t)v;
-            }
+            // test hook: make every wait give up early
+            if (const long long v = knob(ZIPML_KNOB_SPIN_LIMIT); v >= 0 && v <= (long long)kSpinLimit) r.spin_limit = (uint32_t)v;
             int *even = (int *)(wsb + Workspace::kEven);
             uint64_t *acc = (uint64_t *)(wsb + Workspace::kAcc);
             switch (bits) {
@@ -1411,10 +1396,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     a.mfma = (p.mfma && !stepwise && (!debug || production)) ? 1 : 0;   // the matrix-core loop exists in the production launch only
     a.dbg_production = production ? 1 : 0;
     a.spin_limit = kSpinLimit;
-    if (const char *env = getenv("ZIPML_SPIN_LIMIT")) {   // test hook: make every wait give up early
-        const long v = atol(env);
-        if (v >= 0 && v <= (long)kSpinLimit) a.spin_limit = (uint32_t)v;
-    }
+    // test hook: make every wait give up early
+    if (const long long v = knob(ZIPML_KNOB_SPIN_LIMIT); v >= 0 && v <= (long long)kSpinLimit) a.spin_limit = (uint32_t)v;
     a.status = status_dev ? status_dev : (int *)(ws + Workspace::kStatus);
     a.sync = (uint32_t *)(ws + Workspace::kSync);
     a.nrm = (double *)(ws + Workspace::kNorm);

@@ -43,7 +43,7 @@ constexpr int kRefresh = 16;   // steps between exact refreshes of the magnitude
 
 // KB: 64-feature blocks per workgroup (1: GQ <= 2, 2: GQ == 4).
 // NC: 1 = the estimator of eq. (5), g = mean_i Q1(a_i) (Q2(a_i)^T x - b_i);
-//     2 = its symmetrised form (Supp. A.4), 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)]: a
+//     2 = its symmetrised form (Supp. B.2, footnote), 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)]: a
 //     second pair of packed arrays holds copy 1 sample-major and copy 2 feature-major, both
 //     pairs go through the same two passes at the same model, with one exchange for both.
 // REP: the chunks of a minibatch are shared out over replicas of the workgroups (a.R > 1).

@@ -16,7 +16,7 @@
 // non-temporal loads that no branch can skip) in flight while it feeds the previous one to the
 // matrix cores.
 //
-// The symmetrised estimator (Supp. A.4; AVG) runs every tile of samples twice, once per code pair
+// The symmetrised estimator (Supp. B.2, footnote; AVG) runs every tile of samples twice, once per code pair
 // -- (copy 2, copy 1) and (copy 1 sample-major, copy 2 feature-major) -- into the same gradient,
 // which is then the sum over both pairs, and the sum of residuals the sum over both.
 //

@@ -61,7 +61,6 @@ class Workload:
                 A *= self._col_scale[None, :]
         elif self.kind == "gauss":
             A = np.clip(rng.standard_normal(size=(rows, d), dtype=np.float32), -3.0, 3.0)
-            A *= np.float32(1.0 / 3.0)   # column max-abs of clipped N(0,1) is 3
         elif self.kind == "lognormal":
             A = np.exp(rng.standard_normal(size=(rows, d), dtype=np.float32))
         elif self.kind == "tomo":
@@ -82,6 +81,8 @@ class Workload:
             if self.kind == "lognormal":
                 A = (A - self._col_min[None, :]) / (self._col_max - self._col_min)[None, :]
                 A = np.clip(A, 0.0, 1.0).astype(np.float32)
+            elif self.kind == "gauss":
+                A = A / self._col_max[None, :]      # every column scaled by its own max-abs to [-1, 1]
             c0 = chunk * CHUNK
             a, b = max(i0, c0), min(i1, c0 + A.shape[0])
             out[a - i0:b - i0] = A[a - c0:b - c0]
@@ -163,6 +164,13 @@ def _finish(w: Workload, x_scale: float) -> Workload:
         small = rng.permutation(w.d)[: w.d // 5]      # a fixed random 20 % of the columns
         scale[small] = 0.05
         w._col_scale = scale
+    if w.kind == "gauss":
+        # column max-abs over all rows (with 65,536 rows every column holds clipped values, so it
+        # is the clip bound 3 for all of them; shorter test problems get their own maxima)
+        mx = np.zeros(w.d, np.float32)
+        for chunk in range((w.n + CHUNK - 1) // CHUNK):
+            mx = np.maximum(mx, np.abs(w._raw_chunk(chunk)).max(axis=0))
+        w._col_max = np.maximum(mx, np.float32(1e-30))
     if w.kind == "lognormal":
         mn = np.full(w.d, np.inf, np.float32)
         mx = np.full(w.d, -np.inf, np.float32)
@@ -221,3 +229,96 @@ def ongrid(n=1024, d=32, seed=0, bits=3, batch=32, lo=-1.0, hi=1.0) -> Workload:
 
 
 WORKLOADS = {"lssvm": lssvm, "tiny": tiny, "dense8": dense8, "lowbit": lowbit, "tomo": tomo, "e2e": e2e}
+
+
+# ---------------------------------------------------------------------------------------------
+# The same recipes generated on the GPU with torch, for the full-size problems of bench.py (16 GiB
+# of fp32 rows for the tomography shape would take minutes through NumPy and the host link).  The
+# random streams differ from the NumPy ones above -- these are other samples of the same
+# distributions -- and are seeded per chunk as well.  Input generation only: no method arithmetic.
+# ---------------------------------------------------------------------------------------------
+def _device_gen(w: Workload, chunk: int, what: int, device):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed((((w.seed * 8 + _KIND_ID[w.kind]) * 4 + what) << 24) + chunk)
+    return g
+
+
+def _device_raw_chunk(w: Workload, chunk: int, rows: int, device):
+    import torch
+    g = _device_gen(w, chunk, 0, device)
+    d = w.d
+    if w.kind in ("uniform", "hetero"):
+        A = torch.rand(rows, d, generator=g, device=device, dtype=torch.float32) * 2.0 - 1.0
+        if w.kind == "hetero":
+            A *= torch.from_numpy(w._col_scale).to(device)[None, :]
+    elif w.kind == "gauss":
+        A = torch.randn(rows, d, generator=g, device=device, dtype=torch.float32).clamp_(-3.0, 3.0)
+    elif w.kind == "lognormal":
+        A = torch.randn(rows, d, generator=g, device=device, dtype=torch.float32).exp_()
+    elif w.kind == "tomo":
+        # rays as in _tomo_rows; a crossed pixel gets a U[0,1] weight of its own (a ray visits a
+        # pixel in several steps, and which duplicate write wins is not defined on a GPU)
+        side = int(round(np.sqrt(d)))
+        half = side / 2.0
+        diag = half * np.sqrt(2.0)
+        theta = torch.rand(rows, generator=g, device=device, dtype=torch.float64) * np.pi
+        off = (torch.rand(rows, generator=g, device=device, dtype=torch.float64) * 2.0 - 1.0) * diag
+        steps = 2 * side
+        t = torch.linspace(-diag, diag, steps, device=device, dtype=torch.float64)
+        cx = half + off[:, None] * (-torch.sin(theta))[:, None] + t[None, :] * torch.cos(theta)[:, None]
+        cy = half + off[:, None] * torch.cos(theta)[:, None] + t[None, :] * torch.sin(theta)[:, None]
+        px, py = torch.floor(cx).long(), torch.floor(cy).long()
+        ok = (px >= 0) & (px < side) & (py >= 0) & (py < side)
+        idx = (py * side + px).clamp_(0, d - 1)
+        mask = torch.zeros(rows, d, device=device, dtype=torch.float32)
+        mask.scatter_add_(1, idx, ok.to(torch.float32))
+        A = torch.rand(rows, d, generator=g, device=device, dtype=torch.float32)
+        A *= (mask > 0).to(torch.float32)
+    else:
+        raise ValueError(w.kind)
+    return A
+
+
+def device_chunks(w: Workload, device, chunk_rows: int = CHUNK):
+    """Yields (first row, A [rows, d] fp32 on `device`, b [rows] fp32) for consecutive row chunks of
+    the whole problem, generated on the device.  Kinds normalised per column (gauss, lognormal)
+    take a first pass over the raw chunks for the column statistics."""
+    import torch
+    n, d = w.n, w.d
+    nchunks = (n + chunk_rows - 1) // chunk_rows
+    rows_of = lambda c: min(chunk_rows, n - c * chunk_rows)
+    col_min = col_max = None
+    if w.kind in ("gauss", "lognormal"):
+        col_min = torch.full((d,), float("inf"), device=device)
+        col_max = torch.full((d,), float("-inf"), device=device)
+        for c in range(nchunks):
+            A = _device_raw_chunk(w, c, rows_of(c), device)
+            if w.kind == "gauss":
+                A = A.abs_()
+            col_min = torch.minimum(col_min, A.min(dim=0).values)
+            col_max = torch.maximum(col_max, A.max(dim=0).values)
+            del A
+    xs = torch.from_numpy(np.asarray(w.x_star, np.float32)).to(device)
+    for c in range(nchunks):
+        rows = rows_of(c)
+        A = _device_raw_chunk(w, c, rows, device)
+        if w.kind == "gauss":
+            A /= col_max[None, :]
+        elif w.kind == "lognormal":
+            A = ((A - col_min[None, :]) / (col_max - col_min)[None, :]).clamp_(0.0, 1.0)
+        b = A @ xs
+        if w.noise > 0.0:
+            b += torch.randn(rows, generator=_device_gen(w, c, 1, device), device=device) * w.noise
+        if w.sign_labels:
+            b = torch.where(b >= 0, 1.0, -1.0)
+        yield c * chunk_rows, A, b.to(torch.float32)
+
+
+def light(factory, n: int, **kw) -> Workload:
+    """The description of an n-row workload without the host-side column statistics (for
+    device_chunks, which takes its own): the full-size lognormal problem would otherwise be
+    generated once on the host just for them."""
+    w = factory(n=min(n, CHUNK), **kw)
+    w.n = n
+    return w

@@ -25,7 +25,7 @@ EXPORTS = ["zipml_strerror", "zipml_packed_bytes", "zipml_workspace_bytes", "zip
            "zipml_quantize", "zipml_quantize_swapped", "zipml_compact_bytes", "zipml_compact_encode",
            "zipml_compact_decode", "zipml_sgd_epoch", "zipml_sgd_epoch_l2",
            "zipml_sgd_epoch_prox", "zipml_sgd_epoch_avg", "zipml_sgd_epoch_static", "zipml_sgd_status",
-           "zipml_loss",
+           "zipml_loss", "zipml_debug_stream", "zipml_debug_set",
            "zipml_unpack_codes", "zipml_debug_step"]
 
 
@@ -92,6 +92,10 @@ def lib() -> C.CDLL:
         L.zipml_loss.restype = i32
         L.zipml_loss.argtypes = [vp, vp, i64, vp, i32, vp, i32, vp, vp, i64, i64,
                                  C.POINTER(C.c_double), vp, sz]
+        L.zipml_debug_stream.restype = i32
+        L.zipml_debug_stream.argtypes = [vp, vp, vp, sz, vp]
+        L.zipml_debug_set.restype = i32
+        L.zipml_debug_set.argtypes = [i32, i64]
         L.zipml_unpack_codes.restype = i32
         L.zipml_unpack_codes.argtypes = [vp, vp, i32, i64, i64, i32, vp]
         _lib = L
@@ -115,6 +119,22 @@ def _stream(stream=None):
     import torch
     s = stream if stream is not None else torch.cuda.current_stream()
     return C.c_void_p(s.cuda_stream)
+
+
+(KNOB_TARGET_WORKGROUPS, KNOB_NO_MATRIX_CORES, KNOB_CHUNK_SAMPLES, KNOB_MAX_REPLICAS, KNOB_ROWS_MIN_BATCH,
+ KNOB_ROWS_ITEM_BLOCKS, KNOB_ROWS_WORKGROUPS, KNOB_SPIN_LIMIT, KNOB_HOST_DP, KNOB_HIST_FEATURES) = range(10)
+
+
+def debug_set(knob: int, value: int) -> None:
+    """Development knob (see include/zipml.h); value -1 restores the automatic choice."""
+    _check(lib().zipml_debug_set(knob, value), "zipml_debug_set")
+
+
+def debug_stream(src, sink, dst=None, nbytes=None, stream=None) -> None:
+    """Plain streaming read (or copy, with dst) of known size; XOR of all dwords into sink[0]."""
+    nb = src.numel() * src.element_size() if nbytes is None else nbytes
+    _check(lib().zipml_debug_stream(_stream(stream), _ptr(src), _ptr(dst), nb, _ptr(sink)),
+           "zipml_debug_stream")
 
 
 def packed_bytes(n: int, d: int, bits: int) -> int:

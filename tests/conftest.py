@@ -25,3 +25,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def knobs():
+    """Sets development knobs of the library (zipml_debug_set) for one test and restores the
+    automatic choices afterwards."""
+    from paper_1611_05402_amd import zipml
+    used = []
+
+    def set_knob(knob, value):
+        zipml.debug_set(knob, value)
+        used.append(knob)
+
+    yield set_knob
+    for knob in used:
+        zipml.debug_set(knob, -1)

@@ -144,6 +144,18 @@ def test_static_workspace_entry_point_argument_errors(lib):
     assert call(n=n_big, d=16384, batch=n_big) == zipml.EWORKSPACE
 
 
+def test_development_knobs_are_validated(lib):
+    assert lib.zipml_debug_set(zipml.KNOB_SPIN_LIMIT, 5) == zipml.OK
+    assert lib.zipml_debug_set(zipml.KNOB_SPIN_LIMIT, -1) == zipml.OK
+    assert lib.zipml_debug_set(-1, 0) == zipml.EINVAL
+    assert lib.zipml_debug_set(10, 0) == zipml.EINVAL
+    assert lib.zipml_debug_set(zipml.KNOB_HOST_DP, -2) == zipml.EINVAL
+    # and the product reads no environment variable
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "paper_1611_05402_amd", "csrc", "*")):
+        assert "getenv" not in open(path).read(), path
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build runs on one GPU; bench.py says so instead of starting ranks."""
     import subprocess

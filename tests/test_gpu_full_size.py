@@ -67,7 +67,7 @@ def test_dense8_full_size_codes_epoch_and_loss():
             say(f"  epoch {ep}: rel L2 {err:.2e}")
             assert err <= TOL and max_abs_ok(x.cpu().numpy(), x_ref, TOL)
         assert np.linalg.norm(x_ref) > 0
-    # the symmetrised estimator (Supp. A.4) at the headline minibatch (feature owners) and with one
+    # the symmetrised estimator (Supp. B.2, footnote) at the headline minibatch (feature owners) and with one
     # step per epoch (sample owners)
     p1s, p2s = torch.zeros_like(p.p1), torch.zeros_like(p.p2)
     zipml.quantize_swapped(p.A, w.n, w.d, w.d, 0, w.n, p.levels, w.bits, 0, 0, p1s, p2s)

@@ -69,7 +69,7 @@ def test_optimal_levels_match_oracle_dp(n, d, M):
         assert np.array_equal(Lg[j], expect.astype(np.float32))
 
 
-def test_device_and_host_level_search_agree(monkeypatch):
+def test_device_and_host_level_search_agree(knobs):
     """The dynamic program runs on the device when its tables fit in LDS and on the host cores
     otherwise; both must give the same levels, index by index."""
     say("levels optimal: device vs host dynamic program")
@@ -79,13 +79,13 @@ def test_device_and_host_level_search_agree(monkeypatch):
         res = []
         for host in (False, True):
             if host:
-                monkeypatch.setenv("ZIPML_HOST_DP", "1")
+                knobs(zipml.KNOB_HOST_DP, 1)
             else:
-                monkeypatch.delenv("ZIPML_HOST_DP", raising=False)
+                knobs(zipml.KNOB_HOST_DP, -1)
             p = GpuProblem(A, b, bits, 32, n_candidates=512)
             mv = p.make_levels(zipml.OPTIMAL, 0, n_candidates=512, want_mv=True)
             res.append((p.grid.cpu().numpy().copy(), p.levels.cpu().numpy().copy(), mv))
-        monkeypatch.delenv("ZIPML_HOST_DP", raising=False)
+        knobs(zipml.KNOB_HOST_DP, -1)
         assert np.array_equal(res[0][0], res[1][0])
         assert np.array_equal(res[0][1], res[1][1])
         # (the bin moments are accumulated with atomics, so two runs may differ in the last bits)
@@ -403,12 +403,12 @@ def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
     ("tomo4_b16384", synth.tomo, dict(n=32768, d=256), 16384, 0.5, 0.0),         # 4-bit, sparse rows
     ("lssvm_b16384", synth.lssvm, dict(n=16384, d=288, bits=8), 16384, 0.05, 0.05),
 ])
-def test_very_large_minibatches_on_sample_owners(name, factory, kw, batch, lr, l2, monkeypatch):
+def test_very_large_minibatches_on_sample_owners(name, factory, kw, batch, lr, l2, knobs):
     """Very large minibatches (by default from two tiles of 64 samples per compute unit on; here
     from 16,384 samples, the smallest the workspace provides for) go to workgroups that own samples
     instead of features: same estimator, same oracle."""
     say("sample owners", name)
-    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")
+    knobs(zipml.KNOB_ROWS_MIN_BATCH, 16384)
     w = factory(batch=batch, **kw)
     A, b = w.full()
     L = _levels_for(w, A)
@@ -687,10 +687,10 @@ def test_end_to_end_optimal_levels_steps_and_epochs(batch):
     ("lowbit_full_batch_rows", synth.lowbit, dict(n=32768, d=96, batch=32768), 0.2, 0.0),
     ("tomo4_b16384_rows", synth.tomo, dict(n=16384, d=1024, batch=16384), 0.5, 0.01),
 ])
-def test_symmetrised_estimator_matches_oracle(name, factory, kw, lr, l2, monkeypatch):
-    """g = 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)] (Supp. A.4)."""
+def test_symmetrised_estimator_matches_oracle(name, factory, kw, lr, l2, knobs):
+    """g = 1/2 mean_i [Q1 (Q2^T x - b) + Q2 (Q1^T x - b)] (Supp. B.2, footnote)."""
     say("averaged", name)
-    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")
+    knobs(zipml.KNOB_ROWS_MIN_BATCH, 16384)
     w = factory(**kw)
     A, b = w.full()
     L = _levels_for(w, A)
@@ -783,10 +783,10 @@ def test_least_squares_svm_epochs_match_oracle(name, kw):
     ("dense8_sample_owners", synth.dense8, dict(n=16384, d=288, batch=16384), 0.2),
 ])
 @pytest.mark.parametrize("kind,coef", [(zipml.PROX_L1, 0.05), (zipml.PROX_L2SQ, 0.5), (zipml.PROX_BOX, 0.04)])
-def test_proximal_step_matches_oracle(name, factory, kw, lr, kind, coef, monkeypatch):
+def test_proximal_step_matches_oracle(name, factory, kw, lr, kind, coef, knobs):
     """x <- prox_{lr R}(x - lr g) (Sec. 2) on every step loop, for the three regularisers."""
     say("prox", name, kind)
-    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")
+    knobs(zipml.KNOB_ROWS_MIN_BATCH, 16384)
     w = factory(**kw)
     A, b = w.full()
     L = _levels_for(w, A)
@@ -846,21 +846,21 @@ def test_proximal_step_refusals():
     ("dense8_replicas", synth.dense8, dict(n=8192, d=288, batch=4096)),      # chunks on two replicas
     ("dense8_sample_owners", synth.dense8, dict(n=16384, d=288, batch=16384)),
 ])
-def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, monkeypatch):
+def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, knobs):
     """Every device-wide wait is bounded.  With the bound forced to zero polls from the host, each
     wait gives up at once: the kernel must still run to its end and leave ZIPML_ETIMEOUT."""
     say("timeout path", name)
-    monkeypatch.setenv("ZIPML_ROWS_MIN_BATCH", "16384")    # (for the sample-owner case)
+    knobs(zipml.KNOB_ROWS_MIN_BATCH, 16384)    # (for the sample-owner case)
     w = factory(**kw)
     A, b = w.full()
     p = GpuProblem(A, b, w.bits, w.batch)
     p.set_levels(_levels_for(w, A))
     p.quantize(3, 0)
     x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
-    monkeypatch.setenv("ZIPML_SPIN_LIMIT", "0")
+    knobs(zipml.KNOB_SPIN_LIMIT, 0)
     zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 1e-3, p.ws)
     st = zipml.sgd_status(p.ws)
-    monkeypatch.delenv("ZIPML_SPIN_LIMIT")
+    knobs(zipml.KNOB_SPIN_LIMIT, -1)
     assert st == zipml.ETIMEOUT, zipml.strerror(st)
     # the next call on the same workspace is sound again
     x.zero_()
@@ -871,6 +871,25 @@ def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, monkeypatch)
 
 
 # ------------------------------------------------------------------ caller's stream
+def test_stream_probe_reads_and_copies_every_byte():
+    """The plain streaming kernel used for the read ceiling and the counter calibration: the XOR of
+    all 32-bit words it read, and the copy it wrote, against NumPy; sizes around its unrolling."""
+    rng = np.random.default_rng(0)
+    for nbytes in (16, 16 * 1023, 16 * 4096 * 5 + 48, 1 << 24):
+        a = rng.integers(0, 2 ** 32, nbytes // 4, dtype=np.uint32)
+        src = dev(a.view(np.int32))
+        sink = torch.zeros(4, dtype=torch.int32, device=DEV)
+        zipml.debug_stream(src, sink)
+        assert np.uint32(sink[0].item() & 0xFFFFFFFF) == np.bitwise_xor.reduce(a)
+        dst = torch.zeros_like(src)
+        sink.zero_()
+        zipml.debug_stream(src, sink, dst=dst)
+        assert torch.equal(src, dst) and np.uint32(sink[0].item() & 0xFFFFFFFF) == np.bitwise_xor.reduce(a)
+    with pytest.raises(zipml.ZipmlError) as e:
+        zipml.debug_stream(src, sink, nbytes=24)
+    assert e.value.code == zipml.EINVAL
+
+
 def test_everything_runs_on_the_callers_stream():
     """All device work is enqueued on the stream the caller passes: the same calls on a stream of
     the caller's own (default priority) give the same bits as on the default stream."""
