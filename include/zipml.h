@@ -256,11 +256,12 @@ int zipml_unpack_codes(void *stream, const void *packed_dev, int copy, int64_t n
  * the signed integer codes of Q3 / Q4, acc_dev[batch] the int32 dot products (integer mode only),
  * r_dev[batch] the residuals Q2(a_i)^T x - b_i, g_dev[d] the mean gradient before Q4.
  * Without flags the step runs in a launch of its own kind (the vector loop).  With
- * ZIPML_SGD_PRODUCTION it runs in the persistent launch and on the matrix-core step loop that
- * zipml_sgd_epoch uses for evenly spaced 2-, 4- or 8-bit levels and an fp32 model: only r_dev and
- * g_dev may be asked for then (ZIPML_EINVAL otherwise), and shapes or level tables that
- * zipml_sgd_epoch would not run on that loop return ZIPML_EUNSUPPORTED (for the level tables
- * through zipml_sgd_status, with x_dev left untouched). */
+ * ZIPML_SGD_PRODUCTION it runs in the persistent launch and on the step loop that zipml_sgd_epoch
+ * uses: the matrix-core loop for evenly spaced 2-, 4- or 8-bit levels and an fp32 model (only r_dev
+ * and g_dev may be asked for then, ZIPML_EINVAL otherwise), or the end-to-end loop for
+ * model_bits > 0 on more than one workgroup (all five outputs).  Shapes or level tables that
+ * zipml_sgd_epoch would not run on one of these loops return ZIPML_EUNSUPPORTED (for the level
+ * tables through zipml_sgd_status, with x_dev left untouched). */
 int zipml_debug_step(void *stream, const void *packed1_dev, const void *packed2_dev,
                      const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
                      float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d,

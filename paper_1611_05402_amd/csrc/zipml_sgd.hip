@@ -142,6 +142,8 @@ struct Lds {
     uint16_t *Gs;     // grid-index slice [CW][K]   (integer mode with a non-identity grid)
     float *xs, *ys, *los, *dls, *gs;   // model slice, delta*x, lo, delta, gradient slice  [CW]
     int *ms;          // model codes [CW]
+    int *tq;          // G[j][c] * m_j [CW][K]   (end-to-end production loop, at most 4-bit codes)
+    float *Lp;        // level slice with rows K + 1 apart (end-to-end production loop, lds_levels only)
     float *rs;        // residuals [Rlen]
     float *zl;        // local dot products [B+4]   (single workgroup only)
     uint32_t *zp;     // per-unit partial dot products [GQ][B]  (GQ > 1 only)
@@ -669,10 +671,17 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                 const int rgl = g_sl + k * nsl;
                 if (g_live && rgl < nrg) {
                     const float *rr = rs + rgl * 32;
-                    const float *Lj = a.lds_levels ? L.Ls + g_c * K : Lg + (size_t)g_c * K;
-                    if constexpr (kIsInt) part[k] = unit_grad_table_f64<BITS>(c1cur[k], Lj, rr);
-                    else if (MODE == kAffine) part[k] = unit_fma_codes<BITS>(c1cur[k], rr, 0.0f);
-                    else part[k] = unit_grad_table<BITS>(c1cur[k], Lj, rr, 0.0f);
+                    // (LDS and global tables in separate calls: one pointer for both would be generic)
+                    if constexpr (kIsInt) {
+                        if (a.lds_levels) part[k] = unit_grad_table_f64<BITS>(c1cur[k], L.Ls + g_c * K, rr);
+                        else part[k] = unit_grad_table_f64<BITS>(c1cur[k], Lg + (size_t)g_c * K, rr);
+                    } else if (MODE == kAffine) {
+                        part[k] = unit_fma_codes<BITS>(c1cur[k], rr, 0.0f);
+                    } else if (a.lds_levels) {
+                        part[k] = unit_grad_table<BITS>(c1cur[k], L.Ls + g_c * K, rr, 0.0f);
+                    } else {
+                        part[k] = unit_grad_table<BITS>(c1cur[k], Lg + (size_t)g_c * K, rr, 0.0f);
+                    }
                 }
             }
             // gpart[sample group][feature]
@@ -781,6 +790,10 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
 #endif
 }
 
+}  // namespace zipml
+#include "zipml_sgd_e2e.h"
+namespace zipml {
+
 // ---------------------------------------------------------------------------------------------
 // The epoch kernel: LDS carve, one-time set-up, then the step loop of the right mode.
 // ---------------------------------------------------------------------------------------------
@@ -818,6 +831,8 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     L.dls = (float *)carve(CW * 4);
     L.gs = (float *)carve(CW * 4);
     L.ms = (int *)carve(CW * 4);
+    L.tq = (int *)carve(INT && FAST && BITS <= 4 ? (size_t)CW * K * 4 : 0);
+    L.Lp = (float *)carve(INT && FAST && a.lds_levels ? (size_t)CW * (K + 1) * 4 : 0);
     L.rs = (float *)carve((size_t)Rlen * 4);
     L.zl = (float *)carve(a.W == 1 ? (size_t)(B + 4) * 4 : 0);
     L.zp = (uint32_t *)carve(a.GQ > 1 ? (size_t)a.GQ * B * 4 : 0);
@@ -831,6 +846,9 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     const float *Lg = a.levels + (size_t)j0 * K;
     if (a.lds_levels)
         for (int e = tid; e < CW * K; e += kThreads) L.Ls[e] = (j0 + e / K < a.d) ? Lg[e] : 0.0f;
+    if (INT && FAST && a.lds_levels)
+        for (int e = tid; e < CW * K; e += kThreads)
+            L.Lp[(e / K) * (K + 1) + e % K] = (j0 + e / K < a.d) ? Lg[e] : 0.0f;
     if (INT && !a.ident_grid)
         for (int e = tid; e < CW * K; e += kThreads)
             L.Gs[e] = (j0 + e / K < a.d) ? a.grid[(size_t)j0 * K + e] : (uint16_t)0;
@@ -872,10 +890,12 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
     }
 
     constexpr bool kMfmaBits = BITS == 2 || BITS == 4 || BITS == 8;
-    if ((a.chunks > 1 || a.avg || (FAST && (a.dbg_r || a.dbg_g))) &&
-        !(!INT && FAST && kMfmaBits && affine_all && a.mfma)) {
-        // minibatches taken in chunks, the symmetrised estimator and the intermediates of a
-        // production step exist on the matrix-core loop only
+    const bool on_mfma_loop = !INT && FAST && kMfmaBits && affine_all && a.mfma;
+    const bool on_e2e_loop = INT && FAST && a.W > 1;
+    if (((a.chunks > 1 || a.avg) && !on_mfma_loop) ||
+        (FAST && a.dbg_production && !on_mfma_loop && !on_e2e_loop)) {
+        // minibatches taken in chunks and the symmetrised estimator exist on the matrix-core loop
+        // only; the intermediates of a production step on that loop and on the end-to-end loop
         if (blockIdx.x == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
         return;
     }
@@ -910,9 +930,17 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
             sgd_steps<BITS, kTable, FAST, UPT>(a, L);
         }
     } else {
-        if (INT) sgd_steps<BITS, kInt, FAST, UPT>(a, L);
-        else if (affine) sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
-        else sgd_steps<BITS, kTable, FAST, UPT>(a, L);
+        if constexpr (INT && FAST) {
+            // (a single workgroup is launched on the other instantiation: the host sees to it, so
+            // that this one holds the end-to-end loop only and its registers)
+            if (a.W > 1) sgd_steps_e2e<BITS, UPT>(a, L);
+        } else if (INT) {
+            sgd_steps<BITS, kInt, FAST, UPT>(a, L);
+        } else if (affine) {
+            sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
+        } else {
+            sgd_steps<BITS, kTable, FAST, UPT>(a, L);
+        }
     }
 
     // ---- write the model slice back (the replicas hold identical copies: the first one does it)
@@ -933,12 +961,14 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
                                                       const float *__restrict__ x, int d, int K,
                                                       double *bound, int *even,
                                                       float *dl = nullptr, float *mid = nullptr,
-                                                      int nfeat = 0, float off = 0.0f)
+                                                      int nfeat = 0, float off = 0.0f,
+                                                      uint64_t *slots = nullptr, int nslots = 0)
 {
     __shared__ double sb[256], sl[256], sy[256], sm[256];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
     for (int e = i; e < words; e += gridDim.x * blockDim.x) acc[e] = 0ull;
+    for (int e = i; e < nslots; e += gridDim.x * blockDim.x) slots[e] = 0ull;   // norm exchange slots
     // per-feature constants of the sample-owner kernel: delta_j and lo_j + off * delta_j (zero for padding)
     if (dl)
         for (int j = i; j < nfeat; j += gridDim.x * blockDim.x) {
@@ -1035,6 +1065,8 @@ static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool int
     lds_levels = (size_t)CW * K * 4 <= 65536 ? 1 : 0;
     const size_t total = (lds_levels ? up16((size_t)CW * K * 4) : 0) +
                          (int_table ? up16((size_t)CW * K * 2) : 0) + 6 * up16((size_t)CW * 4) +
+                         (int_mode && bits <= 4 ? up16((size_t)CW * K * 4) : 0) +
+                         (int_mode && lds_levels ? up16((size_t)CW * (K + 1) * 4) : 0) +
                          up16((size_t)nrg * 32 * 4) +
                          (solo ? up16((size_t)(batch + 4) * 4) : 0) +
                          (GQ > 1 ? up16((size_t)GQ * batch * 4) : 0) +
@@ -1067,6 +1099,9 @@ static int make_plan(int64_t d32, int bits, int64_t batch, bool int_table, bool 
         if (W > cus || W > 512) continue;
         // units per thread; two code pairs take twice the registers
         if (batch * GQ > (int64_t)(pairs == 2 ? 2 : kMaxUpt) * kThreads) break;
+        // end-to-end mode: its production loop holds at most two units per thread and pass; take
+        // more, thinner workgroups instead where the device has them
+        if (!fp32_model && best && batch * GQ > 2 * (int64_t)kThreads) break;
         int ll = 0;
         // the matrix-core step loop: 2/4/8-bit codes, fp32 model, whole 64-sample blocks, more
         // than one workgroup, at most 8 feature tiles of 16 (whether the levels are evenly
@@ -1092,12 +1127,22 @@ template <int BITS, bool INT>
 static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
 {
     const bool debug = a.dbg_m || a.dbg_acc || a.dbg_gq || a.dbg_r || a.dbg_g;
-    const bool fast = !stepwise && (!debug || a.dbg_production);
+    // production instantiation: whole steps in one persistent launch (a single workgroup in the
+    // end-to-end mode runs the general loop, which keeps everything in LDS)
+    // (the end-to-end loop exists for one or two units per thread and pass: with four its
+    // registers do not fit, and the plan prefers twice the workgroups anyway; larger minibatches
+    // run the general loop)
+    const bool fast = !stepwise && (!debug || a.dbg_production) && !(INT && (a.W == 1 || p.upt > 2));
+    if (a.dbg_production && !fast) return ZIPML_EUNSUPPORTED;
     const void *kern = (const void *)k_sgd<BITS, INT, false, kMaxUpt>;
     if (fast) {
-        kern = p.upt == 1 ? (const void *)k_sgd<BITS, INT, true, 1>
-             : p.upt == 2 ? (const void *)k_sgd<BITS, INT, true, 2>
-                          : (const void *)k_sgd<BITS, INT, true, 4>;
+        if constexpr (INT) {
+            kern = p.upt == 1 ? (const void *)k_sgd<BITS, true, true, 1> : (const void *)k_sgd<BITS, true, true, 2>;
+        } else {
+            kern = p.upt == 1 ? (const void *)k_sgd<BITS, false, true, 1>
+                 : p.upt == 2 ? (const void *)k_sgd<BITS, false, true, 2>
+                              : (const void *)k_sgd<BITS, false, true, 4>;
+        }
         if constexpr (!INT && (BITS == 2 || BITS == 4 || BITS == 8)) {
             if (a.R > 1)
                 kern = p.upt == 1 ? (const void *)k_sgd<BITS, false, true, 1, true>
@@ -1115,7 +1160,9 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     double *bound = const_cast<double *>(a.bound);
     hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, a.status, a.sync,
                        a.acc, words, 1, a.levels, a.x, a.d, K, bound,
-                       a.mfma ? const_cast<int *>(a.even) : nullptr);
+                       a.mfma ? const_cast<int *>(a.even) : nullptr, (float *)nullptr, (float *)nullptr, 0, 0.0f,
+                       INT && !stepwise ? reinterpret_cast<uint64_t *>(a.nrm) : (uint64_t *)nullptr,
+                       INT && !stepwise ? 8 * kNormSlots : 0);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (!stepwise) {
         a.persistent = 1;
@@ -1223,9 +1270,12 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     if (flags & ZIPML_SGD_AVERAGED) return ZIPML_EUNSUPPORTED;
     const bool production = (flags & ZIPML_SGD_PRODUCTION) != 0;
     if (production) {
-        // the intermediates of the production launch: residuals and gradient of an fp32-model step
-        if ((flags & ZIPML_SGD_STEPWISE) || !(dbg_r || dbg_g) || dbg_m || dbg_acc || dbg_gq) return ZIPML_EINVAL;
-        if (model_bits > 0 || packed1s_dev || packed2s_dev) return ZIPML_EUNSUPPORTED;
+        // the intermediates of the production launch: residuals and gradient of an fp32-model
+        // step (matrix-core loop), all five outputs of an end-to-end step
+        if (flags & ZIPML_SGD_STEPWISE) return ZIPML_EINVAL;
+        if (!(dbg_r || dbg_g || dbg_m || dbg_acc || dbg_gq)) return ZIPML_EINVAL;
+        if (model_bits == 0 && (dbg_m || dbg_acc || dbg_gq)) return ZIPML_EINVAL;
+        if (packed1s_dev || packed2s_dev) return ZIPML_EUNSUPPORTED;
     }
     if (grad_bits > 0 && model_bits == 0) return ZIPML_EUNSUPPORTED;
     if (!(l2 >= 0.0f)) return ZIPML_EINVAL;
@@ -1264,7 +1314,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     int replicas = 1;
     int64_t forced = 0;
     if (knob(ZIPML_KNOB_CHUNK_SAMPLES) > 0) forced = knob(ZIPML_KNOB_CHUNK_SAMPLES);   // development override: chunk size
-    if (production && (rc != ZIPML_OK || !p.mfma)) return ZIPML_EUNSUPPORTED;
+    if (production && (rc != ZIPML_OK || (model_bits == 0 && !p.mfma) || (model_bits > 0 && p.W == 1)))
+        return ZIPML_EUNSUPPORTED;
     const bool split_ok = model_bits == 0 && !stepwise && !debug && batch % 64 == 0 &&
                           (bits == 2 || bits == 4 || bits == 8);
     if (split_ok && (rc == ZIPML_EUNSUPPORTED || (rc == ZIPML_OK && p.mfma && forced > 0 && forced < batch))) {

@@ -40,6 +40,7 @@ __host__ __device__ inline size_t mfma_lds_bytes(int GQ, int64_t batch, int pair
 }
 
 constexpr int kRefresh = 16;   // steps between exact refreshes of the magnitude bounds
+constexpr int64_t kWatchFirst = 32768;   // exchange words x workgroups from which a wave polls one word first
 
 // KB: 64-feature blocks per workgroup (1: GQ <= 2, 2: GQ == 4).
 // NC: 1 = the estimator of eq. (5), g = mean_i Q1(a_i) (Q2(a_i)^T x - b_i);
@@ -400,8 +401,23 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             const bool want_side = side_step && wave == 0;     // wave 0 also fetches the side words
             uint32_t spins = 0;
             if (tid < B || want_side) {
+                // A wave first watches ONE word (its first sample's: one request per round instead
+                // of 64) and fetches the words of all its samples once that one is complete; the
+                // workgroups contribute in the same order, so the others are then complete as
+                // well, or are a round later.  With hundreds of workgroups polling, the requests
+                // of the poll compete with the atomics they are waiting for.
+                // (Only then: for a few workgroups the extra round trip costs more than it saves.)
+                const int watch = wave * kWave < B ? wave * kWave : 0;
+                const bool watch_first = (int64_t)W * B >= kWatchFirst;
 #pragma unroll 1
                 for (;;) {
+                    if (watch_first && !dead && (int)(load_dev(acc + watch) >> kCountShift) != W) {
+                        if (++spins > a.spin_limit) {
+                            store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                            dead = true;
+                        }
+                        continue;
+                    }
 #pragma unroll
                     for (int cc = 0; cc < NC; ++cc)
 #pragma unroll

@@ -170,6 +170,8 @@ def test_end_to_end_full_width_steps_and_epochs():
     for step in (0, 15):
         say(f"  step {step}")
         e2e_step_check(p, oracle, c1, c2, Lo, Go, glo, gstep, gmax, b, x0, 0.05, 8, 8, 9, 0, step)
+        e2e_step_check(p, oracle, c1, c2, Lo, Go, glo, gstep, gmax, b, x0, 0.05, 8, 8, 9, 0, step,
+                       zipml.SGD_PRODUCTION)
     x_ref = np.zeros(w.d, np.float32)
     xd = torch.zeros(w.d, dtype=torch.float32, device=DEV)
     for ep in range(2):

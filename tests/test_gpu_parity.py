@@ -604,6 +604,12 @@ E2E_CASES = [
     ("tiny_u8_b256", dict(n=2048, d=288, batch=256, bits=8), 8, 8),
     ("tiny_u2_ragged", dict(n=512, d=70, batch=32, bits=2), 4, 6),
     ("model_only", dict(n=1024, d=96, batch=64, bits=4), 0, 8),
+    # more than 256 features: several workgroups (the production launch takes the end-to-end loop)
+    ("wide_u4_ragged", dict(n=2048, d=300, batch=64, bits=4), 8, 8),
+    ("wide_u2", dict(n=1024, d=520, batch=32, bits=2), 4, 6),
+    ("wide_model_only", dict(n=1024, d=352, batch=128, bits=4), 0, 8),
+    ("wide_u4_b16", dict(n=512, d=288, batch=16, bits=4), 8, 8),
+    ("wide_u3_b512", dict(n=2048, d=1100, batch=512, bits=3), 8, 8),
 ]
 
 
@@ -624,10 +630,16 @@ def e2e_epochs_check(p, c1, c2, L, G, glo, gstep, gmax, b, bits, batch, x0, lr, 
     return xd, x_ref
 
 
-@pytest.mark.parametrize("flags", [0, zipml.SGD_STEPWISE], ids=["persistent", "stepwise"])
+@pytest.mark.parametrize("flags", [0, zipml.SGD_STEPWISE, zipml.SGD_PRODUCTION],
+                         ids=["persistent", "stepwise", "production"])
 @pytest.mark.parametrize("name,kw,gb,mb", E2E_CASES, ids=[c[0] for c in E2E_CASES])
 def test_end_to_end_uniform_grid_steps_and_epochs(name, kw, gb, mb, flags):
+    """flags = 0: single steps in the debug launch, epochs in the production launch; stepwise:
+    both in one launch per segment; production: single steps in the production launch as well
+    (shapes of more than 256 features, which several workgroups share)."""
     say("e2e", name, "flags", flags)
+    if flags == zipml.SGD_PRODUCTION and kw["d"] <= 256:
+        pytest.skip("one workgroup: no production step loop of its own")
     w = synth.tiny(**kw)
     A, b = w.full()
     L = uniform_levels_np(w.d, w.bits, -1.0, 1.0)
@@ -642,21 +654,23 @@ def test_end_to_end_uniform_grid_steps_and_epochs(name, kw, gb, mb, flags):
     # single steps from a given model: every intermediate
     for step in (0, 3):
         e2e_step_check(p, oracle, c1, c2, L, G, glo, gstep, gmax, b, x0, 0.05, gb, mb, 11, 2, step, flags)
+    eflags = flags & zipml.SGD_STEPWISE
     xd, _ = e2e_epochs_check(p, c1, c2, L, G, glo, gstep, gmax, b, w.bits, w.batch, x0, 0.05, gb, mb, 11, 2,
-                             flags)
+                             eflags)
     # and the run is reproducible
     xd2 = dev(x0)
     for ep in range(2):
-        p.epoch(xd2, 0.05, seed=11, epoch=ep, flags=flags, grad_bits=gb, model_bits=mb, grid_lo=glo,
+        p.epoch(xd2, 0.05, seed=11, epoch=ep, flags=eflags, grad_bits=gb, model_bits=mb, grid_lo=glo,
                 grid_step=gstep, grid_max=gmax)
     assert torch.equal(xd, xd2)
 
 
+@pytest.mark.parametrize("d", [160, 416])
 @pytest.mark.parametrize("batch", [64, 96, 512])
-def test_end_to_end_optimal_levels_steps_and_epochs(batch):
-    say("e2e optimal 3-bit levels, 8-bit model and gradient, batch", batch)
+def test_end_to_end_optimal_levels_steps_and_epochs(batch, d):
+    say("e2e optimal 3-bit levels, 8-bit model and gradient, batch", batch, "d", d)
     M = 256
-    w = synth.e2e(n=batch * 24, d=160, batch=batch, n_candidates=M)
+    w = synth.e2e(n=batch * 24, d=d, batch=batch, n_candidates=M)
     A, b = w.full()
     lo, hi = np.zeros(w.d, np.float32), np.ones(w.d, np.float32)
     L, G, _ = oracle.levels_optimal(oracle.hist_moments(A, lo, hi, M), lo, hi, 3)
@@ -670,6 +684,9 @@ def test_end_to_end_optimal_levels_steps_and_epochs(batch):
     x0 = (rng.standard_normal(w.d) * 0.1).astype(np.float32)
     for step in (0, 7, 23):
         e2e_step_check(p, oracle, c1, c2, L, G, glo, gstep, gmax, b, x0, 0.3, 8, 8, 4, 0, step)
+        if d > 256:
+            e2e_step_check(p, oracle, c1, c2, L, G, glo, gstep, gmax, b, x0, 0.3, 8, 8, 4, 0, step,
+                           zipml.SGD_PRODUCTION)
     _, x_ref = e2e_epochs_check(p, c1, c2, L, G, glo, gstep, gmax, b, 3, batch, np.zeros(w.d, np.float32),
                                 0.3, 8, 8, 4, 2)
     assert np.linalg.norm(x_ref) > 0
