@@ -292,7 +292,11 @@ int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t 
 #define ZIPML_KNOB_SPIN_LIMIT        7  /* polls before a device-wide wait gives up (0: at once)        */
 #define ZIPML_KNOB_HOST_DP           8  /* 1: the dynamic program of zipml_levels runs on the host     */
 #define ZIPML_KNOB_HIST_FEATURES     9  /* features per workgroup of the bin-moment kernel              */
-#define ZIPML_KNOB_COUNT            10
+#define ZIPML_KNOB_STORE_EXCHANGE_MIN 10 /* smallest (workgroups x samples of one exchange) from which
+                                            the sums travel through tagged stores and reducer
+                                            workgroups instead of atomics (default 32768; 0: wherever
+                                            the loop can; a huge value: never)                     */
+#define ZIPML_KNOB_COUNT            11
 int zipml_debug_set(int knob, int64_t value);
 
 #ifdef __cplusplus

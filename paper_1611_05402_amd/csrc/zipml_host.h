@@ -74,6 +74,24 @@ struct Workspace {
         if (batch < kRowsMinBatch || batch % 64 != 0) return 0;
         return ((size_t)(kMaxRowsWgs + 2) * (size_t)round_up(d, 64) + kMaxRowsWgs + 64) * 4;
     }
+    // Exchange through tagged stores (zipml_sgd_mfma.h): two buffers of one row of exchange words
+    // per workgroup (at most 256, and no more than there are groups of 32 features) plus one row
+    // of results; a row holds the sums of both code pairs of one exchange (at most 2048 samples)
+    // and two side words, rounded up to pieces of eight.  Behind everything else, 256-byte aligned.
+    static size_t xchg_row_words(int64_t batch)
+    {
+        return (size_t)round_up(2 * (batch < 2048 ? batch : 2048) + 2, 8);
+    }
+    static size_t xchg_bytes(int64_t d, int64_t batch)
+    {
+        const int64_t d32 = round_up(d, 32) / 32;
+        const size_t wmax = (size_t)(d32 < 256 ? d32 : 256);
+        return 2 * (wmax + 1) * xchg_row_words(batch) * 8;
+    }
+    static size_t xchg_offset(int64_t d, int64_t batch)
+    {
+        return (size_t)round_up((int64_t)(sgd_bytes(batch) + (size_t)round_up(d, 64) * 4 + rows_bytes(d, batch)), 256);
+    }
 };
 
 // Development knobs (zipml_debug_set): process-wide overrides of choices the library otherwise

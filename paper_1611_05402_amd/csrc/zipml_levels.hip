@@ -453,7 +453,7 @@ extern "C" size_t zipml_workspace_bytes(int64_t n, int64_t d, int bits, int64_t 
                                         int n_candidates)
 {
     if (n <= 0 || d <= 0 || !valid_bits(bits) || batch <= 0 || n_candidates < 0) return 0;
-    size_t sgd = Workspace::sgd_bytes(batch) + (size_t)round_up(d, 64) * 4 + Workspace::rows_bytes(d, batch);
+    size_t sgd = Workspace::xchg_offset(d, batch) + Workspace::xchg_bytes(d, batch);
     size_t lev = levels_workspace_bytes(d, n_candidates);
     size_t loss = (2048 + 1) * sizeof(double) + 1024;   // partial sums, result, flags of the level check
     size_t need = std::max(sgd, std::max(lev, loss));

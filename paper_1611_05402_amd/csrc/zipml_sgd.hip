@@ -115,6 +115,10 @@ struct SgdArgs {
     uint64_t *gx;          // [2][R][W * 32 GQ] tagged words: gradient exchange between replicas
     uint32_t spin_limit;   // polls before a wait gives up (ZIPML_ETIMEOUT); the kernel still runs to its end
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
+    int xstore;            // 1: the matrix-core loop exchanges its sums through tagged stores
+    int xrow;              // words per row of xpart / xres
+    uint64_t *xpart;       // [2][W][xrow] tagged partial sums, one row per workgroup
+    uint64_t *xres;        // [2][xrow] tagged sums
     // debug outputs (may be null)
     int32_t *dbg_m, *dbg_acc, *dbg_gq;
     float *dbg_r, *dbg_g;
@@ -962,13 +966,15 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
                                                       double *bound, int *even,
                                                       float *dl = nullptr, float *mid = nullptr,
                                                       int nfeat = 0, float off = 0.0f,
-                                                      uint64_t *slots = nullptr, int nslots = 0)
+                                                      uint64_t *slots = nullptr, int nslots = 0,
+                                                      uint64_t *tagged = nullptr, int64_t ntagged = 0)
 {
     __shared__ double sb[256], sl[256], sy[256], sm[256];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
     for (int e = i; e < words; e += gridDim.x * blockDim.x) acc[e] = 0ull;
     for (int e = i; e < nslots; e += gridDim.x * blockDim.x) slots[e] = 0ull;   // norm exchange slots
+    for (int64_t e = i; e < ntagged; e += gridDim.x * blockDim.x) tagged[e] = 0ull;   // tagged exchange words
     // per-feature constants of the sample-owner kernel: delta_j and lo_j + off * delta_j (zero for padding)
     if (dl)
         for (int j = i; j < nfeat; j += gridDim.x * blockDim.x) {
@@ -1055,6 +1061,8 @@ static int device_limits(int &cus, int &lds)
 }
 
 static size_t up16(size_t v) { return (v + 15) & ~(size_t)15; }
+// the exchange words of one chunk (sums of `pairs` code pairs, two side words) fit a row
+static bool NCwords_ok(int pairs, int64_t micro, int xrow) { return (int64_t)pairs * micro + 2 <= xrow; }
 
 // LDS needed for GQ feature groups per workgroup; 0 if it does not fit.
 static size_t plan_lds(int GQ, int bits, int64_t batch, bool int_table, bool int_mode, bool solo,
@@ -1162,7 +1170,9 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
                        a.acc, words, 1, a.levels, a.x, a.d, K, bound,
                        a.mfma ? const_cast<int *>(a.even) : nullptr, (float *)nullptr, (float *)nullptr, 0, 0.0f,
                        INT && !stepwise ? reinterpret_cast<uint64_t *>(a.nrm) : (uint64_t *)nullptr,
-                       INT && !stepwise ? 8 * kNormSlots : 0);
+                       INT && !stepwise ? 8 * kNormSlots : 0,
+                       a.xstore ? a.xpart : (uint64_t *)nullptr,
+                       a.xstore ? (int64_t)2 * (a.W + 1) * a.xrow : (int64_t)0);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (!stepwise) {
         a.persistent = 1;
@@ -1467,6 +1477,19 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
             return ZIPML_EWORKSPACE;
     }
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
+    // Exchange through tagged stores: the matrix-core loop of one launch without replicas, all
+    // eight waves at work, and enough (workgroups x samples) for the atomics to be what a step
+    // waits for.
+    {
+        long long xmin = knob(ZIPML_KNOB_STORE_EXCHANGE_MIN);
+        if (xmin < 0) xmin = 32768;
+        const bool all_waves = !(p.upt == 1 && micro <= 256 && p.GQ <= 2);
+        a.xstore = (a.mfma && replicas == 1 && all_waves && p.W > 1 && (long long)p.W * micro >= xmin) ? 1 : 0;
+        a.xrow = (int)Workspace::xchg_row_words(batch);
+        a.xpart = (uint64_t *)(ws + Workspace::xchg_offset(d, batch));
+        a.xres = a.xpart + (size_t)2 * p.W * a.xrow;
+        if (a.xstore && (p.W > 256 || NCwords_ok(avg ? 2 : 1, micro, a.xrow) == false)) a.xstore = 0;
+    }
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
     switch (bits) {
         case 1: return launch_sgd_mode<1>(s, a, p, stepwise);

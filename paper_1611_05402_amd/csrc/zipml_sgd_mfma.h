@@ -40,6 +40,35 @@ __host__ __device__ inline size_t mfma_lds_bytes(int GQ, int64_t batch, int pair
 }
 
 constexpr int kRefresh = 16;   // steps between exact refreshes of the magnitude bounds
+
+// Exchange through tagged stores (a.xstore), for launches in which the number of exchange words
+// times the number of workgroups is large.  One atomic per (workgroup, sample) is what the
+// device-wide exchange costs then: the memory side completes some 15-25 atomics per ns, and the
+// tomography shape has 65,536 of them per step.  Plain stores and loads are far cheaper, so the
+// sums are formed in two trips instead:
+//   1. a workgroup STORES its partial sums, one 64-bit word per sample in its own row
+//      part[u & 1][workgroup][word]; a word carries a 16-bit tag of the step above the 48-bit
+//      fixed-point value, so one store delivers value and arrival (no counts, nothing to clear
+//      between steps: a stale word has another tag);
+//   2. the words are dealt out in pieces of eight (64 bytes) to "reducer" workgroups; a reducer
+//      polls its piece in every row, adds the W values (integers: exact, any order) and stores the
+//      sums, tagged the same way, to res[u & 1][word];
+//   3. every thread polls the result words of its own samples.
+// Two buffers alternate.  A workgroup writes row words of step u only after it has finished step
+// u-1, for which it needed results that every reducer published after its reads of step u-2; a
+// reducer writes results of step u after it has seen every workgroup's words of step u, which
+// each wrote after reading the results of step u-2.  So no word is overwritten while someone may
+// still read it.  The preparation launch clears both arrays (a stale tag of an earlier call could
+// otherwise match).
+constexpr int kPiece = 8;                                  // exchange words per reducer piece
+__device__ __forceinline__ uint64_t tag_word(uint32_t tag, long long v)
+{
+    return ((uint64_t)tag << 48) | ((uint64_t)v & 0x0000FFFFFFFFFFFFull);
+}
+__device__ __forceinline__ long long tagged_value(uint64_t word)
+{
+    return (long long)(word << 16) >> 16;                  // sign-extends the 48-bit field
+}
 constexpr int64_t kWatchFirst = 32768;   // exchange words x workgroups from which a wave polls one word first
 
 // KB: 64-feature blocks per workgroup (1: GQ <= 2, 2: GQ == 4).
@@ -90,6 +119,9 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const int C = a.chunks / R;
     const int64_t u_begin = a.step0 * C, u_end = (a.step0 + a.nsteps) * C;
     const int nwords = NC * B + 2;                      // exchange words of a chunk: sums, 2 side words
+    const bool xstore = !REP && a.xstore != 0 && nw == kWaves;   // exchange through tagged stores (see above; all waves take part)
+    const int xrow = a.xrow;                            // words per row of part[][] and of res[] (multiple of kPiece)
+    const int npieces = (nwords + kPiece - 1) / kPiece;
     uint64_t *const acc_base = a.acc + (size_t)rep * Workspace::kAccBuffers * a.acc_words;
     const uint32_t *const p2base[2] = {a.p2, a.p2s}, *const p1base[2] = {a.p1, a.p1s};
 
@@ -119,6 +151,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
                 vm_wait_all();
             }
+            if (xstore)
+                for (int pc = w; pc < npieces; pc += W) lds_barrier();   // (the reducer's, see below)
             lds_barrier();
             lds_barrier();
             if (KSS > 1) lds_barrier();
@@ -292,6 +326,10 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     for (int64_t u = u_begin; u < u_end; ++u) {
         const bool first = chunk == 0, last = chunk == C - 1;
         uint64_t *const acc = acc_base + (size_t)(u & 3) * a.acc_words;
+        const uint32_t xtag = ((uint32_t)(u + 1) & 0x7FFFu) | 0x8000u;
+        uint64_t *const xpart = a.xpart + (size_t)(u & 1) * ((size_t)W * xrow);
+        uint64_t *const xmine = xpart + (size_t)w * xrow;
+        uint64_t *const xres = a.xres + (size_t)(u & 1) * xrow;
         const bool side_step = first && (t % kRefresh) == 0;   // bounds travel with this exchange
         const bool side_next = last && ((t + 1) % kRefresh) == 0;
         ZIPML_TICK(7);
@@ -340,8 +378,10 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                             }
                         }
                         const int tile = wave + nw * (4 * gi + q4);
-                        if (tile < ntile)
-                            add_dev(acc + cc * B + 16 * tile + n16, pack_int(combine_digits(c) + kconst));
+                        if (tile < ntile) {
+                            if (xstore) store_dev(xmine + cc * B + 16 * tile + n16, tag_word(xtag, combine_digits(c) + kconst));
+                            else add_dev(acc + cc * B + 16 * tile + n16, pack_int(combine_digits(c) + kconst));
+                        }
                     }
                 }
             }
@@ -354,13 +394,14 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     mx = ymx[f] > mx ? ymx[f] : mx;
                 }
                 const long long v = lane == 0 ? __double2ll_ru(ldexp((double)bw, ky)) + 1 : (long long)mx;
-                add_dev(acc + NC * B + lane, pack_int(v));
+                if (xstore) store_dev(xmine + NC * B + lane, tag_word(xtag, v));
+                else add_dev(acc + NC * B + lane, pack_int(v));
             }
         }
         // The last wave of workgroup 0 clears the exchange words of step t+2 (see zipml_sgd.hip
         // for why that is the right moment and why no wait is needed here); with idle waves
         // around, one of them does it instead.
-        if (nw == kWaves && w == 0 && wave == kWaves - 1) {
+        if (!xstore && nw == kWaves && w == 0 && wave == kWaves - 1) {
             uint64_t *nxt = acc_base + (size_t)((u + 2) & 3) * a.acc_words;
             for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
             if (!(tid < B)) vm_wait_all();
@@ -393,10 +434,101 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         if (u + 1 < u_end) load_labels(u + 1, bfut);
         ZIPML_TICK(1);
 
+        // ============ tagged-store exchange, second trip: this workgroup's pieces of the sums
+        if (xstore) {
+            int turn = 0;
+            for (int pc = w; pc < npieces; pc += W, turn ^= 1) {
+                long long *const red64 = reinterpret_cast<long long *>(L.red) + turn * (kWaves * kPiece);   // [kWaves][kPiece], two in turn
+                const int sidx = pc * kPiece + (tid & (kPiece - 1));          // this thread's word
+                const bool valid = sidx < NC * B || (side_step && sidx < nwords);
+                long long sum = 0;
+                if (valid) {
+                    uint32_t spins = 0;
+                    for (int row = tid / kPiece; row < W; row += kThreads / kPiece) {
+                        const uint64_t *src = xpart + (size_t)row * xrow + sidx;
+                        uint64_t v = load_dev(src);
+#pragma unroll 1
+                        while ((uint32_t)(v >> 48) != xtag && !dead) {
+                            if (++spins > a.spin_limit) {
+                                store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                                dead = true;
+                            }
+                            v = load_dev(src);
+                        }
+                        sum += tagged_value(v);
+                    }
+                }
+                // lanes l, l + 8, ... of a wave hold the same word: add them, then the waves in LDS
+                sum += __shfl_xor(sum, 8, kWave);
+                sum += __shfl_xor(sum, 16, kWave);
+                sum += __shfl_xor(sum, 32, kWave);
+                if (lane < kPiece) red64[wave * kPiece + lane] = sum;
+                lds_barrier();
+                if (tid < kPiece) {
+                    long long tot = 0;
+#pragma unroll
+                    for (int q = 0; q < kWaves; ++q) tot += red64[q * kPiece + tid];
+                    if (valid) store_dev(xres + sidx, tag_word(xtag, tot));
+                }
+            }
+        }
+
+        ZIPML_TICK(3);
         // ============ residuals: poll the sums of this thread's samples
         float r[NC][kBpt];
         float rmax = 0.0f, rsum = 0.0f;
-        {
+        if (xstore) {
+            uint64_t raw[NC][kBpt], rawx = 0;
+            const bool want_side = side_step && wave == 0;
+            uint32_t spins = 0;
+            if (tid < B || want_side) {
+                const int watch = wave * kWave < B ? wave * kWave : 0;
+#pragma unroll 1
+                for (;;) {
+                    // (one word first, as below)
+                    if (!dead && (uint32_t)(load_dev(xres + watch) >> 48) != xtag) {
+                        if (++spins > a.spin_limit) {
+                            store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                            dead = true;
+                        }
+                        continue;
+                    }
+#pragma unroll
+                    for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+                        for (int q = 0; q < kBpt; ++q) {
+                            const int i = tid + q * nthr;
+                            raw[cc][q] = load_dev(xres + cc * B + (i < B ? i : B - 1));
+                        }
+                    if (want_side) rawx = load_dev(xres + NC * B + (lane & 1));
+                    bool all = !want_side || (uint32_t)(rawx >> 48) == xtag;
+#pragma unroll
+                    for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+                        for (int q = 0; q < kBpt; ++q) all = all && (uint32_t)(raw[cc][q] >> 48) == xtag;
+                    if (all || dead) break;
+                    if (++spins > a.spin_limit) {
+                        store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                        dead = true;
+                    }
+                }
+            }
+            if (want_side && lane < 2) side[lane] = fixed_to_float(tagged_value(rawx), ky) * 1.00001f;
+#pragma unroll
+            for (int q = 0; q < kBpt; ++q) {
+                const int i = tid + q * nthr;
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) {
+                    r[cc][q] = 0.0f;
+                    if (i < B) {
+                        r[cc][q] = fixed_to_float(tagged_value(raw[cc][q]), ky) - bnext[q];
+                        rmax = fmaxf(rmax, fabsf(r[cc][q]));
+                        rsum += r[cc][q];
+                    }
+                }
+                bnext[q] = bfut[q];
+            }
+        } else {
             uint64_t raw[NC][kBpt], rawx = 0;
             const bool want_side = side_step && wave == 0;     // wave 0 also fetches the side words
             uint32_t spins = 0;

@@ -482,6 +482,48 @@ def test_large_minibatches_taken_in_chunks(name, factory, kw, batch, lr):
     assert torch.equal(x, x0)
 
 
+@pytest.mark.parametrize("name,factory,kw,lr,avg", [
+    ("dense8_wide_b512", synth.dense8, dict(n=4096, d=1100, batch=512), 1e-2, False),
+    ("lowbit_b1024", synth.lowbit, dict(n=8192, d=640, batch=1024), 0.05, False),
+    ("tomo4_b512", synth.tomo, dict(n=4096, d=1024, batch=512), 0.05, False),
+    ("dense4_chunks_b4096", synth.dense8, dict(n=8192, d=1100, bits=4, batch=4096), 0.05, False),
+    ("dense8_wide_b512_avg", synth.dense8, dict(n=4096, d=1100, batch=512), 1e-2, True),
+])
+def test_exchange_through_tagged_stores(name, factory, kw, lr, avg, knobs):
+    """The matrix-core loop with the sums of a step exchanged through tagged stores and reducer
+    workgroups (forced here on small shapes; by default only hundreds of workgroups x samples take
+    it): the sums are exact integers either way, so the epochs must equal those of the exchange
+    through atomics bit for bit, and the oracle's within the tolerance."""
+    say("tagged-store exchange", name)
+    w = factory(**kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L)
+    p.quantize(8, 0)
+    p1s = p2s = None
+    if avg:
+        p1s, p2s = torch.zeros_like(p.p1), torch.zeros_like(p.p2)
+        zipml.quantize_swapped(p.A, w.n, w.d, w.d, 0, w.n, p.levels, w.bits, 8, 0, p1s, p2s)
+    c1, c2 = oracle.quantize(A, L, w.bits, 8, 0)
+    res = []
+    for xmin in (1 << 40, 0):
+        knobs(zipml.KNOB_STORE_EXCHANGE_MIN, xmin)
+        x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        for ep in range(2):
+            if avg:
+                zipml.sgd_epoch_avg(p.p1, p.p2, p1s, p2s, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, lr, p.ws)
+                assert zipml.sgd_status(p.ws) == 0
+            else:
+                p.epoch(x, lr)
+        res.append(x.cpu().numpy())
+    x_ref = np.zeros(w.d, np.float32)
+    for ep in range(2):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, lr, symmetric=avg)
+    assert np.array_equal(res[0].view(np.uint32), res[1].view(np.uint32))
+    assert rel_l2(res[1], x_ref) <= TOL and max_abs_ok(res[1], x_ref, TOL)
+
+
 def test_sgd_fp32_one_feature_not_evenly_spaced():
     """Evenly spaced levels take the matrix-core loop; a single feature with other levels must
     send every workgroup down the table path (workgroups on different loops would scale their
@@ -862,12 +904,16 @@ def test_proximal_step_refusals():
     ("b5_wide", synth.tiny, dict(n=2048, d=1056, batch=64, bits=5)),         # vector loop, 33 groups
     ("dense8_replicas", synth.dense8, dict(n=8192, d=288, batch=4096)),      # chunks on two replicas
     ("dense8_sample_owners", synth.dense8, dict(n=16384, d=288, batch=16384)),
+    ("dense8_tagged_stores", synth.dense8, dict(n=2048, d=1100, batch=512)),
+    ("e2e_like_wide", synth.dense8, dict(n=2048, d=1100, bits=4, batch=512)),
 ])
 def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, knobs):
     """Every device-wide wait is bounded.  With the bound forced to zero polls from the host, each
     wait gives up at once: the kernel must still run to its end and leave ZIPML_ETIMEOUT."""
     say("timeout path", name)
     knobs(zipml.KNOB_ROWS_MIN_BATCH, 16384)    # (for the sample-owner case)
+    if name == "dense8_tagged_stores":
+        knobs(zipml.KNOB_STORE_EXCHANGE_MIN, 0)
     w = factory(**kw)
     A, b = w.full()
     p = GpuProblem(A, b, w.bits, w.batch)
@@ -875,7 +921,14 @@ def test_wait_that_gives_up_is_reported_not_hung(name, factory, kw, knobs):
     p.quantize(3, 0)
     x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
     knobs(zipml.KNOB_SPIN_LIMIT, 0)
-    zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 1e-3, p.ws)
+    if name == "e2e_like_wide":
+        # the end-to-end production loop: its three exchanges give up as well
+        K = 1 << w.bits
+        p.grid.copy_(dev(np.tile(np.arange(K, dtype=np.int16), (w.d, 1))))
+        zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 1e-3, p.ws, grid_idx=p.grid,
+                        grid_lo=-1.0, grid_step=2.0 / (K - 1), grid_max=K - 1, grad_bits=8, model_bits=8)
+    else:
+        zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 1e-3, p.ws)
     st = zipml.sgd_status(p.ws)
     knobs(zipml.KNOB_SPIN_LIMIT, -1)
     assert st == zipml.ETIMEOUT, zipml.strerror(st)
