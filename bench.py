@@ -42,6 +42,10 @@ def parse():
                     help="all: the four full-size workloads, headline = tomo; else only that one")
     ap.add_argument("--batch", type=int, default=0, help="override the minibatch size")
     ap.add_argument("--rows", type=int, default=0, help="override the number of samples (development)")
+    ap.add_argument("--dim", type=int, default=0, help="override the number of features (development)")
+    ap.add_argument("--bits", type=int, default=0, help="override the code width (development)")
+    ap.add_argument("--no-matrix-cores", action="store_true",
+                    help="keep evenly spaced levels on the vector-ALU step loop (A/B measurement)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the batch sweep and the timings of the other entry points")
@@ -78,7 +82,12 @@ def prepare(name, args, torch, zipml, synth, dev):
     with the library.  The fp32 rows are kept only where a later call needs them."""
     factory = synth.WORKLOADS[name]
     n_full = args.rows or {"tiny": 4096, "dense8": 65536, "lowbit": 1048576, "tomo": 262144, "e2e": 524288}[name]
-    w = synth.light(factory, n_full)
+    kw = {}
+    if args.dim:
+        kw["d"] = args.dim
+    if args.bits:
+        kw["bits"] = args.bits
+    w = synth.light(factory, n_full, **kw)
     if args.batch:
         w.batch = args.batch
     n, d, bits, B = w.n, w.d, w.bits, w.batch
@@ -261,6 +270,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     zipml.lib()   # fails loudly if the HIP library is missing
+    if args.no_matrix_cores:
+        zipml.debug_set(zipml.KNOB_NO_MATRIX_CORES, 1)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     names = ALL if args.workload == "all" else [args.workload]

@@ -908,12 +908,12 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
             if (affine_all && a.mfma) {     // (anything else has been refused above: replicas imply chunks)
                 if (a.avg) {
                     if constexpr (UPT <= 2) {
-                        if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2, true>(a, L, L.mf);
-                        else sgd_steps_mfma<BITS, UPT, 2, 2, true>(a, L, L.mf);
+                        if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2, true, 0>(a, L, L.mf);
+                        else sgd_steps_mfma<BITS, UPT, 2, 2, true, 0>(a, L, L.mf);
                     }
                 } else {
-                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, true>(a, L, L.mf);
-                    else sgd_steps_mfma<BITS, UPT, 2, 1, true>(a, L, L.mf);
+                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, true, 0>(a, L, L.mf);
+                    else sgd_steps_mfma<BITS, UPT, 2, 1, true, 0>(a, L, L.mf);
                 }
             }
         }
@@ -921,12 +921,22 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         if (affine_all && a.mfma) {
             if (a.avg) {
                 if constexpr (UPT <= 2) {      // the plan keeps the symmetrised estimator to these
-                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2, false>(a, L, L.mf);
-                    else sgd_steps_mfma<BITS, UPT, 2, 2, false>(a, L, L.mf);
+                    if (a.GQ <= 2) {
+                        if (a.xstore) sgd_steps_mfma<BITS, UPT, 1, 2, false, 1>(a, L, L.mf);
+                        else sgd_steps_mfma<BITS, UPT, 1, 2, false, 0>(a, L, L.mf);
+                    } else {
+                        if (a.xstore) sgd_steps_mfma<BITS, UPT, 2, 2, false, 1>(a, L, L.mf);
+                        else sgd_steps_mfma<BITS, UPT, 2, 2, false, 0>(a, L, L.mf);
+                    }
                 }
+            } else if (a.GQ <= 2) {
+                if (a.dbg_production) sgd_steps_mfma<BITS, UPT, 1, 1, false, 2>(a, L, L.mf);
+                else if (a.xstore) sgd_steps_mfma<BITS, UPT, 1, 1, false, 1>(a, L, L.mf);
+                else sgd_steps_mfma<BITS, UPT, 1, 1, false, 0>(a, L, L.mf);
             } else {
-                if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, false>(a, L, L.mf);
-                else sgd_steps_mfma<BITS, UPT, 2, 1, false>(a, L, L.mf);
+                if (a.dbg_production) sgd_steps_mfma<BITS, UPT, 2, 1, false, 2>(a, L, L.mf);
+                else if (a.xstore) sgd_steps_mfma<BITS, UPT, 2, 1, false, 1>(a, L, L.mf);
+                else sgd_steps_mfma<BITS, UPT, 2, 1, false, 0>(a, L, L.mf);
             }
         } else if (affine) {
             sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
@@ -1484,7 +1494,8 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
         long long xmin = knob(ZIPML_KNOB_STORE_EXCHANGE_MIN);
         if (xmin < 0) xmin = 32768;
         const bool all_waves = !(p.upt == 1 && micro <= 256 && p.GQ <= 2);
-        a.xstore = (a.mfma && replicas == 1 && all_waves && p.W > 1 && (long long)p.W * micro >= xmin) ? 1 : 0;
+        a.xstore = (a.mfma && replicas == 1 && all_waves && p.W > 1 && !production &&
+                    (long long)p.W * micro >= xmin) ? 1 : 0;
         a.xrow = (int)Workspace::xchg_row_words(batch);
         a.xpart = (uint64_t *)(ws + Workspace::xchg_offset(d, batch));
         a.xres = a.xpart + (size_t)2 * p.W * a.xrow;

@@ -77,9 +77,14 @@ constexpr int64_t kWatchFirst = 32768;   // exchange words x workgroups from whi
 //     second pair of packed arrays holds copy 1 sample-major and copy 2 feature-major, both
 //     pairs go through the same two passes at the same model, with one exchange for both.
 // REP: the chunks of a minibatch are shared out over replicas of the workgroups (a.R > 1).
-template <int BITS, int UPT, int KB, int NC, bool REP>
+// XM: 0 = the plain loop (exchange through atomics), 1 = exchange through tagged stores,
+//     2 = the plain loop that also writes the residuals and the gradient of its steps to the
+//     debug outputs (zipml_debug_step with ZIPML_SGD_PRODUCTION).  Instantiations of their own, so
+//     that neither costs the plain loop registers.
+template <int BITS, int UPT, int KB, int NC, bool REP, int XM>
 __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, unsigned char *mf)
 {
+    constexpr bool kDbg = XM == 2;
     constexpr int HW = BITS / 2;                       // packed dwords per lane operand
     constexpr int kSlots = KB == 1 ? UPT : (UPT + 3) / 4;   // groups of four 16-sample tiles per wave
     constexpr int kTiles = 4 * kSlots;                 // 16-sample tiles per wave, at most
@@ -119,7 +124,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const int C = a.chunks / R;
     const int64_t u_begin = a.step0 * C, u_end = (a.step0 + a.nsteps) * C;
     const int nwords = NC * B + 2;                      // exchange words of a chunk: sums, 2 side words
-    const bool xstore = !REP && a.xstore != 0 && nw == kWaves;   // exchange through tagged stores (see above; all waves take part)
+    const bool xstore = XM == 1 && !REP && nw == kWaves;   // exchange through tagged stores (see above; all waves take part)
     const int xrow = a.xrow;                            // words per row of part[][] and of res[] (multiple of kPiece)
     const int npieces = (nwords + kPiece - 1) / kPiece;
     uint64_t *const acc_base = a.acc + (size_t)rep * Workspace::kAccBuffers * a.acc_words;
@@ -385,6 +390,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     }
                 }
             }
+            ZIPML_TICK(2);
             if (side_step && wave == 0 && lane < 2) {
                 // side words: this workgroup's share of the two bounds, rounded up
                 float bw = 0.0f;
@@ -406,6 +412,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
             if (!(tid < B)) vm_wait_all();
         }
+        ZIPML_TICK(11);
         // Rotate copy 2 and request what later steps need, now: the loads travel while the
         // exchange is under way.  (A wave's memory operations complete in order and the compute
         // unit's memory pipeline keeps that order too, so the poll below cannot return before
@@ -586,11 +593,13 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 bnext[q] = bfut[q];
             }
         }
-        if (a.dbg_r && blockIdx.x == 0) {     // intermediates of a production step (zipml_debug_step)
+        if constexpr (kDbg) {
+            if (a.dbg_r && blockIdx.x == 0) {     // intermediates of a production step (zipml_debug_step)
 #pragma unroll
-            for (int q = 0; q < kBpt; ++q) {
-                const int i = tid + q * nthr;
-                if (i < B) a.dbg_r[i] = r[0][q];
+                for (int q = 0; q < kBpt; ++q) {
+                    const int i = tid + q * nthr;
+                    if (i < B) a.dbg_r[i] = r[0][q];
+                }
             }
         }
         rmax = wave_reduce_dpp(rmax, [](float p, float q) { return fmaxf(p, q); });
@@ -727,7 +736,9 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     float xnew = 0.0f;
                     if (owner) {
                         const float g = o_live ? __fdiv_rn(gsum, (float)B * (float)(a.chunks * NC)) : 0.0f;
-                        if (a.dbg_g && o_live && rep == 0) a.dbg_g[j0 + oc] = g;
+                        if constexpr (kDbg) {
+                            if (a.dbg_g && o_live && rep == 0) a.dbg_g[j0 + oc] = g;
+                        }
                         const float reg = a.l2 * x_own;
                         const float stp = a.lr * (g + reg);
                         x_own = x_own - stp;
