@@ -3,7 +3,9 @@
 // Supp. A.3 "Column Scaling": one range per feature from the column minimum and maximum.
 // Sec. 2.1: uniform levels.  Sec. 3.1-3.2: variance-optimal levels -- one scan of the data into
 // M equal bins per feature (count, sum, sum of squares of the normalised values), then the dynamic
-// program T(k,m) = min_j T(k-1,j) + V(j,m) over the bin edges, run on the host cores.
+// program T(k,m) = min_j T(k-1,j) + V(j,m) over the bin edges -- on the device (one workgroup per
+// feature, k_dp_levels) when its tables fit in LDS, else on the host cores; optionally over the
+// candidates that a greedy merge of the bins leaves (Sec. 3.2; supplement, Algorithm 1).
 #include "zipml_device.h"
 #include "zipml_host.h"
 
@@ -503,7 +505,7 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
         return hip_check(hipGetLastError());
     }
 
-    // ---- OPTIMAL: bin moments on the device, dynamic program on the host
+    // ---- OPTIMAL / GREEDY: bin moments on the device, then the dynamic program (device or host, below)
     const int M = n_candidates, sI = K - 1;
     double *hist_dev = (double *)((unsigned char *)workspace_dev + round_up(d * 8, 256));
     const int64_t hcount = d * (int64_t)M * 3;
