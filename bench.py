@@ -419,7 +419,41 @@ def dense_extras(P, args, torch, zipml, timed):
         q2 = torch.randint(0, 256, (zipml.packed_bytes(n8, d, bits),), dtype=torch.uint8, device=dev)
         sweep_point(n8, q1, q2, torch.randn(n8, device=dev), n8)
         del q1, q2
-    return {"other_ms": other, "batch_sweep": sweep}
+    compact = []
+    if not args.batch and bits == 8 and 512 < d <= 2048 and n >= 16384:
+        # Sec. 2.2, compact storage: the full-batch epoch reading base + 1 bit per copy (10 bits per
+        # value) instead of the two packed copies (16 bits), on the same codes -- the real ones, and
+        # the same rows eight times over (each feature group of an array is contiguous in the samples)
+        p1s, p2s = torch.zeros_like(P.p1), torch.zeros_like(P.p2)
+        zipml.quantize_swapped(P.A, n, d, d, 0, n, P.lev, bits, 0, 0, p1s, p2s)
+        comp = torch.zeros(zipml.compact_bytes(n, d, bits), dtype=torch.uint8, device=dev)
+        zipml.compact_encode(p2s, P.p2, n, d, bits, comp, P.ws)
+        del p1s, p2s
+        d32 = (d + 31) // 32
+        for rep in (1, 8):
+            nn = n * rep
+            tile = lambda t: t.view(d32, -1).repeat(1, rep).reshape(-1) if rep > 1 else t
+            nbase = zipml.packed_bytes(n, d, bits)      # the record is two planes: base levels, pairs of bit words
+            q1, q2, bs = tile(P.p1), tile(P.p2), P.b.repeat(rep)
+            qc = torch.cat([tile(comp[:nbase]), tile(comp[nbase:])])
+            xs = torch.zeros(d, dtype=torch.float32, device=dev)
+            xc = torch.zeros(d, dtype=torch.float32, device=dev)
+            wss = torch.zeros(zipml.workspace_bytes(nn, d, bits, nn), dtype=torch.uint8, device=dev)
+            try:
+                ms_p = timed(lambda: zipml.sgd_epoch(q1, q2, P.lev, bs, nn, d, bits, xs, nn, w.lr, wss), 5)
+                ms_c = timed(lambda: zipml.sgd_epoch_compact(qc, P.lev, bs, nn, d, bits, xc, nn, w.lr, wss), 5)
+            except zipml.ZipmlError as e:
+                compact.append({"n": nn, "batch": nn, "error": str(e)})
+                continue
+            st = zipml.sgd_status(wss)
+            read_c = nn * (d32 * 32 * (bits + 2) / 8 + 4)
+            compact.append({"n": nn, "batch": nn, "status": zipml.strerror(st) if st else "ok",
+                            "ms_per_epoch_two_packed_copies": ms_p, "ms_per_epoch_compact_record": ms_c,
+                            "speedup": ms_p / ms_c, "same_model_bits": bool(torch.equal(xs, xc)),
+                            "compact_GBps": read_c / (ms_c * 1e-3) / 1e9,
+                            "packed_equivalent_GBps": nn * (2 * d * bits / 8 + 4) / (ms_c * 1e-3) / 1e9})
+            del q1, q2, qc, bs, wss
+    return {"other_ms": other, "batch_sweep": sweep, "compact_record_epoch": compact}
 
 
 if __name__ == "__main__":

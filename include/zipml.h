@@ -122,10 +122,11 @@ int zipml_quantize_swapped(void *stream, const float *A_dev, int64_t n_rows, int
  * hold both, bits + 2 bits per value instead of 2 * bits.  packed_a_dev and packed_b_dev are the
  * two copies in the SAME layout -- (packed2s, packed2): copy 1 and copy 2 sample-major, or
  * (packed1, packed1s): copy 1 and copy 2 feature-major, see zipml_quantize_swapped -- and
- * compact_dev holds zipml_compact_bytes(n, d, bits) bytes: per unit of 32 values the smaller of
- * the two codes (bits dwords), then one dword of bits per copy saying which values sit one level
- * above it.  A storage and transfer format: the epoch kernels read the packed copies, which
- * zipml_compact_decode restores bit for bit.  zipml_compact_encode synchronises the stream and
+ * compact_dev holds zipml_compact_bytes(n, d, bits) bytes in two planes: first the smaller of the
+ * two codes of every value, a packed array in the layout of the copies (bits / (bits + 2) of the
+ * record); then, per unit of 32 values in the same order, a pair of dwords of bits saying which
+ * values of copy a / copy b sit one level above it.  A storage and transfer format, restored bit
+ * for bit by zipml_compact_decode; zipml_sgd_epoch_compact runs on the sample-major record as it is.  zipml_compact_encode synchronises the stream and
  * returns ZIPML_EINVAL if some pair of codes differs by more than one level (the arrays are then
  * not two samples of the same values); it uses 256 bytes of workspace. */
 size_t zipml_compact_bytes(int64_t n, int64_t d, int bits);
@@ -134,6 +135,19 @@ int zipml_compact_encode(void *stream, const void *packed_a_dev, const void *pac
                          size_t workspace_bytes);
 int zipml_compact_decode(void *stream, const void *compact_dev, int64_t n, int64_t d, int bits,
                          void *packed_a_dev, void *packed_b_dev);
+
+/* zipml_sgd_epoch for very large minibatches reading the COMPACT record alone (Sec. 2.2, "Overhead
+ * of Storing Samples"): compact_dev is what zipml_compact_encode writes for the two copies in the
+ * sample-major layout, (packed2s, packed2) -- copy 1 from zipml_quantize_swapped, copy 2 from
+ * zipml_quantize.  A step then reads bits + 2 instead of 2 * bits bits per value; the gradient pass
+ * turns its operand on the chip.  Same estimator and arithmetic as zipml_sgd_epoch on the packed
+ * copies (the model after the epoch is bit-identical).  Built for bits = 8, evenly spaced levels,
+ * the fp32 model, minibatches of at least 16384 samples (a multiple of 64) and 513 to 2048
+ * features; ZIPML_EUNSUPPORTED otherwise (for level tables that turn out not to be evenly spaced:
+ * through zipml_sgd_status).  Asynchronous; workspace as for zipml_sgd_epoch. */
+int zipml_sgd_epoch_compact(void *stream, const void *compact_dev, const float *levels_dev,
+                            const float *b_dev, int64_t n, int64_t d, int bits, float *x_dev,
+                            int64_t batch, float lr, void *workspace_dev, size_t workspace_bytes);
 
 /* One epoch of double-sampled minibatch SGD on F(x) = 1/(2n) sum_i (a_i^T x - b_i)^2
  * (Sec. 2 and eq. (5); the minibatch gradient is the mean over `batch` consecutive samples; the

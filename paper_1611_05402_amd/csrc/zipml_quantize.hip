@@ -288,8 +288,12 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
 // Compact storage of two copies that are stored in the same layout (Sec. 2.2, "Overhead of
 // Storing Samples"): the two samples of a value differ by at most one level, so a base level and
 // one bit per sample hold both, b + 2 bits per value instead of 2 b.  One thread per packed unit
-// of 32 codes: [BITS dwords base = min of the two codes][1 dword: copy a sits one above the base]
-// [1 dword: copy b does].  Pairs further apart than one level cannot be stored: counted in *bad.
+// of 32 codes.  The record is two planes: the base levels (min of the two codes) as a packed array
+// in the layout of the copies, then per unit a pair of dwords of bits (copy a sits one above the
+// base; copy b does).  In planes because a kernel that streams the record reads the bases and the
+// bits with different instructions: in one interleaved array every memory line would be touched
+// by both, and streaming (non-temporal) loads then fetch it twice.  Pairs of codes further apart
+// than one level cannot be stored: counted in *bad.
 template <int BITS>
 __global__ __launch_bounds__(256) void k_compact_encode(const uint32_t *__restrict__ pa,
                                                         const uint32_t *__restrict__ pb, int64_t units,
@@ -311,11 +315,12 @@ __global__ __launch_bounds__(256) void k_compact_encode(const uint32_t *__restri
         ua |= ((ca - lo) & 1u) << k;
         ub |= ((cb - lo) & 1u) << k;
     }
-    uint32_t *dst = out + u * (BITS + 2);
+    uint32_t *dst = out + u * BITS;
 #pragma unroll
     for (int q = 0; q < BITS; ++q) dst[q] = base[q];
-    dst[BITS] = ua;
-    dst[BITS + 1] = ub;
+    uint32_t *pair = out + units * BITS + 2 * u;
+    pair[0] = ua;
+    pair[1] = ub;
     if (wrong) atomicAdd(bad, 1);
 }
 
@@ -325,11 +330,11 @@ __global__ __launch_bounds__(256) void k_compact_decode(const uint32_t *__restri
 {
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (u >= units) return;
-    const uint32_t *src = in + u * (BITS + 2);
+    const uint32_t *src = in + u * BITS;
     uint32_t base[BITS], a[BITS], b[BITS];
 #pragma unroll
     for (int q = 0; q < BITS; ++q) { base[q] = src[q]; a[q] = 0u; b[q] = 0u; }
-    const uint32_t ua = src[BITS], ub = src[BITS + 1];
+    const uint32_t ua = in[units * BITS + 2 * u], ub = in[units * BITS + 2 * u + 1];
 #pragma unroll
     for (int k = 0; k < 32; ++k) {
         const uint32_t lo = unit_code<BITS>(base, k);

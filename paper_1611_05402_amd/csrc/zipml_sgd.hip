@@ -217,6 +217,7 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ p, uint32
 }  // namespace zipml
 #include "zipml_sgd_mfma.h"
 #include "zipml_sgd_rows.h"
+#include "zipml_sgd_rows_compact.h"
 namespace zipml {
 
 // ---- inner loops over the 32 codes of a unit (v: 32 wave-uniform fp32/int32 values in LDS) ----
@@ -1568,6 +1569,69 @@ extern "C" int zipml_sgd_epoch_avg(void *stream, const void *packed1_dev, const 
     return run_sgd(stream, packed1_dev, packed2_dev, packed1s_dev, packed2s_dev, levels_dev, nullptr,
                    0.0f, 0.0f, 0, b_dev, n, d, bits, x_dev, batch, lr, l2, 0, 0, 0, 0, flags, 0, steps,
                    nullptr, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes);
+}
+
+// The epoch on the compact record of the two sample-major copies (zipml_sgd_rows_compact.h).
+extern "C" int zipml_sgd_epoch_compact(void *stream, const void *compact_dev, const float *levels_dev,
+                                       const float *b_dev, int64_t n, int64_t d, int bits, float *x_dev,
+                                       int64_t batch, float lr, void *workspace_dev, size_t workspace_bytes)
+{
+    if (!compact_dev || !levels_dev || !b_dev || !x_dev) return ZIPML_EINVAL;
+    if (n <= 0 || d <= 0 || !valid_bits(bits) || batch <= 0 || n % batch != 0) return ZIPML_EINVAL;
+    if (n > (int64_t)1 << 40 || d > (1 << 24)) return ZIPML_EINVAL;
+    if (!aligned16(compact_dev) || !aligned16(levels_dev) || !aligned16(b_dev) || !aligned16(x_dev) ||
+        !aligned16(workspace_dev))
+        return ZIPML_EALIGN;
+    if (!workspace_dev || workspace_bytes < zipml_workspace_bytes(n, d, bits, batch, 0)) return ZIPML_EWORKSPACE;
+    const Layout lay = make_layout(n, d, bits);
+    const int NKB = (int)((lay.d32 + 1) / 2);
+    // built for 8-bit codes (where the record saves most), minibatches that the sample owners take,
+    // and 9 to 32 blocks of 64 features (a wave keeps copy 1 of its two or four blocks of a tile in LDS)
+    if (bits != 8 || batch < Workspace::kRowsMinBatch || batch % 64 != 0 || NKB <= kWaves || NKB > 4 * kWaves)
+        return ZIPML_EUNSUPPORTED;
+    hipStream_t s = entry_stream(stream);
+    int cus = 0, lds = 0;
+    if (int rc = device_limits(cus, lds)) return rc;
+    const size_t shmem = rows_compact_lds_bytes(NKB);
+    if (shmem > (size_t)lds) return ZIPML_EUNSUPPORTED;
+    int wgs = std::min(cus, Workspace::kMaxRowsWgs);
+    if (const long long v = knob(ZIPML_KNOB_ROWS_WORKGROUPS); v >= 1 && v <= Workspace::kMaxRowsWgs) wgs = (int)v;
+    unsigned char *wsb = (unsigned char *)workspace_dev;
+    float *rows = (float *)(wsb + Workspace::sgd_bytes(batch) + (size_t)round_up(d, 64) * 4);
+    RowsArgs r{};
+    r.p1 = nullptr;
+    r.p2 = (const uint32_t *)compact_dev;
+    r.b = b_dev;
+    r.x = x_dev;
+    r.dl = rows;
+    r.mid = rows + (size_t)NKB * 64;
+    r.part = rows + (size_t)2 * NKB * 64;
+    r.n_pad = lay.n_pad;
+    r.n32 = lay.n32;
+    r.d = (int)d;
+    r.d32 = (int)lay.d32;
+    r.NKB = NKB;
+    r.B = batch;
+    r.step0 = 0;
+    r.nsteps = (int)(n / batch);
+    r.lr = lr;
+    r.status = (int *)(wsb + Workspace::kStatus);
+    r.sync = (uint32_t *)(wsb + Workspace::kSync);
+    r.even = (const int *)(wsb + Workspace::kEven);
+    r.spin_limit = kSpinLimit;
+    if (const long long v = knob(ZIPML_KNOB_SPIN_LIMIT); v >= 0 && v <= (long long)kSpinLimit) r.spin_limit = (uint32_t)v;
+    const void *kern = NKB <= 2 * kWaves ? (const void *)k_sgd_rows_compact<2> : (const void *)k_sgd_rows_compact<4>;
+    if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
+        return ZIPML_ELAUNCH;
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, r.status, r.sync,
+                       (uint64_t *)(wsb + Workspace::kAcc), 0, 1, levels_dev, r.x, r.d, 256, (double *)nullptr,
+                       (int *)(wsb + Workspace::kEven), const_cast<float *>(r.dl), const_cast<float *>(r.mid),
+                       NKB * 64, 128.0f);
+    if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
+    void *params[] = {&r};
+    if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(wgs), dim3(kThreads), params, (unsigned)shmem, s)))
+        return ZIPML_ELAUNCH;
+    return ZIPML_OK;
 }
 
 extern "C" int zipml_debug_step(void *stream, const void *packed1_dev, const void *packed2_dev,

@@ -393,7 +393,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_sgd_rows(RowsArgs a)
 }
 
 // LDS of k_sgd_rows for NKB blocks of 64 features.
-inline size_t rows_lds_bytes(int NKB)
+__host__ __device__ inline size_t rows_lds_bytes(int NKB)
 {
     return (size_t)NKB * 512 + kWaves * 64 * 8 + 256 + 64 + 64 + 16;
 }

@@ -25,7 +25,7 @@ EXPORTS = ["zipml_strerror", "zipml_packed_bytes", "zipml_workspace_bytes", "zip
            "zipml_quantize", "zipml_quantize_swapped", "zipml_compact_bytes", "zipml_compact_encode",
            "zipml_compact_decode", "zipml_sgd_epoch", "zipml_sgd_epoch_l2",
            "zipml_sgd_epoch_prox", "zipml_sgd_epoch_avg", "zipml_sgd_epoch_static", "zipml_sgd_status",
-           "zipml_loss", "zipml_debug_stream", "zipml_debug_set",
+           "zipml_loss", "zipml_debug_stream", "zipml_debug_set", "zipml_sgd_epoch_compact",
            "zipml_unpack_codes", "zipml_debug_step"]
 
 
@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
         sgd = [vp, vp, vp, vp, vp, f32, f32, i32, vp, i64, i64, i32, vp, i64, f32, i32, i32, u64, u32]
         L.zipml_sgd_epoch.restype = i32
         L.zipml_sgd_epoch.argtypes = sgd + [i32, vp, sz]
+        L.zipml_sgd_epoch_compact.restype = i32
+        L.zipml_sgd_epoch_compact.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, i64, f32, vp, sz]
         L.zipml_sgd_epoch_static.restype = i32
         L.zipml_sgd_epoch_static.argtypes = sgd + [i32, vp]
         L.zipml_sgd_epoch_l2.restype = i32
@@ -194,6 +196,14 @@ def sgd_epoch_static(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, st
     args = _sgd_args(packed1, packed2, levels_t, grid_idx, grid_lo, grid_step, grid_max, b, n, d,
                      bits, x, batch, lr, grad_bits, model_bits, seed, epoch, stream)
     _check(lib().zipml_sgd_epoch_static(*args, flags, _ptr(status)), "zipml_sgd_epoch_static")
+
+
+def sgd_epoch_compact(compact, levels_t, b, n, d, bits, x, batch, lr, workspace, stream=None):
+    """The epoch on the compact record of (packed2s, packed2) alone (very large minibatches, 8 bits)."""
+    _check(lib().zipml_sgd_epoch_compact(_stream(stream), _ptr(compact), _ptr(levels_t), _ptr(b), n, d,
+                                         bits, _ptr(x), batch, lr, _ptr(workspace),
+                                         workspace.numel() * workspace.element_size()),
+           "zipml_sgd_epoch_compact")
 
 
 def sgd_epoch_l2(packed1, packed2, levels_t, b, n, d, bits, x, batch, lr, l2, workspace, *, flags=0,

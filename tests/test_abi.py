@@ -100,6 +100,17 @@ def test_argument_errors_are_codes_not_crashes(lib):
     assert prox(batch=24) == zipml.EINVAL
     assert prox(x=odd) == zipml.EALIGN
 
+    def compact(rec=fake, n=32768, d=1024, bits=8, batch=16384, ws=1 << 30):
+        return lib.zipml_sgd_epoch_compact(null, rec, fake, fake, n, d, bits, fake, batch, 0.1, fake, ws)
+    assert compact(rec=null) == zipml.EINVAL
+    assert compact(rec=odd) == zipml.EALIGN
+    assert compact(n=1000) == zipml.EINVAL            # whole minibatches
+    assert compact(ws=1024) == zipml.EWORKSPACE
+    assert compact(bits=4) == zipml.EUNSUPPORTED      # built for 8-bit codes,
+    assert compact(batch=4096) == zipml.EUNSUPPORTED  # very large minibatches
+    assert compact(d=512) == zipml.EUNSUPPORTED       # and 513 .. 2048 features
+    assert compact(d=2049) == zipml.EUNSUPPORTED
+
     def avg(p1s=fake, p2s=fake, bits=4, batch=64, flags=0):
         return lib.zipml_sgd_epoch_avg(null, fake, fake, p1s, p2s, fake, fake, 128, 8, bits, fake, batch, 0.1,
                                        0.0, flags, fake, 1 << 20)

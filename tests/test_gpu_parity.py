@@ -272,12 +272,13 @@ def test_compact_storage_roundtrip_and_layout(n, d, bits):
     for copy, pa, pb in ((2, p2s, p.p2), (1, p.p1, p1s)):
         comp = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
         zipml.compact_encode(pa, pb, n, d, bits, comp, p.ws)
-        units = comp.view(torch.int32).view(-1, bits + 2)
-        # the base plane is a packed array of its own, the two bit planes are 1-bit packed arrays
-        zipml.unpack_codes(units[:, :bits].contiguous().view(torch.uint8), copy, n, d, bits, out)
+        # the base plane is a packed array of its own, then come pairs of dwords: two 1-bit packed arrays
+        nbase = zipml.packed_bytes(n, d, bits)
+        zipml.unpack_codes(comp[:nbase], copy, n, d, bits, out)
         assert np.array_equal(out.cpu().numpy(), base)
-        for plane, want in ((bits, u1), (bits + 1, u2)):
-            zipml.unpack_codes(units[:, plane:plane + 1].contiguous().view(torch.uint8), copy, n, d, 1, out)
+        pairs = comp[nbase:].view(torch.int32).view(-1, 2)
+        for plane, want in ((0, u1), (1, u2)):
+            zipml.unpack_codes(pairs[:, plane].contiguous().view(torch.uint8), copy, n, d, 1, out)
             assert np.array_equal(out.cpu().numpy(), want)
         qa, qb = torch.zeros_like(pa), torch.zeros_like(pb)
         zipml.compact_decode(comp, n, d, bits, qa, qb)
@@ -795,6 +796,71 @@ def test_symmetrised_estimator_refusals():
         zipml.sgd_epoch(p.p1, p.p2, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 0.01, p.ws,
                         flags=zipml.SGD_AVERAGED)
     assert e.value.code == zipml.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ epoch on the compact record
+@pytest.mark.parametrize("name,kw,lr", [
+    ("d1000_b16384", dict(n=32768, d=1000, batch=16384), 0.05),    # 16 blocks of 64 features: two per wave
+    ("d600_b16384", dict(n=16384, d=600, batch=16384), 0.05),      # 10 blocks, the last one half padding
+    ("d1990_b16384", dict(n=32768, d=1990, batch=16384), 0.02),    # 32 blocks: four per wave, last half padding
+    ("d2048_full_batch", dict(n=32768, d=2048, batch=32768), 0.02),
+])
+def test_epoch_on_the_compact_record(name, kw, lr, knobs):
+    """Sec. 2.2, "Overhead of Storing Samples": the sample-owner epoch reading base + 1 bit per copy.
+    Same integers as on the two packed copies, so the model is bit-identical to zipml_sgd_epoch's,
+    and both match the oracle."""
+    say("compact epoch", name)
+    knobs(zipml.KNOB_ROWS_MIN_BATCH, 16384)       # zipml_sgd_epoch on the packed copies: sample owners too
+    w = synth.dense8(**kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(L)
+    p.quantize(33, 0)
+    p1s, p2s = torch.zeros_like(p.p1), torch.zeros_like(p.p2)
+    zipml.quantize_swapped(p.A, w.n, w.d, w.d, 0, w.n, p.levels, w.bits, 33, 0, p1s, p2s)
+    comp = torch.zeros(zipml.compact_bytes(w.n, w.d, w.bits), dtype=torch.uint8, device=DEV)
+    zipml.compact_encode(p2s, p.p2, w.n, w.d, w.bits, comp, p.ws)      # (copy 1, copy 2), sample-major
+    assert comp.numel() * 16 == p.p2.numel() * 2 * 10                 # 10 bits per value instead of 16
+    del p1s, p2s
+    c1, c2 = oracle.quantize(A, L, w.bits, 33, 0)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    xc = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(3):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, lr)
+        p.epoch(x, lr)
+        zipml.sgd_epoch_compact(comp, p.levels, p.b, w.n, w.d, w.bits, xc, w.batch, lr, p.ws)
+        assert zipml.sgd_status(p.ws) == 0
+        err = rel_l2(xc.cpu().numpy(), x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}")
+        assert err <= TOL and max_abs_ok(xc.cpu().numpy(), x_ref, TOL)
+        assert torch.equal(x, xc)
+    assert float(xc.abs().max()) > 0.0
+
+
+def test_epoch_on_the_compact_record_refusals():
+    def refused(w, levels=None):
+        A, b = w.full()
+        p = GpuProblem(A, b, w.bits, w.batch)
+        p.set_levels(_levels_for(w, A) if levels is None else levels(w, A))
+        comp = torch.zeros(max(zipml.compact_bytes(w.n, w.d, w.bits), 16), dtype=torch.uint8, device=DEV)
+        x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        try:
+            zipml.sgd_epoch_compact(comp, p.levels, p.b, w.n, w.d, w.bits, x, w.batch, 0.01, p.ws)
+        except zipml.ZipmlError as e:
+            return e.code
+        return zipml.sgd_status(p.ws)
+    assert refused(synth.tiny(n=16384, d=1024, batch=16384, bits=4)) == zipml.EUNSUPPORTED     # 8 bits only
+    assert refused(synth.dense8(n=8192, d=1024, batch=4096)) == zipml.EUNSUPPORTED             # small minibatch
+    assert refused(synth.dense8(n=16384, d=512, batch=16384)) == zipml.EUNSUPPORTED            # 8 blocks: too few
+    assert refused(synth.dense8(n=16384, d=2049, batch=16384)) == zipml.EUNSUPPORTED           # 33 blocks: too many
+
+    def uneven(w, A):   # a level table that is not evenly spaced: refused through the status word
+        L = _levels_for(w, A).copy()
+        L[5, 100] += 0.25 * (L[5, 101] - L[5, 100])
+        return L
+    assert refused(synth.dense8(n=16384, d=576, batch=16384), levels=uneven) == zipml.EUNSUPPORTED
 
 
 # ------------------------------------------------------------------ least-squares SVM
