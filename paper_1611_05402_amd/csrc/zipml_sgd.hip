@@ -537,17 +537,19 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
                     publish(i, pf, pi);
                 }
             }
-            // The last wave of workgroup 0 clears the exchange words of step t+2 (four buffers in
-            // rotation).  Workgroup 0 is past the exchange of step t-1, so every workgroup has
-            // contributed to step t-1 and has therefore finished reading step t-2, the last user of
-            // that buffer.  The stores have been performed before this wave leaves the step: a
+            // The last wave of every workgroup clears its share of the exchange words of step t+2
+            // (four buffers in rotation; one workgroup clearing them all made it the last to arrive
+            // at every exchange).  The workgroup is past the exchange of step t-1, so every workgroup
+            // has contributed to step t-1 and has therefore finished reading step t-2, the last user
+            // of that buffer.  The stores have been performed before this wave leaves the step: a
             // wave's memory operations are reported complete in order, so the poll below (or the
             // explicit wait, if the wave has no samples to poll for) cannot finish before they
             // have.  The workgroup's contributions to step t+1 come after that, and nobody adds to
-            // step t+2 before having seen all contributions to step t+1.
-            if (grid_sync && w == 0 && wave == kWaves - 1) {
+            // step t+2 before having seen all contributions to step t+1 -- this workgroup's among them.
+            if (grid_sync && wave == kWaves - 1) {
                 uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
-                for (int i = lane; i < B + 1; i += kWave) store_dev(nxt + i, (uint64_t)0);
+                const int per = (B + 1 + a.W - 1) / a.W, hi = (w + 1) * per < B + 1 ? (w + 1) * per : B + 1;
+                for (int i = w * per + lane; i < hi; i += kWave) store_dev(nxt + i, (uint64_t)0);
                 if (!(tid < B)) vm_wait_all();
             }
             ZIPML_TICK(1);

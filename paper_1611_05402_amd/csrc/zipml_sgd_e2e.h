@@ -268,20 +268,19 @@ __device__ __forceinline__ void sgd_steps_e2e(const SgdArgs &a, const Lds &L)
             }
         }
         ZIPML_TICK(2);
-        // The last wave of workgroup 0 clears the exchange words and the norm slots of step t+2
-        // (four buffers in rotation).  Workgroup 0 is past the ||x|| exchange of step t, so every
-        // workgroup has finished step t-1 and with it every read of step t-2, the last user of
-        // these buffers; the stores are complete before this wave's poll below returns (a wave's
-        // memory operations complete in order), hence before workgroup 0 contributes to any later
-        // exchange, and nobody reaches step t+2 without those contributions.
-        if (w == 0 && wave == kWaves - 1) {
+        // The last wave of every workgroup clears its share of the exchange words, and its own norm
+        // slots, of step t+2 (four buffers in rotation).  The workgroup is past the ||x|| exchange of
+        // step t, so every workgroup has finished step t-1 and with it every read of step t-2, the
+        // last user of these buffers; the stores are complete before this wave's poll below returns
+        // (a wave's memory operations complete in order), hence before the workgroup contributes to
+        // any later exchange, and nobody reaches step t+2 without those contributions.
+        if (wave == kWaves - 1) {
             uint64_t *nxt = a.acc + (size_t)((t + 2) & 3) * a.acc_words;
-            for (int i = lane; i < B + 1; i += kWave) store_dev(nxt + i, (uint64_t)0);
-            uint64_t *x2 = slot_base + (size_t)((t + 2) & 3) * kNormSlots;
-            uint64_t *g2 = slot_base + (size_t)(4 + ((t + 2) & 3)) * kNormSlots;
-            for (int i = lane; i < W; i += kWave) {
-                store_dev(x2 + i, (uint64_t)0);
-                store_dev(g2 + i, (uint64_t)0);
+            const int per = (B + 1 + W - 1) / W, hi = (w + 1) * per < B + 1 ? (w + 1) * per : B + 1;
+            for (int i = w * per + lane; i < hi; i += kWave) store_dev(nxt + i, (uint64_t)0);
+            if (lane == 0) {
+                store_dev(slot_base + (size_t)((t + 2) & 3) * kNormSlots + w, (uint64_t)0);
+                store_dev(slot_base + (size_t)(4 + ((t + 2) & 3)) * kNormSlots + w, (uint64_t)0);
             }
             if (!(tid < B)) vm_wait_all();
         }

@@ -127,6 +127,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const bool xstore = XM == 1 && !REP && nw == kWaves;   // exchange through tagged stores (see above; all waves take part)
     const int xrow = a.xrow;                            // words per row of part[][] and of res[] (multiple of kPiece)
     const int npieces = (nwords + kPiece - 1) / kPiece;
+    const int clr_per = (nwords + W - 1) / W;           // words of a later step that this workgroup clears
+    const int clr_lo = w * clr_per, clr_hi = clr_lo + clr_per < nwords ? clr_lo + clr_per : nwords;
     uint64_t *const acc_base = a.acc + (size_t)rep * Workspace::kAccBuffers * a.acc_words;
     const uint32_t *const p2base[2] = {a.p2, a.p2s}, *const p1base[2] = {a.p1, a.p1s};
 
@@ -150,10 +152,10 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         // nothing to look after: meet the others at their barriers, step by step
         for (int64_t u = u_begin; u < u_end; ++u) {
             lds_barrier();
-            if (w == 0 && wave == kWaves - 1) {
-                // clear the exchange words of step t+2 (see zipml_sgd.hip for why now)
+            if (wave == kWaves - 1) {
+                // clear this workgroup's share of the exchange words of step t+2 (see zipml_sgd.hip for why now)
                 uint64_t *nxt = acc_base + (size_t)((u + 2) & 3) * a.acc_words;
-                for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
+                for (int i = clr_lo + lane; i < clr_hi; i += kWave) store_dev(nxt + i, (uint64_t)0);
                 vm_wait_all();
             }
             if (xstore)
@@ -404,12 +406,12 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 else add_dev(acc + NC * B + lane, pack_int(v));
             }
         }
-        // The last wave of workgroup 0 clears the exchange words of step t+2 (see zipml_sgd.hip
-        // for why that is the right moment and why no wait is needed here); with idle waves
-        // around, one of them does it instead.
-        if (!xstore && nw == kWaves && w == 0 && wave == kWaves - 1) {
+        // The last wave of every workgroup clears its share of the exchange words of step t+2 (see
+        // zipml_sgd.hip for why that is the right moment and why no wait is needed here); with
+        // idle waves around, one of them does it instead.
+        if (!xstore && nw == kWaves && wave == kWaves - 1) {
             uint64_t *nxt = acc_base + (size_t)((u + 2) & 3) * a.acc_words;
-            for (int i = lane; i < nwords; i += kWave) store_dev(nxt + i, (uint64_t)0);
+            for (int i = clr_lo + lane; i < clr_hi; i += kWave) store_dev(nxt + i, (uint64_t)0);
             if (!(tid < B)) vm_wait_all();
         }
         ZIPML_TICK(11);

@@ -53,7 +53,7 @@ __device__ __forceinline__ v4i spread_bits16(uint32_t bits16)
 template <int NG>
 __device__ __forceinline__ void sgd_rows_compact(const RowsArgs &a, unsigned char *smem)
 {
-    constexpr int BITS = 8, HW = 4;
+    constexpr int HW = 4;                             // dwords of a lane operand: 16 codes of 8 bits
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
