@@ -316,7 +316,9 @@ def main():
         if name == headline and not args.no_cpu_baseline:
             baseline = cpu_baseline(P, args.cpu_seconds, threads)
         if name == "dense8" and not args.no_extras:
-            extras = dense_extras(P, args, torch, zipml, timed)
+            extras.update(dense_extras(P, args, torch, zipml, timed))
+        if name == headline and name != "dense8" and not args.no_extras and not args.batch:
+            extras["batch_sweep_headline"] = headline_sweep(P, torch, zipml, timed)
         del P
         torch.cuda.empty_cache()
 
@@ -360,6 +362,31 @@ def main():
     # release everything and drain the device before the interpreter starts tearing modules down
     del results, out
     torch.cuda.synchronize()
+
+
+def headline_sweep(P, torch, zipml, timed):
+    """The headline workload's epoch at larger minibatches (not part of `value`): where the packed-data
+    rate approaches the HBM peak on this shape."""
+    w = P.w
+    n, d, bits = w.n, w.d, w.bits
+    dev = P.b.device
+    out = []
+    for batch in (4 * w.batch, 16 * w.batch, 64 * w.batch, n):
+        if batch > n or n % batch:
+            continue
+        x = torch.zeros(d, dtype=torch.float32, device=dev)
+        ws = torch.zeros(zipml.workspace_bytes(n, d, bits, batch), dtype=torch.uint8, device=dev)
+        try:
+            ms = timed(lambda: zipml.sgd_epoch(P.p1, P.p2, P.lev, P.b, n, d, bits, x, batch, w.lr, ws), 3)
+        except zipml.ZipmlError as e:
+            out.append({"batch": batch, "error": str(e)})
+            continue
+        st = zipml.sgd_status(ws)
+        gbps = n * (2 * d * bits / 8 + 4) / (ms * 1e-3) / 1e9
+        out.append({"batch": batch, "status": zipml.strerror(st) if st else "ok", "ms_per_epoch": ms,
+                    "us_per_step": ms * 1e3 / (n // batch), "GBps": gbps, "frac_hbm_peak": gbps / HBM_PEAK_GBS})
+        del ws
+    return out
 
 
 def dense_extras(P, args, torch, zipml, timed):
