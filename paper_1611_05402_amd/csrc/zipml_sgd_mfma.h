@@ -183,6 +183,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         return k1 < k2 ? k1 : k2;
     };
     int ky = scale_of();
+    int ky_pub = ky;                                   // the scale the sums in flight were published with
 
     // ---- owner lanes: per-feature constants, and where the digits of y_j go
     const float o_lo = owner ? L.los[oc] : 0.0f, o_dl = owner ? L.dls[oc] : 0.0f;
@@ -335,7 +336,6 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         uint64_t *const acc = acc_base + (size_t)(u & 3) * a.acc_words;
         const uint32_t xtag = ((uint32_t)(u + 1) & 0x7FFFu) | 0x8000u;
         uint64_t *const xpart = a.xpart + (size_t)(u & 1) * ((size_t)W * xrow);
-        uint64_t *const xmine = xpart + (size_t)w * xrow;
         uint64_t *const xres = a.xres + (size_t)(u & 1) * xrow;
         const bool side_step = first && (t % kRefresh) == 0;   // bounds travel with this exchange
         const bool side_next = last && ((t + 1) % kRefresh) == 0;
@@ -352,6 +352,19 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             rmax_step = 0.0f;
         }
 
+        // Dot pass of chunk uu at the model whose digits are in LDS, its partial sums into the
+        // exchange, then the requests for the data of later chunks.  (A function of the chunk so that
+        // the development build -DZIPML_STALE_DOT_EXPERIMENT can publish chunk u + 1 from the OLD
+        // model before the gradient pass of chunk u: a one-step-delayed SGD, not the paper's, which
+        // bounds from above what taking the gradient pass and the update off the path between two
+        // exchanges could gain.  Measured on the dense 8-bit shape: nothing, 2.95 against 2.99 us per
+        // step -- a step is the sum of its phases, and reading the exchange words, a device-scope load
+        // of some 0.6 us, stays on the path however early the sums were published.)
+        auto dot_and_publish = [&](int64_t uu, bool pub_side) __attribute__((always_inline)) {
+        uint64_t *const pub_acc = acc_base + (size_t)(uu & 3) * a.acc_words;
+        const uint32_t pub_xtag = ((uint32_t)(uu + 1) & 0x7FFFu) | 0x8000u;
+        uint64_t *const pub_xmine = a.xpart + (size_t)(uu & 1) * ((size_t)W * xrow) + (size_t)w * xrow;
+        ky_pub = ky;
         // ============ dot pass: one instruction per (16 samples, 64 features)
         {
             // what every sample of this workgroup gets on top of sum_j (code - off) * Y_j
@@ -386,14 +399,14 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                         }
                         const int tile = wave + nw * (4 * gi + q4);
                         if (tile < ntile) {
-                            if (xstore) store_dev(xmine + cc * B + 16 * tile + n16, tag_word(xtag, combine_digits(c) + kconst));
-                            else add_dev(acc + cc * B + 16 * tile + n16, pack_int(combine_digits(c) + kconst));
+                            if (xstore) store_dev(pub_xmine + cc * B + 16 * tile + n16, tag_word(pub_xtag, combine_digits(c) + kconst));
+                            else add_dev(pub_acc + cc * B + 16 * tile + n16, pack_int(combine_digits(c) + kconst));
                         }
                     }
                 }
             }
             ZIPML_TICK(2);
-            if (side_step && wave == 0 && lane < 2) {
+            if (pub_side && wave == 0 && lane < 2) {
                 // side words: this workgroup's share of the two bounds, rounded up
                 float bw = 0.0f;
                 int mx = 0;
@@ -402,15 +415,15 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     mx = ymx[f] > mx ? ymx[f] : mx;
                 }
                 const long long v = lane == 0 ? __double2ll_ru(ldexp((double)bw, ky)) + 1 : (long long)mx;
-                if (xstore) store_dev(xmine + NC * B + lane, tag_word(xtag, v));
-                else add_dev(acc + NC * B + lane, pack_int(v));
+                if (xstore) store_dev(pub_xmine + NC * B + lane, tag_word(pub_xtag, v));
+                else add_dev(pub_acc + NC * B + lane, pack_int(v));
             }
         }
         // The last wave of every workgroup clears its share of the exchange words of step t+2 (see
         // zipml_sgd.hip for why that is the right moment and why no wait is needed here); with
         // idle waves around, one of them does it instead.
         if (!xstore && nw == kWaves && wave == kWaves - 1) {
-            uint64_t *nxt = acc_base + (size_t)((u + 2) & 3) * a.acc_words;
+            uint64_t *nxt = acc_base + (size_t)((uu + 2) & 3) * a.acc_words;
             for (int i = clr_lo + lane; i < clr_hi; i += kWave) store_dev(nxt + i, (uint64_t)0);
             if (!(tid < B)) vm_wait_all();
         }
@@ -432,16 +445,22 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 for (int cc = 0; cc < NC; ++cc) p2ptr[cc][ti][kb] += step_dwords;   // now at step t+1
             }
         if constexpr (kDouble) {
-            if (u + 2 < u_end) load_dot(0, 1, c2nxt);
-            if (u + 1 < u_end) load_grad(0, 1, c1nxt);
+            if (uu + 2 < u_end) load_dot(0, 1, c2nxt);
+            if (uu + 1 < u_end) load_grad(0, 1, c1nxt);
         } else {
-            if (u + 1 < u_end) {
+            if (uu + 1 < u_end) {
 #pragma unroll
                 for (int cc = 0; cc < NC; ++cc) load_dot(cc, 0, c2cur[cc]);
             }
         }
-        if (u + 1 < u_end) load_labels(u + 1, bfut);
+        if (uu + 1 < u_end) load_labels(uu + 1, bfut);
         ZIPML_TICK(1);
+        };
+#ifdef ZIPML_STALE_DOT_EXPERIMENT
+        if (!(XM == 0 && NC == 1 && !REP && C == 1) || u == u_begin) dot_and_publish(u, side_step);
+#else
+        dot_and_publish(u, side_step);
+#endif
 
         // ============ tagged-store exchange, second trip: this workgroup's pieces of the sums
         if (xstore) {
@@ -530,7 +549,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 for (int cc = 0; cc < NC; ++cc) {
                     r[cc][q] = 0.0f;
                     if (i < B) {
-                        r[cc][q] = fixed_to_float(tagged_value(raw[cc][q]), ky) - bnext[q];
+                        r[cc][q] = fixed_to_float(tagged_value(raw[cc][q]), ky_pub) - bnext[q];
                         rmax = fmaxf(rmax, fabsf(r[cc][q]));
                         rsum += r[cc][q];
                     }
@@ -579,7 +598,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                     }
                 }
             }
-            if (want_side && lane < 2) side[lane] = fixed_to_float(unpack_sum(rawx, W), ky) * 1.00001f;
+            if (want_side && lane < 2) side[lane] = fixed_to_float(unpack_sum(rawx, W), ky_pub) * 1.00001f;
 #pragma unroll
             for (int q = 0; q < kBpt; ++q) {
                 const int i = tid + q * nthr;
@@ -587,7 +606,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                 for (int cc = 0; cc < NC; ++cc) {
                     r[cc][q] = 0.0f;
                     if (i < B) {
-                        r[cc][q] = fixed_to_float(unpack_sum(raw[cc][q], W), ky) - bnext[q];
+                        r[cc][q] = fixed_to_float(unpack_sum(raw[cc][q], W), ky_pub) - bnext[q];
                         rmax = fmaxf(rmax, fabsf(r[cc][q]));
                         rsum += r[cc][q];
                     }
@@ -640,6 +659,11 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
             }
         lds_barrier();
         ZIPML_TICK(8);
+#ifdef ZIPML_STALE_DOT_EXPERIMENT
+        // timing experiment: the next chunk's sums are published from the OLD model, before the
+        // gradient pass (a one-step-delayed SGD; an upper bound on what a lookahead could gain)
+        if (XM == 0 && NC == 1 && !REP && C == 1 && u + 1 < u_end) dot_and_publish(u + 1, ((t + 1) % kRefresh) == 0);
+#endif
 
         // ============ gradient pass: one instruction per (16 features, 64 samples)
         {
@@ -748,7 +772,11 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
                         xnew = x_own;
                     }
                     gsum = 0.0f;
+#ifdef ZIPML_STALE_DOT_EXPERIMENT
+                    refresh_y(xnew, ky_own, true);
+#else
                     refresh_y(xnew, ky_own, side_next);
+#endif
                 }
             }
         }
