@@ -806,7 +806,12 @@ namespace zipml {
 // ---------------------------------------------------------------------------------------------
 // REP: the launch has replicas of the workgroups (a.R > 1; matrix-core loop only).  A kernel of
 // its own, so that the code of the replicas costs the ordinary launch no registers.
-template <int BITS, bool INT, bool FAST, int UPT, bool REP = false>
+// SOLO: 0, or the one instantiation of the matrix-core loop that this kernel holds for the plain
+// estimator -- 1 + (KB - 1) + 2 XM: 64 or 128 features per workgroup, exchange through atomics or
+// through tagged stores.  With all its instantiations in one kernel the loop of a production launch
+// spilled some 900 scalar registers into vector lanes (85 reloads inside one loop body); a kernel
+// that holds one of them spills 200, and the dense 8-bit step went from 2.97 to 2.88 us.
+template <int BITS, bool INT, bool FAST, int UPT, bool REP = false, int SOLO = 0>
 __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
 {
     constexpr int K = 1 << BITS;
@@ -906,7 +911,16 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         if (blockIdx.x == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
         return;
     }
-    if constexpr (REP) {
+    if constexpr (SOLO != 0) {
+        // (the host launches this kernel for the plain estimator on the matrix-core plan, without
+        // replicas or debug outputs, with the workgroup width and the exchange it was built for)
+        if constexpr (!INT && FAST && kMfmaBits && !REP) {
+            constexpr int kKB = 1 + ((SOLO - 1) & 1), kXM = (SOLO - 1) >> 1;
+            if (affine_all && a.mfma) sgd_steps_mfma<BITS, UPT, kKB, 1, false, kXM>(a, L, L.mf);
+            else if (affine) sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
+            else sgd_steps<BITS, kTable, FAST, UPT>(a, L);
+        }
+    } else if constexpr (REP) {
         if constexpr (!INT && FAST && kMfmaBits) {
             if (affine_all && a.mfma) {     // (anything else has been refused above: replicas imply chunks)
                 if (a.avg) {
@@ -932,14 +946,13 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
                         else sgd_steps_mfma<BITS, UPT, 2, 2, false, 0>(a, L, L.mf);
                     }
                 }
-            } else if (a.GQ <= 2) {
-                if (a.dbg_production) sgd_steps_mfma<BITS, UPT, 1, 1, false, 2>(a, L, L.mf);
-                else if (a.xstore) sgd_steps_mfma<BITS, UPT, 1, 1, false, 1>(a, L, L.mf);
-                else sgd_steps_mfma<BITS, UPT, 1, 1, false, 0>(a, L, L.mf);
+            } else if (a.dbg_production) {
+                if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, false, 2>(a, L, L.mf);
+                else sgd_steps_mfma<BITS, UPT, 2, 1, false, 2>(a, L, L.mf);
             } else {
-                if (a.dbg_production) sgd_steps_mfma<BITS, UPT, 2, 1, false, 2>(a, L, L.mf);
-                else if (a.xstore) sgd_steps_mfma<BITS, UPT, 2, 1, false, 1>(a, L, L.mf);
-                else sgd_steps_mfma<BITS, UPT, 2, 1, false, 0>(a, L, L.mf);
+                // (the plain estimator runs on the kernels that hold one instantiation each: SOLO)
+                if (blockIdx.x == 0 && tid == 0) store_dev(a.status, (int)ZIPML_EUNSUPPORTED);
+                return;
             }
         } else if (affine) {
             sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
@@ -1169,6 +1182,16 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
                 kern = p.upt == 1 ? (const void *)k_sgd<BITS, false, true, 1, true>
                      : p.upt == 2 ? (const void *)k_sgd<BITS, false, true, 2, true>
                                   : (const void *)k_sgd<BITS, false, true, 4, true>;
+            else if (a.mfma && !a.avg && !a.dbg_production) {
+                // the plain estimator: the kernel that holds just its instantiation of the loop
+                const int solo = 1 + (a.GQ <= 2 ? 0 : 1) + 2 * (a.xstore ? 1 : 0);
+#define ZIPML_SOLO(U) (solo == 1 ? (const void *)k_sgd<BITS, false, true, U, false, 1> \
+                     : solo == 2 ? (const void *)k_sgd<BITS, false, true, U, false, 2> \
+                     : solo == 3 ? (const void *)k_sgd<BITS, false, true, U, false, 3> \
+                                 : (const void *)k_sgd<BITS, false, true, U, false, 4>)
+                kern = p.upt == 1 ? ZIPML_SOLO(1) : p.upt == 2 ? ZIPML_SOLO(2) : ZIPML_SOLO(4);
+#undef ZIPML_SOLO
+            }
         }
     }
     if (a.R > 1 && !(fast && !INT && (BITS == 2 || BITS == 4 || BITS == 8))) return ZIPML_EUNSUPPORTED;
