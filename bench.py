@@ -480,7 +480,38 @@ def dense_extras(P, args, torch, zipml, timed):
                             "compact_GBps": read_c / (ms_c * 1e-3) / 1e9,
                             "packed_equivalent_GBps": nn * (2 * d * bits / 8 + 4) / (ms_c * 1e-3) / 1e9})
             del q1, q2, qc, bs, wss
-    return {"other_ms": other, "batch_sweep": sweep, "compact_record_epoch": compact}
+    # 2-bit codes at very large minibatches (random codes, evenly spaced levels, d=4096): the
+    # sample-owner kernel with its dot pass on the 4-bit floating-point matrix instruction against
+    # the integer kernel, at 1 and 4 GiB of codes per step
+    two_bit = []
+    if not args.batch:
+        d2 = 4096
+        lev2 = torch.zeros(d2, 4, dtype=torch.float32, device=dev)
+        lo2 = torch.full((d2,), -1.0, dtype=torch.float32, device=dev)
+        hi2 = torch.full((d2,), 1.0, dtype=torch.float32, device=dev)
+        zipml.levels(None, 64, d2, d2, 2, zipml.UNIFORM, zipml.RANGE_GIVEN, 0, lo2, hi2, lev2, None, P.ws)
+        for nn in (524288, 2097152):
+            q1 = torch.randint(0, 256, (zipml.packed_bytes(nn, d2, 2),), dtype=torch.uint8, device=dev)
+            q2 = torch.randint(0, 256, (zipml.packed_bytes(nn, d2, 2),), dtype=torch.uint8, device=dev)
+            bs = torch.randn(nn, device=dev)
+            wss = torch.zeros(zipml.workspace_bytes(nn, d2, 2, nn), dtype=torch.uint8, device=dev)
+            row = {"n": nn, "d": d2, "batch": nn}
+            try:
+                for tag, kn in (("integer_kernel", 2), ("fp4_dot_pass", -1)):
+                    zipml.debug_set(zipml.KNOB_ROWS_ITEM_BLOCKS, kn)
+                    xs = torch.zeros(d2, dtype=torch.float32, device=dev)
+                    ms = timed(lambda: zipml.sgd_epoch(q1, q2, lev2, bs, nn, d2, 2, xs, nn, 1e-6, wss), 5)
+                    gb = nn * (2 * d2 * 2 / 8 + 4) / (ms * 1e-3) / 1e9
+                    row[tag] = {"ms_per_epoch": ms, "GBps": gb, "frac_hbm_peak": gb / HBM_PEAK_GBS,
+                                "status": zipml.strerror(zipml.sgd_status(wss)) if zipml.sgd_status(wss) else "ok"}
+            except zipml.ZipmlError as e:
+                row["error"] = str(e)
+            finally:
+                zipml.debug_set(zipml.KNOB_ROWS_ITEM_BLOCKS, -1)
+            two_bit.append(row)
+            del q1, q2, bs, wss
+    return {"other_ms": other, "batch_sweep": sweep, "compact_record_epoch": compact,
+            "two_bit_large_minibatch": two_bit}
 
 
 if __name__ == "__main__":

@@ -301,7 +301,9 @@ int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t 
 #define ZIPML_KNOB_CHUNK_SAMPLES     2  /* chunk size of minibatches taken in chunks                    */
 #define ZIPML_KNOB_MAX_REPLICAS      3  /* most replicas of the workgroups that share the chunks        */
 #define ZIPML_KNOB_ROWS_MIN_BATCH    4  /* smallest minibatch for the sample-owner kernel (>= 16384)    */
-#define ZIPML_KNOB_ROWS_ITEM_BLOCKS  5  /* 64-feature blocks per wave and item of that kernel           */
+#define ZIPML_KNOB_ROWS_ITEM_BLOCKS  5  /* 64-feature blocks per wave and item of that kernel (at 2 bits any
+                                            value keeps the integer kernel; 101, 102: the 4-bit floating-point
+                                            dot pass with tiles of 64, 128 samples)                      */
 #define ZIPML_KNOB_ROWS_WORKGROUPS   6  /* its number of workgroups                                     */
 #define ZIPML_KNOB_SPIN_LIMIT        7  /* polls before a device-wide wait gives up (0: at once)        */
 #define ZIPML_KNOB_HOST_DP           8  /* 1: the dynamic program of zipml_levels runs on the host     */

@@ -218,6 +218,7 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ p, uint32
 #include "zipml_sgd_mfma.h"
 #include "zipml_sgd_rows.h"
 #include "zipml_sgd_rows_compact.h"
+#include "zipml_sgd_rows_fp4.h"
 namespace zipml {
 
 // ---- inner loops over the 32 codes of a unit (v: 32 wave-uniform fp32/int32 values in LDS) ----
@@ -1278,7 +1279,29 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
         if constexpr (BITS == 4) kern = (const void *)k_sgd_rows<4, 1, true>;
         if constexpr (BITS == 2) kern = kpi == 2 ? (const void *)k_sgd_rows<2, 2, true> : (const void *)k_sgd_rows<2, 1, true>;
     }
-    if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
+    size_t lds_bytes = shmem;
+    if constexpr (BITS == 2) {
+        // 2-bit codes, plain estimator: the dot pass on the 4-bit floating-point matrix instruction
+        // (zipml_sgd_rows_fp4.h) where its digits fit in LDS; an explicit item size keeps the
+        // integer kernel (development, A/B)
+        int cus = 0, lds = 0;
+        if (int rc = device_limits(cus, lds)) return rc;
+        const long long item_knob = knob(ZIPML_KNOB_ROWS_ITEM_BLOCKS);
+        const int tm_forced = item_knob == 101 || item_knob == 102 ? (int)item_knob - 100 : 0;   // development, tests
+        if (!r.p1s && (item_knob < 1 || tm_forced)) {
+            // the larger tile (128 or 64 samples) that divides the minibatch, leaves every workgroup
+            // at least two tiles and fits in LDS
+            for (int tm = 2; tm >= 1; tm >>= 1) {
+                if (tm_forced && tm != tm_forced) continue;
+                if (r.B % (64 * tm) != 0 || (!tm_forced && tm > 1 && r.B / (64 * tm) < 2 * (int64_t)wgs)) continue;
+                if (rows_fp4_lds_bytes(r.NKB, tm) > (size_t)lds) continue;
+                kern = tm == 2 ? (const void *)k_sgd_rows_fp4<2> : (const void *)k_sgd_rows_fp4<1>;
+                lds_bytes = rows_fp4_lds_bytes(r.NKB, tm);
+                break;
+            }
+        }
+    }
+    if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)))
         return ZIPML_ELAUNCH;
     // status word, barrier counter, evenly-spaced check (no exchange words to clear)
     hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, r.status, r.sync,
@@ -1286,7 +1309,7 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
                        const_cast<float *>(r.mid), nfeat, BITS == 8 ? 128.0f : 0.0f);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     void *params[] = {&r};
-    if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(wgs), dim3(kThreads), params, (unsigned)shmem, s)))
+    if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(wgs), dim3(kThreads), params, (unsigned)lds_bytes, s)))
         return ZIPML_ELAUNCH;
     return ZIPML_OK;
 }

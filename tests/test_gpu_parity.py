@@ -798,6 +798,45 @@ def test_symmetrised_estimator_refusals():
     assert e.value.code == zipml.EUNSUPPORTED
 
 
+@pytest.mark.parametrize("name,kw,batch,lr", [
+    ("d96_full_batch", dict(n=32768, d=96), 32768, 0.2),        # one block of 128 features, a quarter of it padding
+    ("d1100_b16384", dict(n=32768, d=1100), 16384, 0.1),        # 9 blocks: some waves have two; 35 feature groups
+    ("d2100_b16384", dict(n=16384, d=2100), 16384, 0.05),       # 33 blocks of 64: the last block of 128 is half empty
+])
+def test_two_bit_sample_owners_with_the_dot_pass_in_fp4(name, kw, batch, lr, knobs):
+    """2-bit codes at very large minibatches: the dot pass on the 4-bit floating-point matrix
+    instruction (codes as E2M1 numbers, y in base-4 digits).  Same integers as the integer kernel:
+    the same model bit for bit, and both match the oracle."""
+    say("fp4 dot pass", name)
+    knobs(zipml.KNOB_ROWS_MIN_BATCH, 16384)
+    w = synth.lowbit(batch=batch, **kw)
+    A, b = w.full()
+    L = _levels_for(w, A)
+    p = GpuProblem(A, b, w.bits, batch)
+    p.set_levels(L)
+    p.quantize(19, 0)
+    c1, c2 = oracle.quantize(A, L, w.bits, 19, 0)
+    x_ref = np.zeros(w.d, np.float32)
+    x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    x_int = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    x128 = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    for ep in range(4):
+        x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, batch, lr)
+        knobs(zipml.KNOB_ROWS_ITEM_BLOCKS, -1)                # automatic: here tiles of 64 samples
+        p.epoch(x, lr)
+        knobs(zipml.KNOB_ROWS_ITEM_BLOCKS, 2)                 # an explicit item size: the integer kernel
+        p.epoch(x_int, lr)
+        knobs(zipml.KNOB_ROWS_ITEM_BLOCKS, 102)               # tiles of 128 samples (automatic from 32,768 x CUs / 128 samples on)
+        p.epoch(x128, lr)
+        err = rel_l2(x.cpu().numpy(), x_ref)
+        err128 = rel_l2(x128.cpu().numpy(), x_ref)
+        say(f"  epoch {ep}: rel L2 {err:.2e}, with tiles of 128 samples {err128:.2e}")
+        assert err <= TOL and max_abs_ok(x.cpu().numpy(), x_ref, TOL)
+        assert err128 <= TOL and max_abs_ok(x128.cpu().numpy(), x_ref, TOL)
+        assert torch.equal(x, x_int)      # (same tiles, same sums; larger tiles add in another order)
+    assert float(x.abs().max()) > 0.0
+
+
 # ------------------------------------------------------------------ epoch on the compact record
 @pytest.mark.parametrize("name,kw,lr", [
     ("d1000_b16384", dict(n=32768, d=1000, batch=16384), 0.05),    # 16 blocks of 64 features: two per wave
