@@ -929,6 +929,9 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
                         if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 2, true, 0>(a, L, L.mf);
                         else sgd_steps_mfma<BITS, UPT, 2, 2, true, 0>(a, L, L.mf);
                     }
+                } else if (a.xstore) {
+                    if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, true, 1>(a, L, L.mf);
+                    else sgd_steps_mfma<BITS, UPT, 2, 1, true, 1>(a, L, L.mf);
                 } else {
                     if (a.GQ <= 2) sgd_steps_mfma<BITS, UPT, 1, 1, true, 0>(a, L, L.mf);
                     else sgd_steps_mfma<BITS, UPT, 2, 1, true, 0>(a, L, L.mf);
@@ -1209,7 +1212,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
                        INT && !stepwise ? reinterpret_cast<uint64_t *>(a.nrm) : (uint64_t *)nullptr,
                        INT && !stepwise ? 8 * kNormSlots : 0,
                        a.xstore ? a.xpart : (uint64_t *)nullptr,
-                       a.xstore ? (int64_t)2 * (a.W + 1) * a.xrow : (int64_t)0);
+                       a.xstore ? (int64_t)a.R * 2 * (a.W + 1) * a.xrow : (int64_t)0);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     if (!stepwise) {
         a.persistent = 1;
@@ -1536,19 +1539,21 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
             return ZIPML_EWORKSPACE;
     }
     a.gbuf = (float *)(ws + Workspace::sgd_bytes(batch));
-    // Exchange through tagged stores: the matrix-core loop of one launch without replicas, all
-    // eight waves at work, and enough (workgroups x samples) for the atomics to be what a step
-    // waits for.
+    // Exchange through tagged stores: the matrix-core loop with all eight waves at work and enough
+    // (workgroups x samples) for the atomics to be what a step waits for.  Replicas have rows and
+    // results of their own (the plain estimator only), sized for their chunk, where the room that
+    // zipml_workspace_bytes provides for one launch of this minibatch holds them all.
     {
         long long xmin = knob(ZIPML_KNOB_STORE_EXCHANGE_MIN);
         if (xmin < 0) xmin = 32768;
         const bool all_waves = !(p.upt == 1 && micro <= 256 && p.GQ <= 2);
-        a.xstore = (a.mfma && replicas == 1 && all_waves && p.W > 1 && !production &&
+        a.xstore = (a.mfma && (replicas == 1 || !avg) && all_waves && p.W > 1 && !production &&
                     (long long)p.W * micro >= xmin) ? 1 : 0;
-        a.xrow = (int)Workspace::xchg_row_words(batch);
+        a.xrow = (int)Workspace::xchg_row_words(replicas > 1 ? micro : batch);
         a.xpart = (uint64_t *)(ws + Workspace::xchg_offset(d, batch));
         a.xres = a.xpart + (size_t)2 * p.W * a.xrow;
         if (a.xstore && (p.W > 256 || NCwords_ok(avg ? 2 : 1, micro, a.xrow) == false)) a.xstore = 0;
+        if (a.xstore && (size_t)replicas * 2 * (p.W + 1) * a.xrow * 8 > Workspace::xchg_bytes(d, batch)) a.xstore = 0;
     }
     a.dbg_m = dbg_m; a.dbg_acc = dbg_acc; a.dbg_r = dbg_r; a.dbg_g = dbg_g; a.dbg_gq = dbg_gq;
     switch (bits) {

@@ -54,7 +54,8 @@ constexpr int kRefresh = 16;   // steps between exact refreshes of the magnitude
 //      polls its piece in every row, adds the W values (integers: exact, any order) and stores the
 //      sums, tagged the same way, to res[u & 1][word];
 //   3. every thread polls the result words of its own samples.
-// Two buffers alternate.  A workgroup writes row words of step u only after it has finished step
+// Two buffers alternate (per replica, when the chunks of a minibatch are shared out: a replica's
+// exchanges are its own).  A workgroup writes row words of step u only after it has finished step
 // u-1, for which it needed results that every reducer published after its reads of step u-2; a
 // reducer writes results of step u after it has seen every workgroup's words of step u, which
 // each wrote after reading the results of step u-2.  So no word is overwritten while someone may
@@ -124,9 +125,11 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     const int C = a.chunks / R;
     const int64_t u_begin = a.step0 * C, u_end = (a.step0 + a.nsteps) * C;
     const int nwords = NC * B + 2;                      // exchange words of a chunk: sums, 2 side words
-    const bool xstore = XM == 1 && !REP && nw == kWaves;   // exchange through tagged stores (see above; all waves take part)
+    const bool xstore = XM == 1 && nw == kWaves;        // exchange through tagged stores (see above; all waves take part)
     const int xrow = a.xrow;                            // words per row of part[][] and of res[] (multiple of kPiece)
     const int npieces = (nwords + kPiece - 1) / kPiece;
+    // (every replica has its own rows and results: [2][W][xrow] and [2][xrow] words)
+    uint64_t *const xbase = a.xpart + (size_t)rep * ((size_t)2 * (W + 1) * xrow);
     const int clr_per = (nwords + W - 1) / W;           // words of a later step that this workgroup clears
     const int clr_lo = w * clr_per, clr_hi = clr_lo + clr_per < nwords ? clr_lo + clr_per : nwords;
     uint64_t *const acc_base = a.acc + (size_t)rep * Workspace::kAccBuffers * a.acc_words;
@@ -335,8 +338,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         const bool first = chunk == 0, last = chunk == C - 1;
         uint64_t *const acc = acc_base + (size_t)(u & 3) * a.acc_words;
         const uint32_t xtag = ((uint32_t)(u + 1) & 0x7FFFu) | 0x8000u;
-        uint64_t *const xpart = a.xpart + (size_t)(u & 1) * ((size_t)W * xrow);
-        uint64_t *const xres = a.xres + (size_t)(u & 1) * xrow;
+        uint64_t *const xpart = xbase + (size_t)(u & 1) * ((size_t)W * xrow);
+        uint64_t *const xres = xbase + (size_t)2 * W * xrow + (size_t)(u & 1) * xrow;
         const bool side_step = first && (t % kRefresh) == 0;   // bounds travel with this exchange
         const bool side_next = last && ((t + 1) % kRefresh) == 0;
         ZIPML_TICK(7);
@@ -363,7 +366,7 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
         auto dot_and_publish = [&](int64_t uu, bool pub_side) __attribute__((always_inline)) {
         uint64_t *const pub_acc = acc_base + (size_t)(uu & 3) * a.acc_words;
         const uint32_t pub_xtag = ((uint32_t)(uu + 1) & 0x7FFFu) | 0x8000u;
-        uint64_t *const pub_xmine = a.xpart + (size_t)(uu & 1) * ((size_t)W * xrow) + (size_t)w * xrow;
+        uint64_t *const pub_xmine = xbase + (size_t)(uu & 1) * ((size_t)W * xrow) + (size_t)w * xrow;
         ky_pub = ky;
         // ============ dot pass: one instruction per (16 samples, 64 features)
         {

@@ -489,6 +489,8 @@ def test_large_minibatches_taken_in_chunks(name, factory, kw, batch, lr):
     ("tomo4_b512", synth.tomo, dict(n=4096, d=1024, batch=512), 0.05, False),
     ("dense4_chunks_b4096", synth.dense8, dict(n=8192, d=1100, bits=4, batch=4096), 0.05, False),
     ("dense8_wide_b512_avg", synth.dense8, dict(n=4096, d=1100, batch=512), 1e-2, True),
+    ("dense8_b4096_replicas", synth.dense8, dict(n=8192, d=288, batch=4096), 0.1, False),   # rows and results per replica
+    ("tomo4_b2048_replicas", synth.tomo, dict(n=4096, d=2304, batch=2048), 0.05, False),
 ])
 def test_exchange_through_tagged_stores(name, factory, kw, lr, avg, knobs):
     """The matrix-core loop with the sums of a step exchanged through tagged stores and reducer
