@@ -19,50 +19,94 @@
 
 namespace zipml {
 
-// Order-preserving map float -> uint32 so that min/max can use integer atomics.
-__device__ __forceinline__ uint32_t f2key(float f)
+// Column minimum and maximum (Supp. A.3): one pass over the fp32 matrix.  The rows are split
+// into slabs; a thread takes V neighbouring features (one 16-byte load per row at V = 4) and the
+// rows of one slab, sixteen rows requested at a time with loads that no branch can skip (rows past
+// the slab repeat its last row), and stores its minima and maxima to the slab's own row of
+// part[slab][2][d]; k_range_final goes through the slabs.  (An earlier version sent every
+// thread's result to memory with atomics on order-preserving integer keys: 2 d slabs atomics,
+// which at the 22 per ns that the memory side takes were most of its time.)
+// A workgroup is TX threads across the features times 256 / TX slabs.
+// A value that compares false both ways (a NaN) is never taken over, unless it is a slab's first.
+constexpr int kRangeSlabsMax = 2048;
+inline int64_t range_slabs_max(int64_t d)
 {
-    const uint32_t b = __float_as_uint(f);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    const int64_t m = ((int64_t)1 << 18) / (d > 0 ? d : 1);      // (at most 2 MiB of partial results)
+    return m < 1 ? 1 : m > kRangeSlabsMax ? kRangeSlabsMax : m;
 }
-__device__ __forceinline__ float key2f(uint32_t k)
-{
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
-}
-
-__global__ void k_range_init(uint32_t *kmin, uint32_t *kmax, int64_t d)
-{
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j < d) { kmin[j] = 0xFFFFFFFFu; kmax[j] = 0u; }
-}
-
-// One thread per feature (consecutive lanes read consecutive floats of a row), a slab of rows per
-// blockIdx.y.
+template <int V>
 __global__ __launch_bounds__(256) void k_range_scan(const float *__restrict__ A, int64_t n,
                                                     int64_t d, int64_t lda, int64_t rows_per_slab,
-                                                    uint32_t *kmin, uint32_t *kmax)
+                                                    int64_t nslabs, int TX, float *__restrict__ part)
 {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= d) return;
-    const int64_t i0 = (int64_t)blockIdx.y * rows_per_slab;
-    const int64_t i1 = i0 + rows_per_slab < n ? i0 + rows_per_slab : n;
-    if (i0 >= i1) return;
-    float mn = A[i0 * lda + j], mx = mn;
-    for (int64_t i = i0 + 1; i < i1; ++i) {
-        const float v = A[i * lda + j];
-        mn = v < mn ? v : mn;
-        mx = v > mx ? v : mx;
+    const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+    const int64_t j = ((int64_t)blockIdx.x * TX + tx) * V;
+    const int64_t slab = (int64_t)blockIdx.y * (256 / TX) + ty;
+    if (j >= d || slab >= nslabs) return;
+    const int64_t i0 = slab * rows_per_slab;
+    const int64_t i1 = i0 + rows_per_slab < n ? i0 + rows_per_slab : n;     // (i0 < i1: the host sized the slabs so)
+    constexpr int U = V == 4 ? 16 : 8;
+    float mn[V], mx[V];
+    const float *col = A + j;
+#pragma unroll
+    for (int k = 0; k < V; ++k) mn[k] = mx[k] = col[i0 * lda + k];
+    for (int64_t i = i0; i < i1; i += U) {
+        float a[U][V];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float *src = col + (i + u < i1 ? i + u : i1 - 1) * lda;
+            if constexpr (V == 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(src);
+                a[u][0] = v.x; a[u][1] = v.y; a[u][2] = v.z; a[u][3] = v.w;
+            } else {
+                a[u][0] = *src;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                mn[k] = a[u][k] < mn[k] ? a[u][k] : mn[k];
+                mx[k] = a[u][k] > mx[k] ? a[u][k] : mx[k];
+            }
     }
-    atomicMin(kmin + j, f2key(mn));
-    atomicMax(kmax + j, f2key(mx));
+    float *dst = part + (size_t)slab * 2 * d + j;
+#pragma unroll
+    for (int k = 0; k < V; ++k) { dst[k] = mn[k]; dst[d + k] = mx[k]; }
 }
 
-__global__ void k_range_final(const uint32_t *kmin, const uint32_t *kmax, int64_t d, int symmetric,
-                              float *lo, float *hi)
+// 8 features x 32 lanes that share out the slabs; lane 0 of a feature goes through the lanes' results.
+__global__ __launch_bounds__(256) void k_range_final(const float *__restrict__ part, int64_t nslabs,
+                                                     int64_t d, int symmetric, float *lo, float *hi)
 {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= d) return;
-    float mn = key2f(kmin[j]), mx = key2f(kmax[j]);
+    __shared__ float smn[32][8], smx[32][8];
+    const int fx = threadIdx.x & 7, ly = threadIdx.x >> 3;
+    const int64_t j = (int64_t)blockIdx.x * 8 + fx;
+    const int64_t jc = j < d ? j : d - 1;
+    const int64_t k0 = ly < nslabs ? ly : 0;
+    float mn = part[(size_t)k0 * 2 * d + jc], mx = part[(size_t)k0 * 2 * d + d + jc];
+    for (int64_t k = ly + 32; k < nslabs; k += 32 * 8) {
+        float a[8], b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t kk = k + 32 * u < nslabs ? k + 32 * u : k0;
+            a[u] = part[(size_t)kk * 2 * d + jc];
+            b[u] = part[(size_t)kk * 2 * d + d + jc];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            mn = a[u] < mn ? a[u] : mn;
+            mx = b[u] > mx ? b[u] : mx;
+        }
+    }
+    smn[ly][fx] = mn;
+    smx[ly][fx] = mx;
+    __syncthreads();
+    if (ly != 0 || j >= d) return;
+    for (int q = 1; q < 32; ++q) {
+        mn = smn[q][fx] < mn ? smn[q][fx] : mn;
+        mx = smx[q][fx] > mx ? smx[q][fx] : mx;
+    }
     if (symmetric) {
         const float m = fabsf(mn) > fabsf(mx) ? fabsf(mn) : fabsf(mx);
         mn = -m;
@@ -86,98 +130,154 @@ __global__ void k_levels_uniform(const float *__restrict__ lo, const float *__re
     if (grid) grid[e] = (uint16_t)c;
 }
 
-__global__ void k_zero_f64(double *p, int64_t count)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = 0.0;
-}
-
 // Per-bin moments of the normalised values; hist is [d][M][3] fp64 (count, sum t, sum t^2).
 // One atomic per value and moment straight to memory ran at the rate the memory side takes
 // atomics (about 22 per ns: 18-28 ms for 65,536 x 2048 values).  Here a workgroup owns F
-// consecutive features -- as many as have their M bins in LDS, F a divisor of 256 -- and a slab
-// of rows (all rows when the blocks of features fill the device), adds into LDS, and sends its
-// bins to memory once at the end: 0.44 ms for the same matrix.  The counts are 32-bit integers
-// to save LDS; the two sums are fp64.
-__global__ __launch_bounds__(256) void k_hist(const float *__restrict__ A, int64_t n, int64_t d,
-                                              int64_t lda, int64_t rows_per_slab,
-                                              const float *__restrict__ lo,
-                                              const float *__restrict__ hi, int M, int F,
-                                              int direct, double *__restrict__ hist)
+// consecutive features -- as many as have their M bins in LDS, F a power of two up to 32 -- and
+// a slab of rows, adds into LDS, and stores its bins once at the end (k_hist_merge adds the slabs).
+// The counts are 32-bit integers to save LDS; the two sums are fp64: 20 bytes per bin, which is
+// exactly the 160 KiB of a compute unit for 32 features x 256 bins or 8 x 1024.
+//
+// What the kernel is bound by is the number of cache lines in flight, not bytes or arithmetic
+// (with every addition taken out it ran as long): a workgroup reads 4 F bytes of every row, the
+// memory pipeline moves whole 128-byte lines, so at F = 8 three quarters of every line in flight
+// are somebody else's features (and come from memory again when the workgroups that share a
+// line drift apart: 1.3 to 3.9 times the matrix was fetched).  Hence the largest F that fits,
+// and slabs of rows to fill the device instead of narrower blocks of features.
+// A workgroup has 1024 threads: its bins leave room for one workgroup per compute unit, and its
+// sixteen waves are all there is to hide the latency of the loads with.
+//
+// t = (a - lo) / (hi - lo) in fp64 decides the bin, floor(t M).  A division per value would be
+// most of the kernel's arithmetic, so a thread keeps r = 1 / w (a correctly rounded reciprocal,
+// one division per feature) and forms q = num r, then q + (num - q w) r with two fused
+// operations: the classical last step of a software division, which gives the correctly rounded
+// quotient from a correctly rounded reciprocal.  The bin does not rest on that: q is within 2^-51
+// of the quotient either way, so q M is within 4096 * 2^-51 < 1e-11 of t M, and wherever q M comes
+// closer than 1e-9 to an integer the value is divided for real.  (num == 0 gives exactly 0 both ways.)
+constexpr int kHistThreads = 1024;
+__device__ __forceinline__ void hist_add(float a, double l, double w, double rw, int M, double *st,
+                                         double *st2, uint32_t *cf)
+{
+    double t = 0.0;
+    int m = 0;
+    if (w > 0.0) {
+        const double num = (double)a - l;
+        double q = num * rw;
+        q = fma(fma(-q, w, num), rw, q);
+        q = q < 0.0 ? 0.0 : q;
+        q = q > 1.0 ? 1.0 : q;
+        const double u = q * (double)M;
+        int mi = (int)u;
+        const double fr = u - (double)mi;
+        if ((fr < 1e-9 || fr > 1.0 - 1e-9) && num != 0.0) {      // too close to an edge to trust
+            q = num / w;
+            q = q < 0.0 ? 0.0 : q;
+            q = q > 1.0 ? 1.0 : q;
+            mi = (int)(q * (double)M);
+        }
+        t = q;
+        m = mi > M - 1 ? M - 1 : mi;
+    }
+    atomicAdd(cf + m, 1u);
+    unsafeAtomicAdd(st + m, t);
+    unsafeAtomicAdd(st2 + m, t * t);
+}
+// V: features per thread (4: one 16-byte load per row, when F, d, lda and the address of A allow; 1).
+// out: hist itself (one slab), or the slabs' own copies [gridDim.y][d][M][3].
+template <int V>
+__global__ __launch_bounds__(kHistThreads) void k_hist(const float *__restrict__ A, int64_t n, int64_t d,
+                                                       int64_t lda, int64_t rows_per_slab,
+                                                       const float *__restrict__ lo,
+                                                       const float *__restrict__ hi, int M, int F,
+                                                       double *__restrict__ out)
 {
     extern __shared__ __align__(16) unsigned char hist_smem[];
-    double *sh = (double *)hist_smem;                        // [F][M][2] sum t, sum t^2
+    double *sh = (double *)hist_smem;                        // [F][2][M] sum t, sum t^2
     uint32_t *cnt = (uint32_t *)(sh + (size_t)F * M * 2);    // [F][M] counts (a slab has fewer than 2^32 rows)
     const int tid = threadIdx.x;
     // Blocks go round the 8 dies in turn, and neighbouring blocks of features share the cache
-    // lines of every row: block b takes features block (b % 8) * (gridDim.x / 8) + b / 8, so that
-    // neighbours run on one die at about the same time.  (gridDim.x is a multiple of 8; blocks
-    // past the last features block leave.)
+    // lines of every row (when F < 32): block b takes features block (b % 8) * (gridDim.x / 8) +
+    // b / 8, so that neighbours run on one die at about the same time.  (gridDim.x is a multiple
+    // of 8; blocks past the last features block leave.)
     const int64_t fb = (int64_t)(blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
     const int64_t j0 = fb * F;
     if (j0 >= d) return;
     const int nf = (int)(d - j0 < F ? d - j0 : F);
     const int64_t i0 = (int64_t)blockIdx.y * rows_per_slab;
     const int64_t i1 = i0 + rows_per_slab < n ? i0 + rows_per_slab : n;
-    for (int e = tid; e < nf * M * 2; e += 256) sh[e] = 0.0;
-    for (int e = tid; e < nf * M; e += 256) cnt[e] = 0u;
+    for (int e = tid; e < nf * M * 2; e += kHistThreads) sh[e] = 0.0;
+    for (int e = tid; e < nf * M; e += kHistThreads) cnt[e] = 0u;
     __syncthreads();
-    // F divides 256: thread t keeps feature t % F for good (its range in registers) and takes the
-    // rows t / F, t / F + 256 / F, ...  Sixteen values are requested before the first is used, with
-    // loads that no branch can skip (rows past the slab repeat its last row and are not counted):
-    // a load behind a branch makes the compiler wait for it on the spot, and one workgroup per
-    // compute unit has nothing else to hide that latency with.  Nothing in the loop reads LDS, so
-    // the additions are never waited for.
-    const int f = tid % F;
-    const bool live_col = f < nf;
-    if (i0 < i1 && live_col) {
-        constexpr int U = 16;
-        const int rows_step = 256 / F;
-        const double l = (double)lo[j0 + f], w = (double)hi[j0 + f] - (double)lo[j0 + f];
+    // F / V threads share a row: thread t keeps the features V (t % (F / V)) ... + V - 1 for good
+    // (their ranges in registers) and takes the rows t / (F / V), + 1024 / (F / V), ...  All values
+    // of a round are requested before the first is used, with loads that no branch can skip (rows
+    // past the slab repeat its last row and are not counted): a load behind a branch makes the
+    // compiler wait for it on the spot.  Nothing in the loop reads LDS, so the additions are never
+    // waited for.
+    const int tpr = F / V;
+    const int f = (tid % tpr) * V;
+    if (i0 < i1 && f < nf) {       // (V == 4: d is a multiple of 4, so the four features live or die together)
+        constexpr int U = V == 4 ? 8 : 16;
+        const int rows_step = kHistThreads / tpr;
+        double l[V], w[V], rw[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            l[k] = (double)lo[j0 + f + k];
+            w[k] = (double)hi[j0 + f + k] - l[k];
+            rw[k] = w[k] > 0.0 ? 1.0 / w[k] : 0.0;
+        }
         const float *col = A + j0 + f;
-        double *hf = sh + (size_t)f * M * 2;
-        uint32_t *cf = cnt + (size_t)f * M;
-        for (int64_t i = i0 + tid / F; i < i1; i += (int64_t)U * rows_step) {
-            float a[U];
+        for (int64_t i = i0 + tid / tpr; i < i1; i += (int64_t)U * rows_step) {
+            float a[U][V];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t r = i + (int64_t)u * rows_step;
-                a[u] = col[(r < i1 ? r : i1 - 1) * lda];
+                const float *src = col + (r < i1 ? r : i1 - 1) * lda;
+                if constexpr (V == 4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(src);
+                    a[u][0] = v.x; a[u][1] = v.y; a[u][2] = v.z; a[u][3] = v.w;
+                } else {
+                    a[u][0] = *src;
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (i + (int64_t)u * rows_step < i1) {
-                    double t = 0.0;
-                    if (w > 0.0) {
-                        t = ((double)a[u] - l) / w;
-                        t = t < 0.0 ? 0.0 : t;
-                        t = t > 1.0 ? 1.0 : t;
-                    }
-                    int m = (int)(t * (double)M);
-                    if (m > M - 1) m = M - 1;
-                    atomicAdd(cf + m, 1u);
-                    unsafeAtomicAdd(hf + 2 * m, t);
-                    unsafeAtomicAdd(hf + 2 * m + 1, t * t);
+#pragma unroll
+                    for (int k = 0; k < V; ++k)
+                        hist_add(a[u][k], l[k], w[k], rw[k], M, sh + (size_t)(f + k) * M * 2,
+                                 sh + (size_t)(f + k) * M * 2 + M, cnt + (size_t)(f + k) * M);
                 }
             }
         }
     }
     __syncthreads();
-    double *out = hist + (size_t)j0 * M * 3;
-    for (int e = tid; e < nf * M * 3; e += 256) {
-        const int bin = e / 3, c = e % 3;
-        const double v = c == 0 ? (double)cnt[bin] : sh[bin * 2 + c - 1];
-        if (direct) out[e] = v;                      // the only slab: nobody else adds to these bins
-        else if (v != 0.0) unsafeAtomicAdd(out + e, v);
+    double *dst = out + (size_t)blockIdx.y * ((size_t)d * M * 3) + (size_t)j0 * M * 3;
+    for (int e = tid; e < nf * M * 3; e += kHistThreads) {
+        const int bin = e / 3, c = e % 3, ff = bin / M, m = bin % M;
+        dst[e] = c == 0 ? (double)cnt[bin] : sh[((size_t)ff * 2 + (c - 1)) * M + m];
     }
 }
-// Features per workgroup of k_hist and its LDS bytes.
+// hist = the slabs' copies added up in slab order
+__global__ void k_hist_merge(const double *__restrict__ part, int slabs, int64_t count,
+                             double *__restrict__ hist)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    double v = part[i];
+    for (int k = 1; k < slabs; ++k) v += part[(size_t)k * count + i];
+    hist[i] = v;
+}
+// Features per workgroup of k_hist (a power of two, at most 32) and its LDS bytes.
+inline size_t hist_lds_bytes(int M, int F) { return (size_t)F * (size_t)M * 20; }
 inline int hist_features(int M, int lds_limit)
 {
-    const int f = (int)(((size_t)lds_limit - 1024) / ((size_t)M * 20 + 16));
-    return f < 1 ? 1 : f > 32 ? 32 : f;
+    int f = 1;
+    while (f < 32 && hist_lds_bytes(M, 2 * f) <= (size_t)lds_limit) f *= 2;
+    return f;
 }
-inline size_t hist_lds_bytes(int M, int F) { return (size_t)F * ((size_t)M * 20 + 16); }
+// Room for the slabs' copies of the bin moments (beyond it, fewer slabs).
+constexpr size_t kHistSlabBytes = (size_t)64 << 20;
 
 // ---------------------------------------------------------------------------------------------
 // Host dynamic program for one feature: s intervals over the M+1 bin edges m/M.
@@ -437,14 +537,17 @@ static double dp_one_feature(const double *mom, int M, int s, std::vector<double
     return total;
 }
 
+// the slabs' minima and maxima of the range scan
+static size_t range_bytes(int64_t d) { return (size_t)round_up(d * 8 * range_slabs_max(d), 256); }
 static size_t levels_workspace_bytes(int64_t d, int n_candidates)
 {
-    size_t keys = (size_t)round_up(d * 8, 256);
+    size_t keys = range_bytes(d);
     size_t hist = (size_t)d * (size_t)n_candidates * 3 * sizeof(double);
     size_t objective = (size_t)d * sizeof(double);     // per-feature value of the dynamic program
     // candidates left by the greedy search: bin edges [d][n_candidates + 1] uint16, their number [d]
     size_t greedy = n_candidates > 0 ? (size_t)round_up(d * ((int64_t)n_candidates + 1) * 2, 256) + (size_t)d * 4 : 0;
-    return keys + hist + objective + greedy;
+    size_t slabs = n_candidates > 0 ? kHistSlabBytes : 0;    // the slabs' copies of the bin moments
+    return (size_t)round_up((int64_t)(keys + hist + objective + greedy), 256) + slabs;
 }
 
 }  // namespace zipml
@@ -483,18 +586,25 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
     if (need_data && (!workspace_dev || workspace_bytes < need || !aligned16(workspace_dev)))
         return ZIPML_EWORKSPACE;
     hipStream_t s = entry_stream(stream);
-    const unsigned cb = (unsigned)((d + 255) / 256);
-    // rows are split into slabs so that the scan fills the device
-    int64_t slabs = std::max<int64_t>(1, std::min<int64_t>(n / 64 + 1, 4096 / cb + 1));
-    const int64_t rows_per_slab = n > 0 ? (n + slabs - 1) / slabs : 1;
-    slabs = n > 0 ? (n + rows_per_slab - 1) / rows_per_slab : 1;
 
     if (!(flags & ZIPML_RANGE_GIVEN)) {
-        uint32_t *kmin = (uint32_t *)workspace_dev, *kmax = kmin + d;
-        hipLaunchKernelGGL(k_range_init, dim3(cb), dim3(256), 0, s, kmin, kmax, d);
-        hipLaunchKernelGGL(k_range_scan, dim3(cb, (unsigned)slabs), dim3(256), 0, s, A_dev, n, d, lda,
-                           rows_per_slab, kmin, kmax);
-        hipLaunchKernelGGL(k_range_final, dim3(cb), dim3(256), 0, s, kmin, kmax, d,
+        // 16-byte loads when every row segment of a thread is aligned and whole
+        const bool vec4 = d % 4 == 0 && lda % 4 == 0 && ((uintptr_t)A_dev & 15) == 0;
+        const int64_t ncg = vec4 ? d / 4 : d;                  // threads across a row
+        int TX = 256;
+        while (TX > 8 && TX / 2 >= ncg) TX /= 2;
+        // slabs of rows: enough threads to fill the device, at least 16 rows each
+        int64_t slabs = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>((n + 15) / 16, range_slabs_max(d)),
+                                                               (int64_t)262144 / ncg + 1));
+        const int64_t rows_per_slab = (n + slabs - 1) / slabs;
+        slabs = (n + rows_per_slab - 1) / rows_per_slab;
+        float *part = (float *)workspace_dev;
+        const dim3 grid((unsigned)((ncg + TX - 1) / TX), (unsigned)((slabs + 256 / TX - 1) / (256 / TX)));
+        if (vec4)
+            hipLaunchKernelGGL(k_range_scan<4>, grid, dim3(256), 0, s, A_dev, n, d, lda, rows_per_slab, slabs, TX, part);
+        else
+            hipLaunchKernelGGL(k_range_scan<1>, grid, dim3(256), 0, s, A_dev, n, d, lda, rows_per_slab, slabs, TX, part);
+        hipLaunchKernelGGL(k_range_final, dim3((unsigned)((d + 7) / 8)), dim3(256), 0, s, part, slabs, d,
                            (flags & ZIPML_SYMMETRIC) ? 1 : 0, lo_dev, hi_dev);
         if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     }
@@ -507,42 +617,50 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
 
     // ---- OPTIMAL / GREEDY: bin moments on the device, then the dynamic program (device or host, below)
     const int M = n_candidates, sI = K - 1;
-    double *hist_dev = (double *)((unsigned char *)workspace_dev + round_up(d * 8, 256));
+    double *hist_dev = (double *)((unsigned char *)workspace_dev + range_bytes(d));
     const int64_t hcount = d * (int64_t)M * 3;
-    hipLaunchKernelGGL(k_zero_f64, dim3((unsigned)((hcount + 255) / 256)), dim3(256), 0, s, hist_dev,
-                       hcount);
     int lds_limit = 0, dev = 0;
     if (HIP_FAILED(hipGetDevice(&dev)) ||
         HIP_FAILED(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev)))
         return ZIPML_ELAUNCH;
     {
-        // Blocks of F features, each with all rows when that fills the device (no additions in
-        // memory at all then: with slabs, the workgroups' additions of their bins to memory cost
-        // more than the scan); F is the largest number of features that keeps the number of
-        // rounds of workgroups times F smallest.  Few features: slabs of rows as well.
+        // Blocks of F features, F the most that fit in LDS (whole cache lines at 32), times slabs
+        // of rows: as many as make the rounds of workgroups come out even, and as have room for
+        // their copies of the bin moments, which k_hist_merge adds up.
         int cus = 0;
         if (HIP_FAILED(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))) return ZIPML_ELAUNCH;
-        const int Fmax = hist_features(M, lds_limit);
-        int F = 1;
-        int64_t best = -1;
-        for (int f = 1; f <= Fmax; f *= 2) {      // (F divides 256)
-            const int64_t rounds = ((d + f - 1) / f + cus - 1) / cus;
-            if (best < 0 || rounds * f <= best) { best = rounds * f; F = f; }
-        }
+        int F = hist_features(M, lds_limit);
         // development override: a power of two that fits
-        if (const long long v = knob(ZIPML_KNOB_HIST_FEATURES); v >= 1 && v <= Fmax && (v & (v - 1)) == 0) F = (int)v;
+        if (const long long v = knob(ZIPML_KNOB_HIST_FEATURES); v >= 1 && v <= F && (v & (v - 1)) == 0) F = (int)v;
         const size_t hl = hist_lds_bytes(M, F);
         if (hl > (size_t)lds_limit) return ZIPML_EUNSUPPORTED;
         const int64_t fblocks = (d + F - 1) / F;
-        int64_t hs = fblocks >= cus ? 1 : std::max<int64_t>(1, std::min<int64_t>((n + 255) / 256, (2 * cus + fblocks - 1) / fblocks));
+        const int64_t per_cu = std::min<int64_t>(2, (int64_t)lds_limit / (int64_t)hl);   // (2048 threads)
+        const int64_t room = (int64_t)cus * per_cu;
+        const int64_t hs_max = std::min<int64_t>(std::min<int64_t>(64, (n + 1023) / 1024),
+                                                 (int64_t)(kHistSlabBytes / ((size_t)hcount * 8)));
+        int64_t hs = 1;
+        double best = 0.0;
+        for (int64_t c = 1; c <= std::max<int64_t>(1, hs_max); ++c) {
+            const double cost = (double)((fblocks * c + room - 1) / room) / (double)c + 0.002 * (double)c;
+            if (c == 1 || cost < best) { best = cost; hs = c; }
+        }
         const int64_t hrows = (n + hs - 1) / hs;
         hs = (n + hrows - 1) / hrows;
-        if (fblocks > 0x7fffffff || hs > 65535) return ZIPML_EINVAL;
-        if (HIP_FAILED(hipFuncSetAttribute((const void *)k_hist, hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (fblocks > 0x7fffffff) return ZIPML_EINVAL;
+        double *slabs_dev = (double *)((unsigned char *)workspace_dev +
+                                       round_up((int64_t)(levels_workspace_bytes(d, M) - kHistSlabBytes), 256));
+        // 16-byte loads when every row segment of a thread is aligned and whole
+        const bool vec4 = F % 4 == 0 && d % 4 == 0 && lda % 4 == 0 && ((uintptr_t)A_dev & 15) == 0;
+        auto *kern = vec4 ? k_hist<4> : k_hist<1>;
+        if (HIP_FAILED(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)hl)))
             return ZIPML_ELAUNCH;
-        hipLaunchKernelGGL(k_hist, dim3((unsigned)round_up(fblocks, 8), (unsigned)hs), dim3(256), hl, s, A_dev, n, d, lda,
-                           hrows, lo_dev, hi_dev, M, F, hs == 1 ? 1 : 0, hist_dev);
+        hipLaunchKernelGGL(kern, dim3((unsigned)round_up(fblocks, 8), (unsigned)hs), dim3(kHistThreads), hl, s, A_dev, n, d, lda,
+                           hrows, lo_dev, hi_dev, M, F, hs == 1 ? hist_dev : slabs_dev);
+        if (hs > 1)
+            hipLaunchKernelGGL(k_hist_merge, dim3((unsigned)((hcount + 255) / 256)), dim3(256), 0, s, slabs_dev,
+                               (int)hs, hcount, hist_dev);
         if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     }
 
