@@ -70,7 +70,8 @@ size_t zipml_packed_bytes(int64_t n, int64_t d, int bits);
 
 /* Bytes of device workspace that zipml_levels, zipml_sgd_epoch, zipml_debug_step and zipml_loss
  * need for a problem of this shape (one buffer serves all of them, one call at a time).
- * n_candidates may be 0 if neither ZIPML_OPTIMAL nor ZIPML_GREEDY is used. */
+ * n_candidates may be 0 if neither ZIPML_OPTIMAL nor ZIPML_GREEDY is used (with it, the size
+ * includes the bin moments, 24 d n_candidates bytes, and 64 MiB for partial copies of them). */
 size_t zipml_workspace_bytes(int64_t n, int64_t d, int bits, int64_t batch, int n_candidates);
 
 /* Per-feature quantisation levels.
