@@ -130,10 +130,10 @@ def test_greedy_levels_bit_exact_on_dyadic_data():
     assert np.array_equal(p.levels.cpu().numpy(), L)
     assert np.isclose(mv, mv_ref, rtol=1e-12)      # (the mean over 2100 features is summed on the host)
     # The bin moments are gathered in one of two ways: many features -> a workgroup has all rows of
-    # its features and stores its bins; few features -> slabs of rows, added up in memory.  On this
-    # data both give the same moments exactly, so 300 features at once (first way: at 4096 bins one
-    # feature per workgroup) must get the levels that slices of 40 of them get (second way, the one
-    # compared with the oracle above).
+    # its features and stores its bins; few features -> slabs of rows, each with its own copy of the
+    # bins, added up afterwards.  On this data both give the same moments exactly, so 300 features at
+    # once (first way: at 4096 bins two features per workgroup) must get the levels that slices of
+    # 40 of them get (second way, the one compared with the oracle above).
     n3, d3, M3 = 2048, 300, 4096
     A3 = (rng.beta(0.7, 2.0, (n3, d3)) * 1024).round().astype(np.float32) / 1024
     z3, o3 = np.zeros(d3, np.float32), np.ones(d3, np.float32)
@@ -158,6 +158,47 @@ def test_greedy_levels_bit_exact_on_dyadic_data():
     with pytest.raises(zipml.ZipmlError) as e:
         p.make_levels(zipml.GREEDY, 0, lo=np.zeros(d), hi=np.ones(d), n_candidates=2048)
     assert e.value.code == zipml.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("n,d,pad,M", [(5000, 40, 0, 256), (5000, 42, 0, 256), (9000, 24, 3, 1024),
+                                        (3000, 132, 4, 64), (70000, 8, 0, 128), (1500, 1, 0, 2048)],
+                         ids=["d40", "d42_scalar_loads", "unaligned_rows", "padded_rows", "tall", "one_feature"])
+def test_column_statistics_in_every_decomposition(n, d, pad, M, knobs):
+    """Ranges (Supp. A.3) and bin moments (Sec. 3.2) are gathered by blocks of features x slabs of
+    rows, with 16-byte or 4-byte loads depending on alignment, the number of features per
+    workgroup depending on the bins that fit in LDS.  On values that are multiples of 2^-10 inside
+    a range of width 1 the moments are exact in any order -- and every value sits exactly on a bin
+    edge or at a fixed place inside a bin -- so ranges, levels, grid indices and objective must be
+    the oracle's bit for bit, whatever the decomposition (features per workgroup forced to 1, 2,
+    4 and the default; rows with and without padding)."""
+    say("column statistics", n, d, pad, M)
+    rng = np.random.default_rng(11)
+    t = rng.beta(0.6, 2.5, (n, d))
+    t[0, :] = 0.0
+    t[1, :] = 1.0                                          # every column spans [0, 1] exactly
+    A = (np.round(t * 1024) / 1024).astype(np.float32) + np.float32(0.25)    # ranges [0.25, 1.25]
+    lda = d + pad
+    Ap = np.full((n, lda), np.float32(99.0), np.float32)
+    Ap[:, :d] = A
+    A_dev = dev(Ap)
+    bits = 3
+    lo_ref, hi_ref = oracle.col_range(A)
+    assert np.all(lo_ref == np.float32(0.25)) and np.all(hi_ref == np.float32(1.25))
+    hist = oracle.hist_moments(A, lo_ref, hi_ref, M)
+    L, G, mv_ref = oracle.levels_optimal(hist, lo_ref, hi_ref, bits)
+    ws = torch.zeros(zipml.workspace_bytes(n, d, bits, 32, M), dtype=torch.uint8, device=DEV)
+    for feats in (-1, 1, 2, 4):
+        knobs(zipml.KNOB_HIST_FEATURES, feats)
+        lo = torch.zeros(d, device=DEV)
+        hi = torch.zeros(d, device=DEV)
+        lev = torch.zeros(d, 1 << bits, device=DEV)
+        grid = torch.zeros(d, 1 << bits, dtype=torch.int16, device=DEV)
+        mv = zipml.levels(A_dev, n, d, lda, bits, zipml.OPTIMAL, 0, M, lo, hi, lev, grid, ws, True)
+        assert np.array_equal(lo.cpu().numpy(), lo_ref) and np.array_equal(hi.cpu().numpy(), hi_ref)
+        assert np.array_equal(grid.cpu().numpy().view(np.uint16), G), feats
+        assert np.array_equal(lev.cpu().numpy(), L), feats
+        assert np.isclose(mv, mv_ref, rtol=1e-12), feats
+    knobs(zipml.KNOB_HIST_FEATURES, -1)
 
 
 def test_greedy_levels_on_float_data():
