@@ -175,7 +175,12 @@ int zipml_sgd_epoch_compact(void *stream, const void *compact_dev, const float *
  * own samples instead of features); otherwise ZIPML_EUNSUPPORTED, which for level tables that
  * turn out not to be evenly spaced arrives through zipml_sgd_status with x_dev left untouched.
  * The call is asynchronous; a failed grid-wide wait is reported by zipml_sgd_status (ZIPML_ETIMEOUT):
- * the kernel then still runs to its end, and x_dev holds undefined values afterwards. */
+ * the kernel then still runs to its end, and x_dev holds undefined values afterwards.
+ * The workgroups of an epoch kernel wait for each other, so they must all be resident at once: the
+ * library sizes the grid for that and refuses the launch (ZIPML_ELAUNCH) if the device cannot hold
+ * it, but kernels of other streams that occupy the compute units at the same time can still keep
+ * workgroups out -- two epoch calls on different streams of one device must not overlap; if they do,
+ * the waits give up (ZIPML_ETIMEOUT) rather than hang. */
 int zipml_sgd_epoch(void *stream, const void *packed1_dev, const void *packed2_dev,
                     const float *levels_dev, const uint16_t *grid_idx_dev, float grid_lo,
                     float grid_step, int grid_max, const float *b_dev, int64_t n, int64_t d,
@@ -313,7 +318,11 @@ int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t 
                                             the sums travel through tagged stores and reducer
                                             workgroups instead of atomics (default 32768; 0: wherever
                                             the loop can; a huge value: never)                     */
-#define ZIPML_KNOB_COUNT            11
+#define ZIPML_KNOB_COOPERATIVE_LAUNCH 11 /* 1: the epoch kernels go through the runtime's cooperative
+                                            launch (it checks that the grid can be resident, as the
+                                            library does itself, and queues such launches apart from
+                                            the stream's other work: some 20 us per call)          */
+#define ZIPML_KNOB_COUNT            12
 int zipml_debug_set(int knob, int64_t value);
 
 #ifdef __cplusplus

@@ -332,7 +332,6 @@ __device__ __forceinline__ void sgd_steps(const SgdArgs &a, const Lds &L)
     // ---- the units this thread owns, the same in every step
     // dot pass:      unit k = (sample d_i[k] of the batch, owned feature group d_g[k])
     // gradient pass: unit k = (owned feature g_c, sample group g_rg[k] of the batch)
-    const int n_dot = B * ngroups;
     int d_i[UPT], d_g[UPT];
 #pragma unroll
     for (int k = 0; k < UPT; ++k) {
@@ -1090,6 +1089,26 @@ static int device_limits(int &cus, int &lds)
     return ZIPML_OK;
 }
 
+// Launch of a persistent kernel, all of whose workgroups wait for each other: it is refused unless
+// the whole grid can be resident at once (workgroups per compute unit, from the kernel's registers
+// and LDS, times compute units).  The runtime's cooperative launch makes the same check and, on
+// top, sends such launches through a queue of their own, which costs some 20 us per call (measured:
+// gaps of 14 and 11 us around the kernel instead of 3 to 5) -- a fifth of a step over 65,536 samples.
+// An ordinary launch is the default; ZIPML_KNOB_COOPERATIVE_LAUNCH = 1 brings the other back.  Either
+// way residency also needs the device's compute units to be free of other streams' kernels; every
+// device-wide wait of these kernels is bounded, so the worst case is ZIPML_ETIMEOUT, not a hang.
+static int launch_resident(const void *kern, int grid, void **params, size_t shmem, hipStream_t s)
+{
+    if (knob(ZIPML_KNOB_COOPERATIVE_LAUNCH) == 1)
+        return HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(grid), dim3(kThreads), params, (unsigned)shmem, s))
+                   ? ZIPML_ELAUNCH : ZIPML_OK;
+    int cus = 0, lds = 0, per_cu = 0;
+    if (int rc = device_limits(cus, lds)) return rc;
+    if (HIP_FAILED(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, shmem))) return ZIPML_ELAUNCH;
+    if ((int64_t)per_cu * cus < grid) return ZIPML_ELAUNCH;
+    return HIP_FAILED(hipLaunchKernel(kern, dim3(grid), dim3(kThreads), params, shmem, s)) ? ZIPML_ELAUNCH : ZIPML_OK;
+}
+
 static size_t up16(size_t v) { return (v + 15) & ~(size_t)15; }
 // the exchange words of one chunk (sums of `pairs` code pairs, two side words) fit a row
 static bool NCwords_ok(int pairs, int64_t micro, int xrow) { return (int64_t)pairs * micro + 2 <= xrow; }
@@ -1223,10 +1242,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         a.seg_first = 0;
         a.seg_last = 3;
         void *params[] = {&a};
-        if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(a.W * a.R), dim3(kThreads), params,
-                                                  (unsigned)p.shmem, s)))
-            return ZIPML_ELAUNCH;
-        return ZIPML_OK;
+        return launch_resident(kern, a.W * a.R, params, p.shmem, s);
     }
     // stepwise: every segment of every step is its own launch; kernel boundaries replace barriers
     const int64_t first = a.step0, count = a.nsteps;
@@ -1316,9 +1332,7 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
                        const_cast<float *>(r.mid), nfeat, BITS == 8 ? 128.0f : 0.0f);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     void *params[] = {&r};
-    if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(wgs), dim3(kThreads), params, (unsigned)lds_bytes, s)))
-        return ZIPML_ELAUNCH;
-    return ZIPML_OK;
+    return launch_resident(kern, wgs, params, lds_bytes, s);
 }
 
 static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_dev,
@@ -1686,9 +1700,7 @@ extern "C" int zipml_sgd_epoch_compact(void *stream, const void *compact_dev, co
                        NKB * 64, 128.0f);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
     void *params[] = {&r};
-    if (HIP_FAILED(hipLaunchCooperativeKernel(kern, dim3(wgs), dim3(kThreads), params, (unsigned)shmem, s)))
-        return ZIPML_ELAUNCH;
-    return ZIPML_OK;
+    return launch_resident(kern, wgs, params, shmem, s);
 }
 
 extern "C" int zipml_debug_step(void *stream, const void *packed1_dev, const void *packed2_dev,

@@ -438,6 +438,36 @@ def test_fp32_epochs_are_bit_reproducible(name, factory, kw, lr):
     assert np.isfinite(runs[0].view(np.float32)).all() and np.any(runs[0] != 0)
 
 
+@pytest.mark.parametrize("name,factory,kw,lr,exact", [
+    ("dense8_small", synth.dense8, dict(n=8192, d=288, batch=256), 1e-3, True),          # feature owners
+    ("dense8_replicas", synth.dense8, dict(n=16384, d=288, batch=8192), 0.05, True),     # replicas of them
+    ("dense8_rows", synth.dense8, dict(n=32768, d=288, batch=16384), 0.05, False),       # sample owners
+])
+def test_ordinary_and_cooperative_launch_agree(name, factory, kw, lr, exact, knobs):
+    """The epoch kernels are launched as ordinary kernels after the library's own check that the
+    grid can be resident; the runtime's cooperative launch stays available behind a knob.  Same
+    kernels, same arguments: the models must agree (bit for bit where the sums are integer sums)."""
+    say("launch kinds", name)
+    w = factory(**kw)
+    A, b = w.full()
+    p = GpuProblem(A, b, w.bits, w.batch)
+    p.set_levels(_levels_for(w, A))
+    p.quantize(3, 0)
+    res = []
+    for coop in (-1, 1):
+        knobs(zipml.KNOB_COOPERATIVE_LAUNCH, coop)
+        x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        for _ep in range(2):
+            p.epoch(x, lr)
+        res.append(x.cpu().numpy().copy())
+    knobs(zipml.KNOB_COOPERATIVE_LAUNCH, -1)
+    assert np.isfinite(res[0]).all() and np.any(res[0] != 0)
+    if exact:
+        assert np.array_equal(res[0].view(np.uint32), res[1].view(np.uint32))
+    else:
+        assert np.max(np.abs(res[0] - res[1])) <= 1e-6 * np.max(np.abs(res[0]))
+
+
 @pytest.mark.parametrize("name,factory,kw,batch,lr,l2", [
     ("dense8_b16384", synth.dense8, dict(n=32768, d=288), 16384, 0.05, 0.0),     # odd number of feature groups
     ("dense8_wide_full_batch", synth.dense8, dict(n=16384, d=1100), 16384, 0.02, 0.0),
