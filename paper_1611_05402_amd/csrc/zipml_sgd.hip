@@ -988,7 +988,11 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
 //   bound[0] = sum_j maxabs(L_j) |x_j|,   bound[1] = sum_j maxabs(L_j)^2,
 //   bound[2] = max_j delta_j |x_j|,       bound[3] = max_j delta_j maxabs(L_j),
 // (delta_j: spacing of evenly spaced levels) in fp64 with a fixed order.
-__global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync, uint64_t *acc,
+// (1024 threads: a block's share of the level tables is then two loads per thread, all in flight
+// together; with 256 the launch took 10 us on 2,048 x 256 levels, now 5.5.  The bounds' block reads a
+// cache line per feature through one compute unit: 19 us at 16,384 features, of an epoch of 3.3 ms.)
+constexpr int kPrepThreads = 1024;
+__global__ __launch_bounds__(kPrepThreads) void k_sgd_prepare(int *status, uint32_t *sync, uint64_t *acc,
                                                       int words, int clear_status,
                                                       const float *__restrict__ levels,
                                                       const float *__restrict__ x, int d, int K,
@@ -998,7 +1002,7 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
                                                       uint64_t *slots = nullptr, int nslots = 0,
                                                       uint64_t *tagged = nullptr, int64_t ntagged = 0)
 {
-    __shared__ double sb[256], sl[256], sy[256], sm[256];
+    __shared__ double sb[kPrepThreads], sl[kPrepThreads], sy[kPrepThreads], sm[kPrepThreads];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) { sync[0] = 0u; if (clear_status) status[0] = 0; }
     for (int e = i; e < words; e += gridDim.x * blockDim.x) acc[e] = 0ull;
@@ -1025,7 +1029,7 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
         const int64_t per = (total + Workspace::kEvenBlocks - 1) / Workspace::kEvenBlocks;
         const int64_t s_end = (blockIdx.x + 1) * per < total ? (blockIdx.x + 1) * per : total;
         int ok = 1;
-        for (int64_t sg = blockIdx.x * per + threadIdx.x; sg < s_end; sg += 256) {
+        for (int64_t sg = blockIdx.x * per + threadIdx.x; sg < s_end; sg += kPrepThreads) {
             const int64_t j = sg / spf;
             const int c0 = (int)(sg % spf) * 4;
             const float *row = levels + j * K;
@@ -1042,7 +1046,7 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
     // one more block takes the magnitude bounds (the sample-owner kernel takes its scales from the data)
     if (blockIdx.x != Workspace::kEvenBlocks || !bound) return;
     double pb = 0.0, pl = 0.0, py = 0.0, pm = 0.0;
-    for (int j = threadIdx.x; j < d; j += 256) {
+    for (int j = threadIdx.x; j < d; j += kPrepThreads) {
         const double lo = (double)levels[(size_t)j * K], hi = (double)levels[(size_t)j * K + K - 1];
         const double m = fmax(fabs(lo), fabs(hi));
         const double delta = (double)(float)((hi - lo) / (double)(K - 1));
@@ -1056,7 +1060,7 @@ __global__ __launch_bounds__(256) void k_sgd_prepare(int *status, uint32_t *sync
     sy[threadIdx.x] = py;
     sm[threadIdx.x] = pm;
     __syncthreads();
-    for (int stride = 128; stride > 0; stride >>= 1) {
+    for (int stride = kPrepThreads / 2; stride > 0; stride >>= 1) {
         if ((int)threadIdx.x < stride) {
             sb[threadIdx.x] += sb[threadIdx.x + stride];
             sl[threadIdx.x] += sl[threadIdx.x + stride];
@@ -1229,7 +1233,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
     const int words = a.R * Workspace::kAccBuffers * a.acc_words + (a.R > 1 ? 2 * (int)Workspace::kGradWords : 0);
     const int K = 1 << BITS;
     double *bound = const_cast<double *>(a.bound);
-    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, a.status, a.sync,
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(kPrepThreads), 0, s, a.status, a.sync,
                        a.acc, words, 1, a.levels, a.x, a.d, K, bound,
                        a.mfma ? const_cast<int *>(a.even) : nullptr, (float *)nullptr, (float *)nullptr, 0, 0.0f,
                        INT && !stepwise ? reinterpret_cast<uint64_t *>(a.nrm) : (uint64_t *)nullptr,
@@ -1253,7 +1257,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         // the exchange buffer that step t uses was last used by step t-4: clear it; the magnitude
         // bounds are taken from the model as it stands before this step
         uint64_t *acct = a.acc + (size_t)(t & 3) * a.acc_words;
-        hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, a.status,
+        hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(kPrepThreads), 0, s, a.status,
                            a.sync, acct, a.acc_words, 0, a.levels, a.x, a.d, K, bound, nullptr);
         for (int seg = 0; seg <= 3; ++seg) {
             if (seg == 0 && a.model_bits == 0) continue;
@@ -1327,7 +1331,7 @@ static int launch_rows(hipStream_t s, RowsArgs &r, const float *levels, int wgs,
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)))
         return ZIPML_ELAUNCH;
     // status word, barrier counter, evenly-spaced check (no exchange words to clear)
-    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, r.status, r.sync,
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(kPrepThreads), 0, s, r.status, r.sync,
                        acc, 0, 1, levels, r.x, r.d, K, (double *)nullptr, even, const_cast<float *>(r.dl),
                        const_cast<float *>(r.mid), nfeat, BITS == 8 ? 128.0f : 0.0f);
     if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
@@ -1694,7 +1698,7 @@ extern "C" int zipml_sgd_epoch_compact(void *stream, const void *compact_dev, co
     const void *kern = NKB <= 2 * kWaves ? (const void *)k_sgd_rows_compact<2> : (const void *)k_sgd_rows_compact<4>;
     if (HIP_FAILED(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
         return ZIPML_ELAUNCH;
-    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(256), 0, s, r.status, r.sync,
+    hipLaunchKernelGGL(k_sgd_prepare, dim3(Workspace::kEvenBlocks + 1), dim3(kPrepThreads), 0, s, r.status, r.sync,
                        (uint64_t *)(wsb + Workspace::kAcc), 0, 1, levels_dev, r.x, r.d, 256, (double *)nullptr,
                        (int *)(wsb + Workspace::kEven), const_cast<float *>(r.dl), const_cast<float *>(r.mid),
                        NKB * 64, 128.0f);
