@@ -446,6 +446,22 @@ def dense_extras(P, args, torch, zipml, timed):
         q2 = torch.randint(0, 256, (zipml.packed_bytes(n8, d, bits),), dtype=torch.uint8, device=dev)
         sweep_point(n8, q1, q2, torch.randn(n8, device=dev), n8)
         del q1, q2
+    # What a device-wide exchange costs: the same epoch with minibatches of 4 and 32 samples -- a
+    # step then moves 16 or 128 KiB of codes, and what is left of it is one exchange of the partial
+    # sums between the workgroups (an atomic add, a wait, a poll) plus the fixed work around it.
+    exchange = []
+    if not args.batch:
+        for bsmall in (4, 32):
+            xs = torch.zeros(d, dtype=torch.float32, device=dev)
+            wss = torch.zeros(zipml.workspace_bytes(n, d, bits, bsmall), dtype=torch.uint8, device=dev)
+            try:
+                ms = timed(lambda: zipml.sgd_epoch(P.p1, P.p2, P.lev, P.b, n, d, bits, xs, bsmall, w.lr, wss), 3)
+                st = zipml.sgd_status(wss)
+                exchange.append({"batch": bsmall, "steps_per_epoch": n // bsmall, "us_per_step": ms * 1e3 / (n // bsmall),
+                                 "status": zipml.strerror(st) if st else "ok"})
+            except zipml.ZipmlError as e:
+                exchange.append({"batch": bsmall, "error": str(e)})
+            del wss
     compact = []
     if not args.batch and bits == 8 and 512 < d <= 2048 and n >= 16384:
         # Sec. 2.2, compact storage: the full-batch epoch reading base + 1 bit per copy (10 bits per
@@ -510,8 +526,8 @@ def dense_extras(P, args, torch, zipml, timed):
                 zipml.debug_set(zipml.KNOB_ROWS_ITEM_BLOCKS, -1)
             two_bit.append(row)
             del q1, q2, bs, wss
-    return {"other_ms": other, "batch_sweep": sweep, "compact_record_epoch": compact,
-            "two_bit_large_minibatch": two_bit}
+    return {"other_ms": other, "batch_sweep": sweep, "step_with_next_to_no_data": exchange,
+            "compact_record_epoch": compact, "two_bit_large_minibatch": two_bit}
 
 
 if __name__ == "__main__":
