@@ -75,6 +75,37 @@ __device__ __forceinline__ void unit_set(uint32_t (&w)[BITS], int k, uint32_t co
     w[wi] |= code << sh;
     if (sh + BITS > 32) w[wi + 1] |= code >> (32 - sh);
 }
+// (the same on an array of N dwords that holds fewer than 32 codes of `bits` bits)
+template <int N>
+__device__ __forceinline__ void unit_set(uint32_t (&w)[N], int k, int bits, uint32_t code)
+{
+    const int bit = k * bits, wi = bit >> 5, sh = bit & 31;
+    w[wi] |= code << sh;
+    if (sh + bits > 32) w[wi + 1] |= code >> (32 - sh);
+}
+
+// A unit from one of its halves: `half` holds sixteen codes as a bit string of 16 BITS bits from bit 0
+// (built with unit_set on an array of kHalfDwords dwords, every index a constant); the result is that
+// string at bit 0 (h == 0) or at bit 16 BITS (h == 1: BITS / 2 dwords further on, and for odd BITS
+// another 16 bits), zeros elsewhere, with every register index still a constant.
+template <int BITS> constexpr int kHalfDwords = (16 * BITS + 31) / 32;
+template <int BITS>
+__device__ __forceinline__ void place_half(uint32_t (&unit)[BITS], const uint32_t (&half)[kHalfDwords<BITS>], int h)
+{
+    constexpr int HB = kHalfDwords<BITS>, OFF = BITS / 2;
+#pragma unroll
+    for (int q = 0; q < BITS; ++q) {
+        const uint32_t lo = q < HB ? half[q] : 0u;
+        uint32_t hi = 0u;
+        if constexpr (BITS % 2 == 0) {
+            if (q >= OFF && q - OFF < HB) hi = half[q - OFF < HB ? q - OFF : 0];
+        } else {
+            if (q >= OFF && q - OFF < HB) hi = half[q - OFF < HB ? q - OFF : 0] << 16;
+            if (q >= OFF + 1 && q - OFF - 1 < HB) hi |= half[q - OFF - 1 < HB ? q - OFF - 1 : 0] >> 16;
+        }
+        unit[q] = h ? hi : lo;
+    }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Device-scope (all XCDs) access to data that other workgroups write during the same kernel.

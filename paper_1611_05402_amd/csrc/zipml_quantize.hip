@@ -206,38 +206,45 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
         }
         __syncthreads();
 
-        // ---- phase 2: pack 32 codes per unit and store
+        // ---- phase 2: pack 32 codes per unit and store.  Two neighbouring lanes share a unit, sixteen
+        // codes each (with one lane per unit half the workgroup packed while the other half waited
+        // at the barrier); the halves are put together with a lane exchange and the even lane stores.
         const int64_t rg = row0 / 32 + rg_local;          // sample group in the whole matrix
-        if (tid < 64) {
-            // copy 2: one unit = sample r, feature group gq
-            const int r = tid & 31, gq = tid >> 5;
+        {
+            const bool second = tid >= 128;               // waves 0-1: copy 2, waves 2-3: copy 1
+            const int u = (tid & 127) >> 1, h = tid & 1;  // unit of the tile, half of the unit
+            const int gq = u >> 5, in = u & 31;           // feature group of the tile; sample (copy 2) or feature (copy 1) in it
             const int64_t g = col0 / 32 + gq;
-            if (g < d32) {
-                uint32_t unit[BITS];
+            uint32_t half[kHalfDwords<BITS>];
 #pragma unroll
-                for (int q = 0; q < BITS; ++q) unit[q] = 0;
+            for (int q = 0; q < kHalfDwords<BITS>; ++q) half[q] = 0;
+            if (!second) {
+                // copy 2: one unit = sample `in`, feature group gq; this lane's codes 16 h .. 16 h + 15
+                // are four words of the tile's row
 #pragma unroll
-                for (int k = 0; k < 32; ++k) {
-                    const uint32_t w = c2w[r * kLdsRow + gq * 8 + (k >> 2)];
-                    unit_set<BITS>(unit, k, (w >> (8 * (k & 3))) & 0xFFu);
+                for (int kk = 0; kk < 16; ++kk) {
+                    const uint32_t w = c2w[in * kLdsRow + gq * 8 + 4 * h + (kk >> 2)];
+                    unit_set<kHalfDwords<BITS>>(half, kk, BITS, (w >> (8 * (kk & 3))) & 0xFFu);
                 }
-                const int64_t i = rg * 32 + r;
-                store_unit<BITS>(p2 + (g * nb64 * 64 + i) * BITS, unit);
+            } else {
+                // copy 1: one unit = feature u of the tile, the 32 samples of this group
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) {
+                    const uint32_t w = c1w[(16 * h + kk) * kLdsRow + (u >> 2)];
+                    unit_set<kHalfDwords<BITS>>(half, kk, BITS, (w >> (8 * (u & 3))) & 0xFFu);
+                }
             }
-        } else if (tid < 128) {
-            // copy 1: one unit = feature c, the 32 samples of this group
-            const int c = tid - 64, gq = c >> 5, cin = c & 31;
-            const int64_t g = col0 / 32 + gq;
-            if (g < d32) {
-                uint32_t unit[BITS];
+            uint32_t unit[BITS];
+            place_half<BITS>(unit, half, h);
 #pragma unroll
-                for (int q = 0; q < BITS; ++q) unit[q] = 0;
-#pragma unroll
-                for (int k = 0; k < 32; ++k) {
-                    const uint32_t w = c1w[k * kLdsRow + (c >> 2)];
-                    unit_set<BITS>(unit, k, (w >> (8 * (c & 3))) & 0xFFu);
+            for (int q = 0; q < BITS; ++q) unit[q] |= __shfl_xor(unit[q], 1, 64);
+            if (h == 0 && g < d32) {
+                if (!second) {
+                    const int64_t i = rg * 32 + in;
+                    store_unit<BITS>(p2 + (g * nb64 * 64 + i) * BITS, unit);
+                } else {
+                    store_unit<BITS>(p1 + ((g * n32 + rg) * 32 + in) * BITS, unit);
                 }
-                store_unit<BITS>(p1 + ((g * n32 + rg) * 32 + cin) * BITS, unit);
             }
         }
         __syncthreads();
