@@ -118,22 +118,27 @@ constexpr int kTileCols = 64;    // 2 feature groups per workgroup
 constexpr int kLdsRow = 17;      // dwords per LDS row of 64 code bytes (+1: conflict-free columns)
 
 // Level tables of the workgroup's 64 features live in LDS ([64][K] floats, staged once); the
-// workgroup then walks down its share of the sample groups, 32 samples x 64 features per round,
-// with the fp32 values of the next round requested before the current one is worked on.
-template <int BITS>
-__global__ __launch_bounds__(256) void k_quantize_pack(
+// workgroup then walks down its share of the sample groups, 32 samples x 64 features per round
+// and 256 threads, with the fp32 values of the next round requested before the current one is
+// worked on.  HALVES = 2: two such sets of 256 threads share the tables and take every other
+// sample group each -- at 8 bits the 64 KiB of tables leave room for two workgroups per compute
+// unit, and with 256 threads each that is two waves per SIMD to hide anything with.
+template <int BITS, int HALVES>
+__global__ __launch_bounds__(256 * HALVES) void k_quantize_pack(
     const float *__restrict__ A, int64_t n_rows, int64_t d, int64_t lda, int64_t row0,
     int64_t nb64, int64_t n32, int64_t d32, const float *__restrict__ levels, uint64_t seed,
     uint32_t epoch, uint32_t *__restrict__ p1, uint32_t *__restrict__ p2, int vec_ok,
     int64_t groups_per_block, int swapped)
 {
     extern __shared__ __align__(16) float tab[];          // [kTileCols][K]
-    __shared__ uint32_t c1w[32 * kLdsRow];
-    __shared__ uint32_t c2w[32 * kLdsRow];
+    __shared__ uint32_t c1w_all[HALVES][32 * kLdsRow];
+    __shared__ uint32_t c2w_all[HALVES][32 * kLdsRow];
     constexpr int K = 1 << BITS;
-    const int tid = threadIdx.x;
+    const int hw = HALVES == 1 ? 0 : (int)threadIdx.x >> 8;     // which set of 256 threads
+    const int tid = threadIdx.x & 255;                          // thread of the set
+    uint32_t *const c1w = c1w_all[hw], *const c2w = c2w_all[hw];
     const int64_t col0 = (int64_t)blockIdx.y * kTileCols;
-    for (int e = tid; e < kTileCols * K; e += 256) {
+    for (int e = threadIdx.x; e < kTileCols * K; e += 256 * HALVES) {
         const int64_t j = col0 + e / K;
         tab[e] = j < d ? levels[j * K + e % K] : 0.0f;
     }
@@ -173,17 +178,21 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
             }
         }
     };
+    // (both sets run the same number of rounds, for the barriers; a set without a group in the last
+    // round repeats the loads of the last group and stores nothing)
     float vcur[2][4], vnxt[2][4];
-    fetch(g_begin, vcur);
-    for (int64_t rg_local = g_begin; rg_local < g_end; ++rg_local) {
-        fetch(rg_local + 1, vnxt);
+    fetch(g_begin + hw, vcur);
+    for (int64_t rg_first = g_begin; rg_first < g_end; rg_first += HALVES) {
+        const int64_t rg_local = rg_first + hw;
+        const bool active = rg_local < g_end;
+        fetch(rg_local + HALVES, vnxt);
         // ---- phase 1: decide both codes of every element of the tile
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             const int r = pass * 16 + (tid >> 4);
             const int64_t i = rg_local * 32 + r;
             uint32_t w1 = 0, w2 = 0;
-            if (i < n_rows && col < d) {
+            if (active && i < n_rows && col < d) {
                 const uint64_t row = (uint64_t)(row0 + i);
                 // swapped: the feature-major array gets copy 2 (stream 2), the sample-major copy 1
                 const Philox4 r1 = philox_block(seed, epoch, row, (uint32_t)(col >> 2), swapped ? 2u : 1u);
@@ -238,7 +247,7 @@ __global__ __launch_bounds__(256) void k_quantize_pack(
             place_half<BITS>(unit, half, h);
 #pragma unroll
             for (int q = 0; q < BITS; ++q) unit[q] |= __shfl_xor(unit[q], 1, 64);
-            if (h == 0 && g < d32) {
+            if (active && h == 0 && g < d32) {
                 if (!second) {
                     const int64_t i = rg * 32 + in;
                     store_unit<BITS>(p2 + (g * nb64 * 64 + i) * BITS, unit);
@@ -379,11 +388,13 @@ static int launch_quantize(hipStream_t s, const float *A, int64_t n_rows, int64_
     if (col_blocks > 65535 || row_blocks > 0x7FFFFFFF) return ZIPML_EUNSUPPORTED;
     const int64_t per_block = (groups + row_blocks - 1) / row_blocks;
     const size_t shmem = (size_t)kTileCols * (1u << BITS) * sizeof(float);
-    if (HIP_FAILED(hipFuncSetAttribute((const void *)k_quantize_pack<BITS>,
+    // (two sets of threads per workgroup where the tables limit the workgroups per compute unit)
+    constexpr int kHalves = BITS >= 8 ? 2 : 1;
+    if (HIP_FAILED(hipFuncSetAttribute((const void *)k_quantize_pack<BITS, kHalves>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem)))
         return ZIPML_ELAUNCH;
     dim3 grid((unsigned)row_blocks, (unsigned)col_blocks);
-    hipLaunchKernelGGL(k_quantize_pack<BITS>, grid, dim3(256), shmem, s, A, n_rows, d, lda, row0,
+    hipLaunchKernelGGL((k_quantize_pack<BITS, kHalves>), grid, dim3(256 * kHalves), shmem, s, A, n_rows, d, lda, row0,
                        lay.nb64, lay.n32, lay.d32, levels, seed, epoch, p1, p2, vec_ok, per_block,
                        swapped);
     return hip_check(hipGetLastError());
