@@ -288,8 +288,9 @@ constexpr size_t kHistSlabBytes = (size_t)64 << 20;
 //   V(j, m) = sum over the points in [d_j, d_m) of (d_m - t)(t - d_j), from prefix moments.
 // The arithmetic is that of the host version below, operation by operation (prefix sums in index
 // order, the same expression for V, the smallest j on ties), so both give the same levels.
-// Thread tid takes the end points m = tid, tid + 256, ...; in step i of the inner loop all threads
-// read the same j, which LDS serves as a broadcast.
+// Thread tid takes the end points m = M - tid, M - 1023 + tid, M - 1024 - tid, ... (512 threads: the tables leave room
+// for two workgroups per compute unit, and with 256 threads each the vector units idled half the time);
+// in step i of the inner loop all threads of a wave read the same j, which LDS serves as a broadcast.
 // LDS: 6 arrays of M+1 doubles and the argmin table (s+1) x (M+1) uint16.
 __host__ __device__ inline size_t dp_lds_bytes(int M, int s)
 {
@@ -299,7 +300,8 @@ __host__ __device__ inline size_t dp_lds_bytes(int M, int s)
 // With sel / count (the greedy search below): the candidates of feature j are the count[j] + 1 bin
 // edges sel[j][0 .. count[j]] and hist holds the moments of the intervals between them; Mcap is
 // the largest number of intervals a feature can have (it sizes the tables).
-__global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hist,
+constexpr int kDpThreads = 512;
+__global__ __launch_bounds__(kDpThreads) void k_dp_levels(const double *__restrict__ hist,
                                                    const float *__restrict__ lo,
                                                    const float *__restrict__ hi, int64_t d, int Mgrid,
                                                    int s, float *__restrict__ levels,
@@ -309,7 +311,7 @@ __global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hi
                                                    const int *__restrict__ count, int Mcap)
 {
     extern __shared__ __align__(16) unsigned char dp_smem[];
-    const int K = s + 1, tid = threadIdx.x;
+    const int K = s + 1, tid = threadIdx.x, T = blockDim.x;    // (T <= kDpThreads: fewer threads for few candidates)
     const int Wcap = Mcap + 1;
     double *C = (double *)dp_smem, *S1 = C + Wcap, *S2 = S1 + Wcap, *edge = S2 + Wcap,
            *prev = edge + Wcap, *cur = prev + Wcap;
@@ -333,7 +335,7 @@ __global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hi
                 dst[m + 1] = acc;
             }
         }
-        for (int m = tid; m < W; m += 256) {
+        for (int m = tid; m < W; m += T) {
             edge[m] = (double)(cand ? (int)cand[m] : m) / (double)Mgrid;
             prev[m] = INF;
         }
@@ -342,13 +344,17 @@ __global__ __launch_bounds__(256) void k_dp_levels(const double *__restrict__ hi
             const double dj = edge[jj], dm = edge[m];
             return -(S2[m] - S2[jj]) + (dj + dm) * (S1[m] - S1[jj]) - dj * dm * (C[m] - C[jj]);
         };
-        for (int m = 1 + tid; m <= M; m += 256) {
+        for (int m = 1 + tid; m <= M; m += T) {
             prev[m] = V(0, m);
             arg[1 * W + m] = 0;
         }
         __syncthreads();
         for (int k = 2; k <= s; ++k) {
-            for (int m = tid; m < W; m += 256) {
+            // (end points in runs of T, every other run taken backwards: the work of an end point
+            // grows with m, and this way every thread's end points add up to about the same)
+            for (int e0 = 0; e0 < W; e0 += T) {
+                const int m = M - (((e0 / T) & 1) ? e0 + T - 1 - tid : e0 + tid);   // from M down
+                if (m < 0) continue;
                 double best = INF;
                 int bj = k - 1;
                 if (m >= k) {
@@ -694,7 +700,8 @@ extern "C" int zipml_levels(void *stream, const float *A_dev, int64_t n, int64_t
         if (HIP_FAILED(hipFuncSetAttribute((const void *)k_dp_levels,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dp_lds)))
             return ZIPML_ELAUNCH;
-        hipLaunchKernelGGL(k_dp_levels, dim3(blocks), dim3(256), dp_lds, s, hist_dev, lo_dev, hi_dev, d,
+        const int dp_threads = greedy ? std::min(kDpThreads, std::max(64, (int)round_up(Mcap + 1, 64))) : kDpThreads;
+        hipLaunchKernelGGL(k_dp_levels, dim3(blocks), dim3(dp_threads), dp_lds, s, hist_dev, lo_dev, hi_dev, d,
                            M, sI, levels_dev, grid_dev, objective_dev, (const uint16_t *)sel_dev,
                            (const int *)count_dev, greedy ? Mcap : M);
         if (HIP_FAILED(hipGetLastError())) return ZIPML_ELAUNCH;
