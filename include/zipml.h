@@ -322,7 +322,10 @@ int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t 
                                             launch (it checks that the grid can be resident, as the
                                             library does itself, and queues such launches apart from
                                             the stream's other work: some 20 us per call)          */
-#define ZIPML_KNOB_COUNT            12
+#define ZIPML_KNOB_REDUCER_WORKGROUPS 12 /* workgroups that only reduce the tagged partial sums, on
+                                            compute units the launch leaves idle (0: none; 100 + n: n
+                                            of them with pieces of four words instead of eight)   */
+#define ZIPML_KNOB_COUNT            13
 int zipml_debug_set(int knob, int64_t value);
 
 #ifdef __cplusplus

@@ -117,6 +117,8 @@ struct SgdArgs {
     float *gbuf;           // [d] gradient carried between launches (stepwise, grad_bits > 0)
     int xstore;            // 1: the matrix-core loop exchanges its sums through tagged stores
     int xrow;              // words per row of xpart / xres
+    int nred;              // workgroups behind the W owners that only reduce the tagged partial sums (0: the owners do)
+    int red_piece;         // exchange words per piece of theirs (8 or 4)
     uint64_t *xpart;       // [2][W][xrow] tagged partial sums, one row per workgroup
     uint64_t *xres;        // [2][xrow] tagged sums
     // debug outputs (may be null)
@@ -916,6 +918,12 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         // replicas or debug outputs, with the workgroup width and the exchange it was built for)
         if constexpr (!INT && FAST && kMfmaBits && !REP) {
             constexpr int kKB = 1 + ((SOLO - 1) & 1), kXM = (SOLO - 1) >> 1;
+            if constexpr (kXM == 1) {
+                if ((int)blockIdx.x >= a.W) {           // a workgroup that only reduces (a.nred > 0)
+                    if (affine_all && a.mfma) sgd_reducers<UPT>(a, L);
+                    return;
+                }
+            }
             if (affine_all && a.mfma) sgd_steps_mfma<BITS, UPT, kKB, 1, false, kXM>(a, L, L.mf);
             else if (affine) sgd_steps<BITS, kAffine, FAST, UPT>(a, L);
             else sgd_steps<BITS, kTable, FAST, UPT>(a, L);
@@ -1222,6 +1230,25 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
                                  : (const void *)k_sgd<BITS, false, true, U, false, 4>)
                 kern = p.upt == 1 ? ZIPML_SOLO(1) : p.upt == 2 ? ZIPML_SOLO(2) : ZIPML_SOLO(4);
 #undef ZIPML_SOLO
+                // idle compute units take the reducing of the tagged partial sums (sgd_reducers), where
+                // the loop really exchanges that way (all eight waves at work, as the kernel decides too)
+                int cus = 0, lds = 0;
+                if (int rc = device_limits(cus, lds)) return rc;
+                const bool all_waves = !(p.upt == 1 && a.B <= 256 && a.GQ <= 2);
+                const int npieces = ((int)a.B + 2 + 7) / 8;
+                if (a.xstore && all_waves && cus - a.W >= npieces) {
+                    // (a reducer per piece of eight words, or none: with fewer, a reducer takes its pieces
+                    // one after the other, and the owners do better themselves -- tomography shape,
+                    // us per step: none 6.57, 16 reducers 10.1, 32: 7.6, 64: 6.41, 65 = one per piece: 6.39;
+                    // pieces of four words on twice the reducers: 6.8)
+                    a.red_piece = 8;
+                    a.nred = npieces;
+                    // development override: 0 = none, n = that many (4 words per piece from 100 on: n - 100 of them)
+                    if (const long long v = knob(ZIPML_KNOB_REDUCER_WORKGROUPS); v >= 0) {
+                        a.red_piece = v >= 100 ? 4 : 8;
+                        a.nred = (int)std::min<long long>(v >= 100 ? v - 100 : v, cus - a.W);
+                    }
+                }
             }
         }
     }
@@ -1246,7 +1273,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         a.seg_first = 0;
         a.seg_last = 3;
         void *params[] = {&a};
-        return launch_resident(kern, a.W * a.R, params, p.shmem, s);
+        return launch_resident(kern, a.W * a.R + a.nred, params, p.shmem, s);
     }
     // stepwise: every segment of every step is its own launch; kernel boundaries replace barriers
     const int64_t first = a.step0, count = a.nsteps;

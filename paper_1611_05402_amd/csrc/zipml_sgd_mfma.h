@@ -466,7 +466,8 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
 #endif
 
         // ============ tagged-store exchange, second trip: this workgroup's pieces of the sums
-        if (xstore) {
+        // (unless the launch has workgroups that do nothing else: sgd_reducers below)
+        if (xstore && a.nred == 0) {
             int turn = 0;
             for (int pc = w; pc < npieces; pc += W, turn ^= 1) {
                 long long *const red64 = reinterpret_cast<long long *>(L.red) + turn * (kWaves * kPiece);   // [kWaves][kPiece], two in turn
@@ -793,6 +794,92 @@ __device__ __forceinline__ void sgd_steps_mfma(const SgdArgs &a, const Lds &L, u
     if (w == 0 && tid == 0)
         for (int k = 0; k < 12; ++k) ((long long *)(a.nrm + 2048))[k] = prof_[k];
 #endif
+}
+
+// Workgroups that only reduce (a.nred of them, behind the W workgroups that own features; plain
+// estimator, no replicas): when a launch leaves compute units idle, they take the second trip of the
+// exchange through tagged stores off the workgroups that own features -- whose polls of the rows
+// otherwise queue behind their own loads of packed codes in the compute unit's memory pipeline, and
+// which cannot start to reduce before their own dot pass is done.  Piece pc goes to reducer
+// pc mod nred.  Same words, same tags, same buffers as in sgd_steps_mfma; a reducer leaves step u
+// when it has stored its sums of step u, so it cannot run ahead of the owners (they need those
+// sums), and every wait is bounded like theirs.
+template <int UPT>
+__device__ __forceinline__ void sgd_reducers(const SgdArgs &a, const Lds &L)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int W = a.W, B = a.B, FT = 2 * a.GQ;
+    const int nw = (UPT == 1 && B <= 256 && FT <= 4) ? 4 : kWaves;
+    if (nw != kWaves) return;                           // (the owners then exchange through atomics)
+    const int rid = (int)blockIdx.x - W, nred = a.nred;
+    const int C = a.chunks;
+    const int64_t u_begin = a.step0 * C, u_end = (a.step0 + a.nsteps) * C;
+    const int nwords = B + 2, xrow = a.xrow;
+    // words per piece: eight, or four when there are reducers enough for pieces that small -- then
+    // every thread polls one word of one row (128 rows of owners)
+    const int piece = a.red_piece;
+    const int npieces = (nwords + piece - 1) / piece;
+    bool dead = false;
+    int64_t t = a.step0;
+    int chunk = 0;
+    for (int64_t u = u_begin; u < u_end; ++u) {
+        const bool side_step = chunk == 0 && (t % kRefresh) == 0;
+        const uint32_t xtag = ((uint32_t)(u + 1) & 0x7FFFu) | 0x8000u;
+        const uint64_t *const xpart = a.xpart + (size_t)(u & 1) * ((size_t)W * xrow);
+        uint64_t *const xres = a.xpart + (size_t)2 * W * xrow + (size_t)(u & 1) * xrow;
+        int turn = 0;
+        for (int pc = rid; pc < npieces; pc += nred, turn ^= 1) {
+            long long *const red64 = reinterpret_cast<long long *>(L.red) + turn * (kWaves * kPiece);   // (piece <= kPiece)
+            const int sidx = pc * piece + (tid & (piece - 1));
+            const bool valid = sidx < B || (side_step && sidx < nwords);
+            // this thread's word in up to four rows (at most 256 owners, at least 64 threads per word):
+            // all requested at once, and only those asked again that have not arrived
+            long long sum = 0;
+            if (valid) {
+                const int stride = kThreads / piece;
+                const uint64_t *src[4];
+                uint64_t v[4];
+                bool need[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int row = tid / piece + k * stride;
+                    need[k] = row < W;
+                    src[k] = xpart + (size_t)(need[k] ? row : 0) * xrow + sidx;
+                    v[k] = need[k] ? load_dev(src[k]) : 0;
+                }
+                uint32_t spins = 0;
+#pragma unroll 1
+                while (!dead) {
+                    bool all = true;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) all = all && (!need[k] || (uint32_t)(v[k] >> 48) == xtag);
+                    if (all) break;
+                    if (++spins > a.spin_limit) {
+                        store_dev(a.status, (int)ZIPML_ETIMEOUT);
+                        dead = true;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);        // (nothing else to do here: leave the memory side to the owners)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (need[k] && (uint32_t)(v[k] >> 48) != xtag) v[k] = load_dev(src[k]);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (need[k]) sum += tagged_value(v[k]);
+            }
+            for (int sh = piece; sh < kWave; sh <<= 1) sum += __shfl_xor(sum, sh, kWave);
+            if (lane < piece) red64[wave * piece + lane] = sum;
+            lds_barrier();
+            if (tid < piece) {
+                long long tot = 0;
+#pragma unroll
+                for (int q = 0; q < kWaves; ++q) tot += red64[q * piece + tid];
+                if (valid) store_dev(xres + sidx, tag_word(xtag, tot));
+            }
+        }
+        if (chunk == C - 1) { chunk = 0; ++t; } else { ++chunk; }
+    }
 }
 
 }  // namespace zipml

@@ -581,8 +581,13 @@ def test_exchange_through_tagged_stores(name, factory, kw, lr, avg, knobs):
         zipml.quantize_swapped(p.A, w.n, w.d, w.d, 0, w.n, p.levels, w.bits, 8, 0, p1s, p2s)
     c1, c2 = oracle.quantize(A, L, w.bits, 8, 0)
     res = []
-    for xmin in (1 << 40, 0):
+    # (exchange through atomics; through tagged stores with the workgroups the library adds to do the
+    # reducing on idle compute units -- a launch of the plain estimator without replicas gets them --;
+    # with the owners of the features reducing themselves; with three such workgroups, which take
+    # their pieces one after the other; with pieces of four words)
+    for xmin, reducers in ((1 << 40, -1), (0, -1), (0, 0), (0, 3), (0, 104)):
         knobs(zipml.KNOB_STORE_EXCHANGE_MIN, xmin)
+        knobs(zipml.KNOB_REDUCER_WORKGROUPS, reducers)
         x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
         for ep in range(2):
             if avg:
@@ -591,10 +596,12 @@ def test_exchange_through_tagged_stores(name, factory, kw, lr, avg, knobs):
             else:
                 p.epoch(x, lr)
         res.append(x.cpu().numpy())
+    knobs(zipml.KNOB_REDUCER_WORKGROUPS, -1)
     x_ref = np.zeros(w.d, np.float32)
     for ep in range(2):
         x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, lr, symmetric=avg)
-    assert np.array_equal(res[0].view(np.uint32), res[1].view(np.uint32))
+    for r in res[1:]:
+        assert np.array_equal(res[0].view(np.uint32), r.view(np.uint32))
     assert rel_l2(res[1], x_ref) <= TOL and max_abs_ok(res[1], x_ref, TOL)
 
 
