@@ -325,7 +325,9 @@ int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t 
 #define ZIPML_KNOB_REDUCER_WORKGROUPS 12 /* workgroups that only reduce the tagged partial sums, on
                                             compute units the launch leaves idle (0: none; 100 + n: n
                                             of them with pieces of four words instead of eight)   */
-#define ZIPML_KNOB_COUNT            13
+#define ZIPML_KNOB_PREFETCH_WORKGROUPS 13 /* workgroups that only read the packed codes of a later chunk
+                                            into the cache, on compute units still idle (0: none)  */
+#define ZIPML_KNOB_COUNT            14
 int zipml_debug_set(int knob, int64_t value);
 
 #ifdef __cplusplus

@@ -119,6 +119,7 @@ struct SgdArgs {
     int xrow;              // words per row of xpart / xres
     int nred;              // workgroups behind the W owners that only reduce the tagged partial sums (0: the owners do)
     int red_piece;         // exchange words per piece of theirs (8 or 4)
+    int npref;             // workgroups behind those that only read the packed codes of a later chunk into the cache
     uint64_t *xpart;       // [2][W][xrow] tagged partial sums, one row per workgroup
     uint64_t *xres;        // [2][xrow] tagged sums
     // debug outputs (may be null)
@@ -919,6 +920,10 @@ __global__ __launch_bounds__(kThreads) void k_sgd(SgdArgs a)
         if constexpr (!INT && FAST && kMfmaBits && !REP) {
             constexpr int kKB = 1 + ((SOLO - 1) & 1), kXM = (SOLO - 1) >> 1;
             if constexpr (kXM == 1) {
+                if ((int)blockIdx.x >= a.W + a.nred) {  // a workgroup that only prefetches (a.npref > 0)
+                    if (affine_all && a.mfma) sgd_prefetchers<BITS>(a);
+                    return;
+                }
                 if ((int)blockIdx.x >= a.W) {           // a workgroup that only reduces (a.nred > 0)
                     if (affine_all && a.mfma) sgd_reducers<UPT>(a, L);
                     return;
@@ -1248,6 +1253,10 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
                         a.red_piece = v >= 100 ? 4 : 8;
                         a.nred = (int)std::min<long long>(v >= 100 ? v - 100 : v, cus - a.W);
                     }
+                    // what is idle even then reads ahead (sgd_prefetchers); 16-byte reads of whole segments
+                    const int idle = cus - a.W - a.nred;
+                    if (a.nred > 0 && idle >= 16 && ((int64_t)a.B * BITS * 4) % 16 == 0) a.npref = std::min(idle, 64);
+                    if (const long long v = knob(ZIPML_KNOB_PREFETCH_WORKGROUPS); v >= 0) a.npref = a.nred > 0 ? (int)std::min<long long>(v, idle) : 0;
                 }
             }
         }
@@ -1273,7 +1282,7 @@ static int launch_sgd(hipStream_t s, SgdArgs &a, const Plan &p, bool stepwise)
         a.seg_first = 0;
         a.seg_last = 3;
         void *params[] = {&a};
-        return launch_resident(kern, a.W * a.R + a.nred, params, p.shmem, s);
+        return launch_resident(kern, a.W * a.R + a.nred + a.npref, params, p.shmem, s);
     }
     // stepwise: every segment of every step is its own launch; kernel boundaries replace barriers
     const int64_t first = a.step0, count = a.nsteps;

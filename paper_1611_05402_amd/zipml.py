@@ -125,7 +125,7 @@ def _stream(stream=None):
 
 (KNOB_TARGET_WORKGROUPS, KNOB_NO_MATRIX_CORES, KNOB_CHUNK_SAMPLES, KNOB_MAX_REPLICAS, KNOB_ROWS_MIN_BATCH,
  KNOB_ROWS_ITEM_BLOCKS, KNOB_ROWS_WORKGROUPS, KNOB_SPIN_LIMIT, KNOB_HOST_DP, KNOB_HIST_FEATURES,
- KNOB_STORE_EXCHANGE_MIN, KNOB_COOPERATIVE_LAUNCH, KNOB_REDUCER_WORKGROUPS) = range(13)
+ KNOB_STORE_EXCHANGE_MIN, KNOB_COOPERATIVE_LAUNCH, KNOB_REDUCER_WORKGROUPS, KNOB_PREFETCH_WORKGROUPS) = range(14)
 
 
 def debug_set(knob: int, value: int) -> None:

@@ -159,7 +159,7 @@ def test_development_knobs_are_validated(lib):
     assert lib.zipml_debug_set(zipml.KNOB_SPIN_LIMIT, 5) == zipml.OK
     assert lib.zipml_debug_set(zipml.KNOB_SPIN_LIMIT, -1) == zipml.OK
     assert lib.zipml_debug_set(-1, 0) == zipml.EINVAL
-    assert lib.zipml_debug_set(13, 0) == zipml.EINVAL
+    assert lib.zipml_debug_set(14, 0) == zipml.EINVAL
     assert lib.zipml_debug_set(zipml.KNOB_HOST_DP, -2) == zipml.EINVAL
     # and the product reads no environment variable
     import glob

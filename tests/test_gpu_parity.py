@@ -585,9 +585,11 @@ def test_exchange_through_tagged_stores(name, factory, kw, lr, avg, knobs):
     # reducing on idle compute units -- a launch of the plain estimator without replicas gets them --;
     # with the owners of the features reducing themselves; with three such workgroups, which take
     # their pieces one after the other; with pieces of four words)
-    for xmin, reducers in ((1 << 40, -1), (0, -1), (0, 0), (0, 3), (0, 104)):
+    # (and with none or five of the workgroups that read the next chunks' codes ahead on what is idle then)
+    for xmin, reducers, readers in ((1 << 40, -1, -1), (0, -1, -1), (0, 0, -1), (0, 3, 5), (0, 104, 0), (0, -1, 0)):
         knobs(zipml.KNOB_STORE_EXCHANGE_MIN, xmin)
         knobs(zipml.KNOB_REDUCER_WORKGROUPS, reducers)
+        knobs(zipml.KNOB_PREFETCH_WORKGROUPS, readers)
         x = torch.zeros(w.d, dtype=torch.float32, device=DEV)
         for ep in range(2):
             if avg:
@@ -597,6 +599,7 @@ def test_exchange_through_tagged_stores(name, factory, kw, lr, avg, knobs):
                 p.epoch(x, lr)
         res.append(x.cpu().numpy())
     knobs(zipml.KNOB_REDUCER_WORKGROUPS, -1)
+    knobs(zipml.KNOB_PREFETCH_WORKGROUPS, -1)
     x_ref = np.zeros(w.d, np.float32)
     for ep in range(2):
         x_ref = oracle.sgd_epoch(c1, c2, L, b, w.bits, x_ref, w.batch, lr, symmetric=avg)
