@@ -56,10 +56,12 @@ def parse():
     return ap.parse_args()
 
 
-def recorded_traffic(workload, batch):
+def recorded_traffic(workload, batch, note=False):
     """HBM bytes per epoch launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), as
-    recorded in the text summary under profiles/ for this workload; None if there is none."""
+    recorded in the text summary under profiles/ for this workload; None if there is none.
+    note=True: the remark recorded with it (what the counters include), or None."""
     path = os.path.join(ROOT, "profiles", f"sgd_epoch_{workload}_hbm_traffic.txt")
+    value, remark = None, None
     try:
         with open(path) as f:
             for line in f:
@@ -67,10 +69,12 @@ def recorded_traffic(workload, batch):
                     fields = line.split()
                     if len(fields) >= 4 and fields[2] == "batch" and int(fields[3]) != batch:
                         return None
-                    return float(fields[1])
+                    value = float(fields[1])
+                elif line.startswith("traffic_note:"):
+                    remark = line[len("traffic_note:"):].strip()
     except OSError:
         pass
-    return None
+    return remark if note else value
 
 
 class Problem:
@@ -312,6 +316,7 @@ def main():
         res = run_epochs(P, args, torch, zipml)
         res["frac_of_measured_stream_read"] = res["packed_GBps"] / read_ceiling
         res["hbm_traffic_bytes_per_epoch"] = recorded_traffic(name, P.w.batch)
+        res["hbm_traffic_note"] = recorded_traffic(name, P.w.batch, note=True)
         results.append(res)
         if name == headline and not args.no_cpu_baseline:
             baseline = cpu_baseline(P, args.cpu_seconds, threads)
@@ -344,6 +349,7 @@ def main():
         "packed_GBps": head["packed_GBps"],
         "roofline": {"bound": "hbm", "achieved": head["packed_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["frac_hbm_peak"], "traffic": head["hbm_traffic_bytes_per_epoch"],
+                     "traffic_note": head.get("hbm_traffic_note"),
                      "kernel": f"k_sgd<{head['bits']}> (persistent epoch kernel, one launch per epoch)",
                      "kernel_ms": head["ms_per_epoch"],
                      "us_per_minibatch_step": head["us_per_minibatch_step"],
