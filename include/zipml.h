@@ -316,8 +316,9 @@ int zipml_debug_stream(void *stream, const void *src_dev, void *dst_dev, size_t 
 #define ZIPML_KNOB_HIST_FEATURES     9  /* features per workgroup of the bin-moment kernel              */
 #define ZIPML_KNOB_STORE_EXCHANGE_MIN 10 /* smallest (workgroups x samples of one exchange) from which
                                             the sums travel through tagged stores and reducer
-                                            workgroups instead of atomics (default 32768; 0: wherever
-                                            the loop can; a huge value: never)                     */
+                                            workgroups instead of atomics (0: wherever the loop can; a
+                                            huge value: never; by itself the library asks for 32768
+                                            and at least 128 workgroups)                           */
 #define ZIPML_KNOB_COOPERATIVE_LAUNCH 11 /* 1: the epoch kernels go through the runtime's cooperative
                                             launch (it checks that the grid can be resident, as the
                                             library does itself, and queues such launches apart from

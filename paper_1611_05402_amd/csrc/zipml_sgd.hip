@@ -1602,11 +1602,16 @@ static int run_sgd(void *stream, const void *packed1_dev, const void *packed2_de
     // results of their own (the plain estimator only), sized for their chunk, where the room that
     // zipml_workspace_bytes provides for one launch of this minibatch holds them all.
     {
+        // (by itself: from 128 workgroups and 32,768 workgroups x samples on.  What the atomics cost
+        // grows with the workgroups that add to one word: at the same 65,536 atomics per step 128
+        // workgroups x 512 samples take 9.1 us per step with atomics and 6.0 with tagged stores, 64 x
+        // 1,024 take 4.8 and 5.7.)
         long long xmin = knob(ZIPML_KNOB_STORE_EXCHANGE_MIN);
-        if (xmin < 0) xmin = 32768;
+        const bool automatic = xmin < 0;
+        if (automatic) xmin = 32768;
         const bool all_waves = !(p.upt == 1 && micro <= 256 && p.GQ <= 2);
         a.xstore = (a.mfma && (replicas == 1 || !avg) && all_waves && p.W > 1 && !production &&
-                    (long long)p.W * micro >= xmin) ? 1 : 0;
+                    (long long)p.W * micro >= xmin && (!automatic || p.W >= 128)) ? 1 : 0;
         a.xrow = (int)Workspace::xchg_row_words(replicas > 1 ? micro : batch);
         a.xpart = (uint64_t *)(ws + Workspace::xchg_offset(d, batch));
         a.xres = a.xpart + (size_t)2 * p.W * a.xrow;
